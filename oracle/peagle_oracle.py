@@ -1,0 +1,273 @@
+"""fp64 CPU oracle for the parallel-drafting attention of the P-EAGLE drafter.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this module; it is
+used by ``tests/``, the smoke check and the ``cpu_baseline`` leg of the benchmark.  It
+shares no code with the HIP path and never reads a value produced by it.
+
+What is computed (paper, Sec. 3): a sequence of ``L`` tokens is expanded to ``T = L*K``
+positions, one per (anchor ``i``, prediction depth ``d``); depth ``d`` predicts the
+token ``d+1`` ahead.  Attention over the expanded sequence runs under the
+parallel-prediction mask (Sec. 3, second paragraph, and Sec. 3.2 "Challenge 2"):
+
+  * a row of depth ``d`` sees depths ``<= d`` only;
+  * in position coordinates ``p = i + d`` the row ``(p, d)`` depends on ``(p-1, d-1)``,
+    hence on the whole chain down to depth 1, i.e. in anchor coordinates on
+    ``(i, 1), ..., (i, d)`` (self included);
+  * depth-0 keys are the ordinary causal context: anchors ``j <= i``.
+
+Readings of points the paper leaves open are listed in the design notes of this
+repository; the ones that matter here: a row attends to itself and to ``(i, 0)``;
+no other anchor's keys at depth >= 1 are visible; the expanded sequence is stored
+depth-major, ``t = d*L + i``; query head ``h`` uses KV head ``h // (Hq/Hkv)`` (the
+drafter is a LLaMA-3 style decoder, Sec. 2); the log-sum-exp is natural-log and
+includes the softmax scale.
+
+Everything is plain dense fp64: an explicit boolean mask evaluated element by element
+from the predicate, ``numpy`` matmuls, max-subtracted softmax.  The only blocking is
+over query rows, to bound memory; there is no tiling, fusion or reordering.
+
+Pins (tests/test_oracle_pins.py): closed-form visible counts, causal reduction at
+depth 0 and at K=1 against an independent library routine, library autograd with an
+independently built mask, zero-query closed forms, finite differences, crop
+invariance, and the worked partition example of Sec. 3.2 / Fig. 4 for the segment
+assignment routine.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+from typing import Dict, Iterable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+__all__ = [
+    "visible",
+    "token_index",
+    "token_coords",
+    "element_mask",
+    "attn_forward",
+    "attn_backward",
+    "segment_rows",
+    "segment_keys",
+    "attn_step_partitioned",
+    "partition_assign",
+    "cod_position_count",
+]
+
+
+# --------------------------------------------------------------------------------------
+# index space and mask (Sec. 3: n x K positions; mask rule in the PARD paragraph and
+# the dependency rule of Sec. 3.2, Challenge 2)
+# --------------------------------------------------------------------------------------
+
+def visible(i: int, d: int, j: int, e: int) -> bool:
+    """May query (anchor i, depth d) attend to key (anchor j, depth e)?"""
+    if e == 0:
+        return j <= i
+    return j == i and 1 <= e <= d
+
+
+def token_index(i, d, L: int):
+    """Depth-major storage order of the expanded sequence (blocks G0 | G1 | ... of Fig. 3)."""
+    return d * L + i
+
+
+def token_coords(t, L: int):
+    """Inverse of :func:`token_index`: returns (anchor, depth)."""
+    return t % L, t // L
+
+
+def element_mask(L: int, K: int, rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None) -> np.ndarray:
+    """Boolean mask M[r, c] over expanded positions, evaluated element by element.
+
+    ``rows`` / ``cols`` are token indices (default: all ``T = L*K``).
+    """
+    T = L * K
+    rows = np.arange(T) if rows is None else np.asarray(rows)
+    cols = np.arange(T) if cols is None else np.asarray(cols)
+    i, d = token_coords(rows, L)
+    j, e = token_coords(cols, L)
+    i = i[:, None]
+    d = d[:, None]
+    j = j[None, :]
+    e = e[None, :]
+    depth0 = (e == 0) & (j <= i)
+    chain = (e >= 1) & (e <= d) & (j == i)
+    return depth0 | chain
+
+
+# --------------------------------------------------------------------------------------
+# dense masked attention, forward and backward
+# --------------------------------------------------------------------------------------
+
+def _row_blocks(rows: np.ndarray, block: int) -> Iterable[np.ndarray]:
+    for s in range(0, len(rows), block):
+        yield rows[s:s + block]
+
+
+def _kv_head(h: int, Hq: int, Hkv: int) -> int:
+    return h // (Hq // Hkv)
+
+
+def attn_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, L: int, K: int, scale: float,
+                 rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
+                 row_block: int = 1024, return_probs: bool = False):
+    """O = softmax(scale * Q K^T + mask) V and LSE = ln sum exp(scale * q.k) over visible keys.
+
+    q: [T, Hq, D]; k, v: [T, Hkv, D] (fp64).  ``rows``: token indices of the query rows
+    to compute (default all); ``cols``: token indices of the keys that are present
+    (default all) - used by the segment semantics of Sec. 3.2.
+
+    Returns O [len(rows), Hq, D], LSE [Hq, len(rows)] (and P [Hq, len(rows), len(cols)]
+    when ``return_probs``).
+    """
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert T == L * K and k.shape == v.shape and k.shape[0] == T and Hq % Hkv == 0
+    rows = np.arange(T) if rows is None else np.asarray(rows)
+    cols = np.arange(T) if cols is None else np.asarray(cols)
+    O = np.zeros((len(rows), Hq, D), dtype=np.float64)
+    LSE = np.zeros((Hq, len(rows)), dtype=np.float64)
+    P_all = np.zeros((Hq, len(rows), len(cols)), dtype=np.float64) if return_probs else None
+    pos = 0
+    for rb in _row_blocks(rows, row_block):
+        M = element_mask(L, K, rb, cols)
+        for h in range(Hq):
+            g = _kv_head(h, Hq, Hkv)
+            S = scale * (q[rb, h, :] @ k[cols, g, :].T)
+            S = np.where(M, S, -np.inf)
+            m = S.max(axis=1, keepdims=True)
+            E = np.exp(S - m)
+            Z = E.sum(axis=1, keepdims=True)
+            P = E / Z
+            O[pos:pos + len(rb), h, :] = P @ v[cols, g, :]
+            LSE[h, pos:pos + len(rb)] = (m + np.log(Z))[:, 0]
+            if return_probs:
+                P_all[h, pos:pos + len(rb), :] = P
+        pos += len(rb)
+    if return_probs:
+        return O, LSE, P_all
+    return O, LSE
+
+
+def attn_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, do: np.ndarray, L: int, K: int, scale: float,
+                  rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
+                  row_block: int = 1024) -> Dict[str, np.ndarray]:
+    """Gradients of sum(O * dO) for the rows in ``rows`` (default all).
+
+    With P the softmax probabilities: dV = P^T dO, dP = dO V^T, Delta = rowsum(P * dP),
+    dS = P * (dP - Delta), dQ = scale * dS K, dK = scale * dS^T Q; dK and dV are summed
+    over the query heads that share a KV head.
+
+    Returns dict with O, LSE, dQ (rows given, in the given order) and dK, dV
+    ([T, Hkv, D], zero outside ``cols``).
+    """
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    rows = np.arange(T) if rows is None else np.asarray(rows)
+    cols = np.arange(T) if cols is None else np.asarray(cols)
+    O = np.zeros((len(rows), Hq, D))
+    LSE = np.zeros((Hq, len(rows)))
+    dQ = np.zeros((len(rows), Hq, D))
+    dK = np.zeros((T, Hkv, D))
+    dV = np.zeros((T, Hkv, D))
+    pos = 0
+    for rb in _row_blocks(rows, row_block):
+        M = element_mask(L, K, rb, cols)
+        sl = slice(pos, pos + len(rb))
+        for h in range(Hq):
+            g = _kv_head(h, Hq, Hkv)
+            Kc = k[cols, g, :]
+            Vc = v[cols, g, :]
+            S = scale * (q[rb, h, :] @ Kc.T)
+            S = np.where(M, S, -np.inf)
+            m = S.max(axis=1, keepdims=True)
+            E = np.exp(S - m)
+            Z = E.sum(axis=1, keepdims=True)
+            P = E / Z
+            dOh = do[rb, h, :]
+            O[sl, h, :] = P @ Vc
+            LSE[h, sl] = (m + np.log(Z))[:, 0]
+            dP = dOh @ Vc.T
+            delta = (P * dP).sum(axis=1, keepdims=True)
+            dS = P * (dP - delta)
+            dQ[sl, h, :] = scale * (dS @ Kc)
+            dK[cols, g, :] += scale * (dS.T @ q[rb, h, :])
+            dV[cols, g, :] += P.T @ dOh
+        pos += len(rb)
+    return {"O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
+
+
+# --------------------------------------------------------------------------------------
+# sequence partitioning / within-sequence gradient accumulation (Sec. 3.2)
+# --------------------------------------------------------------------------------------
+
+def segment_rows(L: int, K: int, b_lo: int, b_hi: int) -> np.ndarray:
+    """Query rows of the segment holding anchors [b_lo, b_hi): every depth of those anchors."""
+    i = np.arange(b_lo, b_hi)
+    return np.concatenate([token_index(i, d, L) for d in range(K)])
+
+
+def segment_keys(L: int, K: int, b_lo: int, b_hi: int) -> np.ndarray:
+    """Keys present while the segment runs: depth-0 positions cumulatively up to the
+    segment's end (Phase 3 of Algorithm 1) plus the segment's own positions."""
+    n0 = np.arange(0, b_hi)                       # cumulative depth-0 context N_s
+    own = np.arange(b_lo, b_hi)
+    return np.concatenate([token_index(n0, 0, L)] + [token_index(own, d, L) for d in range(1, K)])
+
+
+def attn_step_partitioned(q, k, v, do, L: int, K: int, scale: float, seg_bounds: Sequence[int],
+                          row_block: int = 1024) -> Dict[str, np.ndarray]:
+    """One forward+backward per segment, gradients accumulated across segments.
+
+    Each segment runs as a separate pass that holds only its own rows and the keys of
+    :func:`segment_keys`; dK and dV are summed over the passes in fp64; O, LSE and dQ
+    of a row come from the one pass that owns the row.
+    """
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    b = [int(x) for x in seg_bounds]
+    assert b[0] == 0 and b[-1] == L and all(b[s] < b[s + 1] for s in range(len(b) - 1))
+    O = np.zeros((T, Hq, D))
+    LSE = np.zeros((Hq, T))
+    dQ = np.zeros((T, Hq, D))
+    dK = np.zeros((T, Hkv, D))
+    dV = np.zeros((T, Hkv, D))
+    for s in range(len(b) - 1):
+        rows = segment_rows(L, K, b[s], b[s + 1])
+        cols = segment_keys(L, K, b[s], b[s + 1])
+        r = attn_backward(q, k, v, do, L, K, scale, rows=rows, cols=cols, row_block=row_block)
+        O[rows] = r["O"]
+        LSE[:, rows] = r["LSE"]
+        dQ[rows] = r["dQ"]
+        dK += r["dK"]
+        dV += r["dV"]
+    return {"O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
+
+
+def partition_assign(positions: Sequence[Sequence[int]], S: int, L: int) -> Tuple[List[Dict[int, int]], List[List[int]]]:
+    """Segment assignment of Algorithm 1 for (possibly COD-sampled) position sets.
+
+    ``positions[g]`` lists the sequence positions kept at depth g.  Boundaries are
+    B_s = s*L/S.  Depths 0 and 1 are assigned by position (largest s with B_s <= p);
+    a position p at depth g >= 2 inherits the segment of position p-1 at depth g-1;
+    segment s additionally carries the depth-0 positions below B_{s+1}.
+
+    Returns (A, N): A[g] maps position -> segment, N[s] lists cumulative depth-0 positions.
+    """
+    Kd = len(positions)
+    B = [s * L / S for s in range(S + 1)]
+    A: List[Dict[int, int]] = [dict() for _ in range(Kd)]
+    for g in range(min(2, Kd)):
+        for p in positions[g]:
+            A[g][p] = max(s for s in range(S) if B[s] <= p)
+    for g in range(2, Kd):
+        for p in positions[g]:
+            A[g][p] = A[g - 1][p - 1]
+    N = [[p for p in positions[0] if p < B[s + 1]] for s in range(S)]
+    return A, N
+
+
+def cod_position_count(n: int, K: int, r: float) -> float:
+    """Total positions over all depths under geometric retention: n * (1 - r^K) / (1 - r) (Sec. 3.2)."""
+    if r == 1.0:
+        return float(n * K)
+    return n * (1.0 - r ** K) / (1.0 - r)

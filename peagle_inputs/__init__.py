@@ -1,0 +1,17 @@
+"""Seeded synthetic inputs shared by the fp64 oracle and the HIP path.
+
+This module holds no attention arithmetic: it names the workload shapes, draws the
+random tensors and rounds them to bf16 bit patterns.  Both sides consume exactly
+these bytes.
+"""
+from .gen import CONFIGS, WorkloadConfig, bf16_bits_to_f64, f32_to_bf16_bits, make_inputs, useful_pairs, useful_flops
+
+__all__ = [
+    "CONFIGS",
+    "WorkloadConfig",
+    "bf16_bits_to_f64",
+    "f32_to_bf16_bits",
+    "make_inputs",
+    "useful_pairs",
+    "useful_flops",
+]

@@ -1,0 +1,339 @@
+"""Pins for the fp64 oracle: every check compares it with something other than itself
+(closed forms, library routines, brute force from the paper's dependency rules,
+finite differences, values printed in the paper)."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import peagle_oracle as orc
+from peagle_inputs import CONFIGS, bf16_bits_to_f64, f32_to_bf16_bits, make_inputs, useful_pairs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(L, K, Hq, Hkv, D, seed):
+    rng = np.random.default_rng(seed)
+    T = L * K
+    return (rng.standard_normal((T, Hq, D)), rng.standard_normal((T, Hkv, D)),
+            rng.standard_normal((T, Hkv, D)), rng.standard_normal((T, Hq, D)))
+
+
+# ----------------------------------------------------------------------------- mask
+
+def _mask_from_dependency_rules(L, K):
+    """Mask rebuilt in *position* coordinates from the paper's rules, by brute force:
+    (p, d) with p = i + d depends on (p-1, d-1) transitively down to depth 1, sees
+    itself, and sees the depth-0 context available to its anchor (positions <= p - d)."""
+    T = L * K
+    M = np.zeros((T, T), dtype=bool)
+    for i, d in itertools.product(range(L), range(K)):
+        r = d * L + i
+        p = i + d
+        for q0 in range(0, p - d + 1):          # depth-0 positions q0 <= p-d, anchor == position
+            M[r, q0] = True
+        pp, dd = p, d
+        while dd >= 1:                          # self, then (p-1,d-1), (p-2,d-2), ... down to depth 1
+            anchor = pp - dd
+            M[r, dd * L + anchor] = True
+            pp, dd = pp - 1, dd - 1
+    return M
+
+
+@pytest.mark.parametrize("L,K", [(1, 1), (5, 1), (7, 3), (16, 4), (9, 8)])
+def test_mask_matches_dependency_rules(L, K):
+    assert np.array_equal(orc.element_mask(L, K), _mask_from_dependency_rules(L, K))
+
+
+@pytest.mark.parametrize("L,K", [(7, 3), (16, 4), (33, 8)])
+def test_mask_scalar_predicate_agrees(L, K):
+    M = orc.element_mask(L, K)
+    for r in range(L * K):
+        i, d = orc.token_coords(r, L)
+        for c in range(L * K):
+            j, e = orc.token_coords(c, L)
+            assert M[r, c] == orc.visible(i, d, j, e)
+
+
+@pytest.mark.parametrize("L,K", [(16, 4), (128, 4), (50, 8), (64, 1)])
+def test_mask_closed_form_counts(L, K):
+    M = orc.element_mask(L, K)
+    T = L * K
+    i, d = orc.token_coords(np.arange(T), L)
+    assert np.array_equal(M.sum(axis=1), i + 1 + d)               # row (i,d) sees i+1 causal + d chain keys
+    assert M.sum() == useful_pairs(L, K)
+    col = M.sum(axis=0)
+    j, e = orc.token_coords(np.arange(T), L)
+    expect = np.where(e == 0, K * (L - j), K - e)                  # depth-0 key j: K*(L-j) rows; chain key: K-e rows
+    assert np.array_equal(col, expect)
+    # depth rule: no key of a deeper depth is ever visible
+    assert not M[(d[:, None] < e[None, :])].any()
+
+
+def test_useful_pairs_values():
+    assert useful_pairs(128, 4) == 33792
+    assert useful_pairs(2048, 4) == 8404992
+    assert useful_pairs(4096, 8) == 67239936
+
+
+def test_mask_k1_is_causal():
+    assert np.array_equal(orc.element_mask(37, 1), np.tril(np.ones((37, 37), dtype=bool)))
+
+
+@pytest.mark.parametrize("L1,L2,K", [(5, 12, 3), (16, 40, 4), (8, 9, 8)])
+def test_mask_crop_invariance(L1, L2, K):
+    """Position invariance (Sec. 3.1): the mask of the shorter sequence is the longer one's
+    restricted to anchors < L1, in (anchor, depth) coordinates."""
+    M1 = orc.element_mask(L1, K)
+    M2 = orc.element_mask(L2, K)
+    idx = np.array([orc.token_index(i, d, L2) for d in range(K) for i in range(L1)])
+    assert np.array_equal(M2[np.ix_(idx, idx)], M1)
+
+
+# ----------------------------------------------------------------------------- forward
+
+def _torch_sdpa(q, k, v, mask=None, causal=False, scale=None):
+    """Library routine: torch SDPA on CPU in fp64. q [T,H,D] -> [T,H,D]."""
+    tq = torch.from_numpy(q).permute(1, 0, 2).unsqueeze(0)
+    tk = torch.from_numpy(k).permute(1, 0, 2).unsqueeze(0)
+    tv = torch.from_numpy(v).permute(1, 0, 2).unsqueeze(0)
+    m = None if mask is None else torch.from_numpy(mask)
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=m, is_causal=causal, scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+def test_depth0_rows_are_plain_causal_attention():
+    L, K, Hq, Hkv, D = 48, 4, 4, 2, 16
+    q, k, v, _ = _rand(L, K, Hq, Hkv, D, 3)
+    scale = 0.37
+    O, LSE = orc.attn_forward(q, k, v, L, K, scale)
+    rep = Hq // Hkv
+    ref = _torch_sdpa(q[:L], np.repeat(k[:L], rep, axis=1), np.repeat(v[:L], rep, axis=1), causal=True, scale=scale)
+    assert np.allclose(O[:L], ref, rtol=1e-12, atol=1e-12)
+    # LSE of depth-0 rows against scipy's logsumexp
+    from scipy.special import logsumexp
+    for h in range(Hq):
+        g = h // rep
+        S = scale * q[:L, h] @ k[:L, g].T
+        S[np.triu_indices(L, 1)] = -np.inf
+        assert np.allclose(LSE[h, :L], logsumexp(S, axis=1), rtol=1e-12, atol=1e-12)
+
+
+def test_k1_whole_problem_is_causal_attention_fwd_bwd():
+    L, K, Hq, Hkv, D = 40, 1, 2, 1, 8
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 4)
+    scale = 1.0 / np.sqrt(D)
+    r = orc.attn_backward(q, k, v, do, L, K, scale)
+    tq = torch.from_numpy(q).requires_grad_()
+    tk = torch.from_numpy(k).requires_grad_()
+    tv = torch.from_numpy(v).requires_grad_()
+    o = torch.nn.functional.scaled_dot_product_attention(
+        tq.permute(1, 0, 2)[None], tk.permute(1, 0, 2).repeat_interleave(2, 0)[None],
+        tv.permute(1, 0, 2).repeat_interleave(2, 0)[None], is_causal=True, scale=scale)[0].permute(1, 0, 2)
+    (o * torch.from_numpy(do)).sum().backward()
+    assert np.allclose(r["O"], o.detach().numpy(), atol=1e-12)
+    assert np.allclose(r["dQ"], tq.grad.numpy(), atol=1e-12)
+    assert np.allclose(r["dK"], tk.grad.numpy(), atol=1e-12)
+    assert np.allclose(r["dV"], tv.grad.numpy(), atol=1e-12)
+
+
+@pytest.mark.parametrize("L,K,Hq,Hkv,D", [(12, 3, 4, 2, 8), (16, 4, 4, 1, 16), (6, 8, 2, 2, 4)])
+def test_library_autograd_with_independent_mask(L, K, Hq, Hkv, D):
+    """Forward and all three gradients against torch autograd through its own SDPA, with the mask
+    rebuilt from the dependency rules (not the oracle's builder) and GQA done by repeat_interleave."""
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 5)
+    scale = 0.21
+    r = orc.attn_backward(q, k, v, do, L, K, scale)
+    M = torch.from_numpy(_mask_from_dependency_rules(L, K))
+    rep = Hq // Hkv
+    tq = torch.from_numpy(q).requires_grad_()
+    tk = torch.from_numpy(k).requires_grad_()
+    tv = torch.from_numpy(v).requires_grad_()
+    o = torch.nn.functional.scaled_dot_product_attention(
+        tq.permute(1, 0, 2)[None], tk.permute(1, 0, 2).repeat_interleave(rep, 0)[None],
+        tv.permute(1, 0, 2).repeat_interleave(rep, 0)[None], attn_mask=M, scale=scale)[0].permute(1, 0, 2)
+    (o * torch.from_numpy(do)).sum().backward()
+    assert np.allclose(r["O"], o.detach().numpy(), atol=1e-12)
+    assert np.allclose(r["dQ"], tq.grad.numpy(), atol=1e-11)
+    assert np.allclose(r["dK"], tk.grad.numpy(), atol=1e-11)
+    assert np.allclose(r["dV"], tv.grad.numpy(), atol=1e-11)
+
+
+def test_softmax_rows_sum_to_one_and_lse_consistent():
+    L, K, Hq, Hkv, D = 20, 4, 2, 1, 8
+    q, k, v, _ = _rand(L, K, Hq, Hkv, D, 6)
+    O, LSE, P = orc.attn_forward(q, k, v, L, K, 0.5, return_probs=True)
+    assert np.allclose(P.sum(axis=2), 1.0, atol=1e-14)
+    M = _mask_from_dependency_rules(L, K)
+    assert (P[:, ~M] == 0).all()
+    # P == exp(S - LSE) on visible entries
+    S = 0.5 * np.einsum("rhd,chd->hrc", q, np.repeat(k, 2, axis=1))
+    assert np.allclose(P[:, M], np.exp(S - LSE[:, :, None])[:, M], atol=1e-13)
+
+
+def test_zero_query_closed_form():
+    """Q == 0: uniform softmax, so O(i,d) is the mean of the visible V rows and LSE = ln(i+1+d)."""
+    L, K, Hq, Hkv, D = 24, 4, 2, 2, 8
+    _, k, v, do = _rand(L, K, Hq, Hkv, D, 7)
+    q = np.zeros((L * K, Hq, D))
+    r = orc.attn_backward(q, k, v, do, L, K, 0.3)
+    for i, d in itertools.product(range(L), range(K)):
+        t = d * L + i
+        cnt = i + 1 + d
+        for h in range(Hq):
+            mean = (v[:i + 1, h].sum(axis=0) + sum(v[e * L + i, h] for e in range(1, d + 1))) / cnt
+            assert np.allclose(r["O"][t, h], mean, atol=1e-13)
+            assert np.isclose(r["LSE"][h, t], np.log(cnt), atol=1e-13)
+    # dV closed form: each row spreads dO/count over its visible keys
+    dV = np.zeros_like(v)
+    for i, d in itertools.product(range(L), range(K)):
+        t = d * L + i
+        cnt = i + 1 + d
+        for h in range(Hq):
+            dV[:i + 1, h] += do[t, h] / cnt
+            for e in range(1, d + 1):
+                dV[e * L + i, h] += do[t, h] / cnt
+    assert np.allclose(r["dV"], dV, atol=1e-12)
+
+
+def test_constant_v_gives_constant_output():
+    L, K, Hq, Hkv, D = 10, 3, 2, 1, 4
+    q, k, _, _ = _rand(L, K, Hq, Hkv, D, 8)
+    v = np.tile(np.arange(D, dtype=np.float64), (L * K, Hkv, 1))
+    O, _ = orc.attn_forward(q, k, v, L, K, 1.0)
+    assert np.allclose(O, np.arange(D), atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- backward
+
+def test_finite_differences():
+    L, K, Hq, Hkv, D = 6, 3, 4, 2, 4
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 9)
+    scale = 0.45
+    r = orc.attn_backward(q, k, v, do, L, K, scale)
+
+    def loss(q_, k_, v_):
+        O, _ = orc.attn_forward(q_, k_, v_, L, K, scale)
+        return (O * do).sum()
+
+    eps = 1e-6
+    rng = np.random.default_rng(0)
+    for name, arr, grad in (("q", q, r["dQ"]), ("k", k, r["dK"]), ("v", v, r["dV"])):
+        flat = arr.reshape(-1)
+        for idx in rng.choice(flat.size, size=40, replace=False):
+            old = flat[idx]
+            flat[idx] = old + eps
+            fp = loss(q, k, v)
+            flat[idx] = old - eps
+            fm = loss(q, k, v)
+            flat[idx] = old
+            fd = (fp - fm) / (2 * eps)
+            assert np.isclose(fd, grad.reshape(-1)[idx], rtol=1e-6, atol=1e-8), (name, idx)
+
+
+def test_backward_identities():
+    L, K, Hq, Hkv, D = 14, 4, 2, 1, 8
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 10)
+    scale = 0.3
+    r = orc.attn_backward(q, k, v, do, L, K, scale)
+    # sum_rows dQ . q == sum dK . k (both equal sum dS*S/scale*scale): the score gradient seen from both sides
+    assert np.isclose((r["dQ"] * q).sum(), (r["dK"] * k).sum(), rtol=1e-12)
+    # sum over keys of dV equals sum over rows of dO per KV head (softmax rows sum to 1)
+    assert np.allclose(r["dV"].sum(axis=0)[0], do.sum(axis=(0, 1)), atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- partition
+
+@pytest.mark.parametrize("bounds", [[0, 16], [0, 8, 16], [0, 4, 8, 12, 16], [0, 5, 16]])
+def test_partitioned_equals_unpartitioned(bounds):
+    L, K, Hq, Hkv, D = 16, 4, 4, 2, 8
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 11)
+    full = orc.attn_backward(q, k, v, do, L, K, 0.35)
+    part = orc.attn_step_partitioned(q, k, v, do, L, K, 0.35, bounds)
+    for name in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.allclose(full[name], part[name], atol=1e-13), name
+
+
+def test_segment_rows_partition_all_rows_and_keys_cover_mask():
+    L, K = 24, 4
+    bounds = [0, 8, 16, 24]
+    seen = []
+    M = _mask_from_dependency_rules(L, K)
+    for s in range(3):
+        rows = orc.segment_rows(L, K, bounds[s], bounds[s + 1])
+        cols = set(orc.segment_keys(L, K, bounds[s], bounds[s + 1]).tolist())
+        seen.extend(rows.tolist())
+        needed = set(np.nonzero(M[rows].any(axis=0))[0].tolist())
+        assert needed <= cols                      # every key a row may see is present in its segment
+    assert sorted(seen) == list(range(L * K))      # disjoint cover of all query rows
+
+
+def _read_partition_example():
+    d = {}
+    assigns = []
+    with open(os.path.join(GOLDEN, "partition_example.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            tok = line.split()
+            if tok[0] == "assign":
+                assigns.append((int(tok[1][-1]), int(tok[2]), int(tok[3])))
+            elif tok[0].startswith("depth"):
+                d[tok[0]] = [int(x) for x in tok[1:]]
+            else:
+                d[tok[0]] = int(tok[1])
+    return d, assigns
+
+
+def test_partition_worked_example_from_paper():
+    d, assigns = _read_partition_example()
+    pos = [d[f"depth{g}"] for g in range(d["K"])]
+    assert sum(len(p) for p in pos) == d["total"]
+    A, N = orc.partition_assign(pos, d["S"], d["n"])
+    for g, p, s in assigns:
+        assert A[g][p] == s
+    # every position shares the segment of its dependency (p-1, g-1) for g >= 2
+    for g in range(2, d["K"]):
+        for p in pos[g]:
+            assert A[g][p] == A[g - 1][p - 1]
+    assert N[0] == list(range(8)) and N[1] == list(range(16))
+    assert all(A[0][p] == (0 if p < 8 else 1) for p in pos[0])
+
+
+def test_cod_count_formula_value_from_paper():
+    vals = {}
+    with open(os.path.join(GOLDEN, "cod_count.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                a, b = line.split()
+                vals[a] = float(b)
+    got = orc.cod_position_count(int(vals["n"]), int(vals["K"]), vals["r"])
+    assert abs(got - vals["approx"]) / vals["approx"] < vals["rel_tol"]
+    assert abs(got - 34088.0) < 1.0
+    assert orc.cod_position_count(16, 4, 1.0) == 64
+
+
+# ----------------------------------------------------------------------------- input generator
+
+def test_bf16_rounding_matches_torch():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(100000).astype(np.float32)
+    bits = f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(bits, ref)
+    back = bf16_bits_to_f64(bits)
+    assert np.array_equal(back, torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+def test_make_inputs_shapes_and_determinism():
+    cfg = CONFIGS["c1_tiny"]
+    a = make_inputs(cfg)
+    b = make_inputs(cfg)
+    assert a[0].shape == (512, 4, 64) and a[1].shape == (512, 1, 64) and a[3].shape == (512, 4, 64)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    assert a[0].dtype == np.uint16
+    x = bf16_bits_to_f64(a[0])
+    assert abs(x.mean()) < 0.02 and abs(x.std() - 1.0) < 0.02
