@@ -1,0 +1,184 @@
+/*
+ * peagle.h - C ABI of the MI355X (gfx950) parallel-drafting attention path of P-EAGLE.
+ *
+ * The library computes, for the training of the P-EAGLE drafter, masked attention over the
+ * expanded sequence of Sec. 3 of the paper: a sequence of L tokens becomes T = L*K positions,
+ * one per (anchor i in [0,L), prediction depth d in [0,K)); depth 0 is the ordinary next-token
+ * position, depths 1..K-1 carry the shared hidden state.  The parallel-prediction mask
+ * (Sec. 3, PARD paragraph: a depth-d row sees depths <= d only; Sec. 3.2 "Challenge 2":
+ * position p at depth d depends on position p-1 at depth d-1) reads, in anchor coordinates:
+ *
+ *     row (i,d) sees key (j,e)   iff   (e == 0 and j <= i)  or  (j == i and 1 <= e <= d).
+ *
+ * Storage order of every [T, ...] tensor is depth-major: t = d*L + i (the G0|G1|... blocks of
+ * Fig. 3).  Query head h uses KV head h / (Hq/Hkv).
+ *
+ * Conventions shared by all entry points
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library never frees or keeps caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All GPU work is
+ *     enqueued on it; no entry point synchronises the device except peagle_build_tilemap
+ *     (whose upload is complete on return).
+ *   - Return value: PEAGLE_OK (0) or a negative peagle_status.  Arguments are validated on the
+ *     host before anything is launched, so every error path can be exercised without a GPU.
+ *     Nothing is printed, thrown or aborted.
+ */
+#ifndef PEAGLE_H
+#define PEAGLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum peagle_status {
+  PEAGLE_OK = 0,
+  PEAGLE_EINVAL = -1,       /* bad scalar argument (negative size, Hq % Hkv != 0, seg out of range ...) */
+  PEAGLE_ENULL = -2,        /* a required pointer is NULL */
+  PEAGLE_ESHAPE = -3,       /* shape does not fit the tile map (L > L_max, K mismatch) */
+  PEAGLE_EBOUNDS = -4,      /* segment bounds not strictly increasing from 0 to L_max, or an inner bound
+                               is not a multiple of the anchors-per-row-tile */
+  PEAGLE_EUNSUPPORTED = -5, /* head_dim not in {64, 128}, K > 128, unknown layout */
+  PEAGLE_EWORKSPACE = -6,   /* workspace missing or smaller than peagle_workspace_bytes() */
+  PEAGLE_EHIP = -7,         /* a HIP runtime call failed (allocation, copy, launch) */
+  PEAGLE_ENODEVICE = -8     /* the tile map was built host-only (device < 0) and cannot be used to launch */
+} peagle_status;
+
+#define PEAGLE_LAYOUT_DEPTH_MAJOR 0   /* t = d*L + i; the only layout */
+
+/* Problem shape of one call.  L may be any value in [1, L_max of the tile map]: the shorter
+ * sequence uses the prefix of the tile map (position invariance of the mask, Sec. 3.1). */
+typedef struct peagle_shape {
+  int32_t L;       /* anchor tokens */
+  int32_t K;       /* prediction depths; must equal the tile map's K */
+  int32_t Hq;      /* query heads */
+  int32_t Hkv;     /* key/value heads, divides Hq */
+  int32_t D;       /* head dimension, 64 or 128 */
+  int32_t layout;  /* PEAGLE_LAYOUT_DEPTH_MAJOR */
+  float scale;     /* softmax scale applied to q.k (e.g. 1/sqrt(D)) */
+} peagle_shape_t;
+
+/* Opaque tile map: library-owned host copy plus (unless built host-only) a device copy. */
+typedef struct peagle_tilemap peagle_tilemap_t;
+
+/* Tile classes of peagle_tilemap_classes(). */
+#define PEAGLE_TILE_EMPTY 0
+#define PEAGLE_TILE_FULL 1
+#define PEAGLE_TILE_PARTIAL 2
+
+typedef struct peagle_tilemap_info {
+  int32_t L_max, K, S;
+  int32_t anchors_per_row_tile;  /* A = 128 / K (integer division): a row tile is A anchors x all K depths */
+  int32_t rows_per_tile;         /* 128 (A*K of them in use) */
+  int32_t keys_per_tile;         /* 64 */
+  int32_t n_row_tiles;           /* ceil(L_max / A) */
+  int32_t n_depth0_key_tiles;    /* ceil(L_max / 64): key tile c holds depth-0 anchors [64c, 64c+64) */
+  int32_t n_chain_sub_tiles;     /* ceil(A*(K-1) / 64): chain key tiles per row tile */
+  int32_t n_key_tiles;           /* depth-0 tiles followed by n_row_tiles * n_chain_sub_tiles chain tiles */
+  int64_t n_full;                /* non-empty tile pairs whose every element is visible */
+  int64_t n_partial;             /* tile pairs that need a bitmask */
+  int32_t n_masks;               /* distinct bitmasks in the pool (128 rows x 64 bits each) */
+  int64_t device_bytes;          /* bytes of the device copy (0 if host-only) */
+} peagle_tilemap_info_t;
+
+/*
+ * Mask -> tile map, built once for the maximum length (amortized mask construction, Sec. 3.1)
+ * with the segment boundaries of sequence partitioning (Sec. 3.2, boundaries B of Algorithm 1,
+ * given explicitly because L/S need not be an integer).
+ *
+ *   L_max       maximum anchor count, >= 1
+ *   K           prediction depths, 1..128
+ *   seg_bounds  host, int32[S+1], anchor indices, seg_bounds[0] = 0 < ... < seg_bounds[S] = L_max;
+ *               every inner bound must be a multiple of A = 128/K.  NULL with S = 1 means {0, L_max}.
+ *   device      HIP device ordinal for the device copy, or -1 for a host-only map (introspection only)
+ *   out         receives the handle; release with peagle_tilemap_destroy
+ *
+ * Geometry: a row tile is A consecutive anchors at all K depths (row r of the tile is depth r/A,
+ * anchor r%A).  Its keys come from two streams: depth-0 key tiles of 64 consecutive anchors, and
+ * the chain key tiles holding the depth >= 1 positions of the tile's own anchors (key k of the
+ * chain stream is depth 1 + k/A, anchor k%A).  Each (row tile, key tile) pair is classified
+ * empty / full / partial from interval tests; partial pairs point into a pool of de-duplicated
+ * bitmasks (the pool has O(1) entries because the mask is position-invariant).
+ */
+int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg_bounds, int32_t S, int32_t device,
+                         peagle_tilemap_t** out);
+
+void peagle_tilemap_destroy(peagle_tilemap_t* tm);
+
+int peagle_tilemap_info(const peagle_tilemap_t* tm, peagle_tilemap_info_t* info /* host, out */);
+
+/*
+ * Host-side expansion of the tile map back to the element mask, for bit-exact checks.
+ * For the query rows t in [row_begin, row_end) (token indices of a length-L problem, L <= L_max)
+ * writes (row_end-row_begin) * ceil(L*K/8) bytes to bits_out (host): bit (c % 8) of byte c/8 of a
+ * row is 1 iff key token c is visible.  With seg >= 0, rows outside segment `seg` come out all zero.
+ */
+int peagle_tilemap_expand_rows(const peagle_tilemap_t* tm, int32_t L, int32_t seg, int64_t row_begin,
+                               int64_t row_end, uint8_t* bits_out);
+
+/* Dense class map: classes_out (host) receives n_row_tiles * n_key_tiles bytes, row-tile major,
+ * each PEAGLE_TILE_EMPTY / _FULL / _PARTIAL. */
+int peagle_tilemap_classes(const peagle_tilemap_t* tm, uint8_t* classes_out);
+
+/* Bytes of device scratch that peagle_attn_bwd / peagle_attn_step_partitioned need for this shape. */
+size_t peagle_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape);
+
+/*
+ * Attention forward over the query rows of one segment (seg in [0,S)) or of the whole sequence
+ * (seg = -1): S = scale * Q K^T on non-empty tiles, mask bits on partial tiles, online softmax,
+ * O = P V, LSE = ln sum exp (natural log, scale included).  The attention is the O((nK)^2) term
+ * of Sec. 3; a segment's keys are the cumulative depth-0 context plus its own chains (Sec. 3.2).
+ *
+ *   q        device, bf16 [T, Hq, D]           k, v   device, bf16 [T, Hkv, D]
+ *   o        device, bf16 [T, Hq, D]  (out; only the segment's rows are written)
+ *   lse      device, fp32 [Hq, T]     (out; only the segment's rows are written)
+ */
+int peagle_attn_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg, const void* q,
+                    const void* k, const void* v, void* o, float* lse, void* stream);
+
+/*
+ * Attention backward for the same rows: Delta = rowsum(dO * O), P = exp(S - LSE), dV = P^T dO,
+ * dP = dO V^T, dS = P * (dP - Delta), dQ = scale * dS K, dK = scale * dS^T Q, with dK/dV summed
+ * over the query heads of a KV group ("separate forward-backward pass" per segment, Sec. 3.2).
+ *
+ *   o, d_o     device, bf16 [T, Hq, D]   (O from peagle_attn_fwd, upstream gradient)
+ *   lse        device, fp32 [Hq, T]
+ *   dq         device, bf16 [T, Hq, D]   (out; only the segment's rows are written)
+ *   dk_acc     device, fp32 [T, Hkv, D]  (out; only keys visible to the segment are touched)
+ *   dv_acc     device, fp32 [T, Hkv, D]
+ *   accumulate 0: touched dK/dV elements are overwritten; 1: added to (caller zeroed or holds
+ *              earlier segments' sums)
+ *   workspace  device, >= peagle_workspace_bytes(); contents undefined before and after
+ */
+int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg, const void* q,
+                    const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
+                    float* dk_acc, float* dv_acc, int32_t accumulate, void* workspace, size_t ws_bytes,
+                    void* stream);
+
+/*
+ * Within-sequence gradient accumulation (Sec. 3.2, Algorithm 1 for dense position sets): runs
+ * forward + backward for segments seg_begin .. seg_end-1 one after another and accumulates dK/dV
+ * across them in fp32.  Each query row is computed in exactly one segment.
+ *
+ * dK/dV need no zeroing when segments run in increasing order starting at 0: a depth-0 key first
+ * touched by segment s is overwritten there and added to by later segments; chain keys are written
+ * by their own segment only.  A call with seg_begin > 0 continues a run whose earlier segments
+ * already ran on the same dk_acc/dv_acc.
+ *
+ *   dk_bf16, dv_bf16   device, bf16 [T, Hkv, D] or NULL: if given and seg_end == S, the fp32
+ *                      sums are rounded once to bf16 into them after the last segment.
+ */
+int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin,
+                                 int32_t seg_end, const void* q, const void* k, const void* v, const void* d_o,
+                                 void* o, float* lse, void* dq, float* dk_acc, float* dv_acc, void* dk_bf16,
+                                 void* dv_bf16, void* workspace, size_t ws_bytes, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* peagle_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PEAGLE_H */

@@ -1,0 +1,18 @@
+"""MI355X-native parallel-drafting attention of the P-EAGLE drafter (training hot path).
+
+Thin ctypes binding over ``libpeagle_attn.so`` (C ABI in ``include/peagle.h``).  PyTorch is
+used only for device buffers and streams; every step of the path runs in the HIP kernels.
+"""
+from .binding import (  # noqa: F401
+    PeagleError,
+    Shape,
+    TileMap,
+    lib_path,
+    load_library,
+    peagle_attn_bwd,
+    peagle_attn_fwd,
+    peagle_attn_step_partitioned,
+    peagle_build_tilemap,
+    peagle_strerror,
+    peagle_workspace_bytes,
+)

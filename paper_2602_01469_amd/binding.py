@@ -1,0 +1,236 @@
+"""ctypes binding: argument marshalling only.  Names mirror the C ABI of include/peagle.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libpeagle_attn.so"
+_lib = None
+
+
+class PeagleError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {peagle_strerror(status)} (status {status})")
+
+
+class _ShapeC(C.Structure):
+    _fields_ = [("L", C.c_int32), ("K", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+                ("layout", C.c_int32), ("scale", C.c_float)]
+
+
+class _InfoC(C.Structure):
+    _fields_ = [("L_max", C.c_int32), ("K", C.c_int32), ("S", C.c_int32), ("anchors_per_row_tile", C.c_int32),
+                ("rows_per_tile", C.c_int32), ("keys_per_tile", C.c_int32), ("n_row_tiles", C.c_int32),
+                ("n_depth0_key_tiles", C.c_int32), ("n_chain_sub_tiles", C.c_int32), ("n_key_tiles", C.c_int32),
+                ("n_full", C.c_int64), ("n_partial", C.c_int64), ("n_masks", C.c_int32), ("device_bytes", C.c_int64)]
+
+
+EXPORTS = [
+    "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
+    "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
+    "peagle_attn_step_partitioned", "peagle_strerror",
+]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load the HIP extension; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2602_01469_amd.build` "
+                          "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(path)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    lib.peagle_build_tilemap.argtypes = [i32, i32, C.POINTER(i32), i32, i32, C.POINTER(vp)]
+    lib.peagle_build_tilemap.restype = C.c_int
+    lib.peagle_tilemap_destroy.argtypes = [vp]
+    lib.peagle_tilemap_destroy.restype = None
+    lib.peagle_tilemap_info.argtypes = [vp, C.POINTER(_InfoC)]
+    lib.peagle_tilemap_info.restype = C.c_int
+    lib.peagle_tilemap_expand_rows.argtypes = [vp, i32, i32, i64, i64, vp]
+    lib.peagle_tilemap_expand_rows.restype = C.c_int
+    lib.peagle_tilemap_classes.argtypes = [vp, vp]
+    lib.peagle_tilemap_classes.restype = C.c_int
+    lib.peagle_workspace_bytes.argtypes = [vp, C.POINTER(_ShapeC)]
+    lib.peagle_workspace_bytes.restype = sz
+    lib.peagle_attn_fwd.argtypes = [vp, C.POINTER(_ShapeC), i32, vp, vp, vp, vp, vp, vp]
+    lib.peagle_attn_fwd.restype = C.c_int
+    lib.peagle_attn_bwd.argtypes = [vp, C.POINTER(_ShapeC), i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.peagle_attn_bwd.restype = C.c_int
+    lib.peagle_attn_step_partitioned.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                 vp, vp, vp, sz, vp]
+    lib.peagle_attn_step_partitioned.restype = C.c_int
+    lib.peagle_strerror.argtypes = [C.c_int]
+    lib.peagle_strerror.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def peagle_strerror(status: int) -> str:
+    return load_library().peagle_strerror(int(status)).decode()
+
+
+class Shape:
+    """Mirror of peagle_shape_t."""
+
+    def __init__(self, L: int, K: int, Hq: int, Hkv: int, D: int, scale: Optional[float] = None, layout: int = 0):
+        self.L, self.K, self.Hq, self.Hkv, self.D, self.layout = int(L), int(K), int(Hq), int(Hkv), int(D), int(layout)
+        self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(D))
+        self._c = _ShapeC(self.L, self.K, self.Hq, self.Hkv, self.D, self.layout, self.scale)
+
+    @property
+    def T(self) -> int:
+        return self.L * self.K
+
+    def c(self):
+        return C.byref(self._c)
+
+
+class TileMap:
+    """Owner of a peagle_tilemap_t handle."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("tile map already destroyed")
+        return self._h
+
+    def destroy(self):
+        if self._h:
+            load_library().peagle_tilemap_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def info(self) -> dict:
+        inf = _InfoC()
+        rc = load_library().peagle_tilemap_info(self.handle, C.byref(inf))
+        if rc != 0:
+            raise PeagleError(rc, "peagle_tilemap_info")
+        return {name: getattr(inf, name) for name, _ in _InfoC._fields_}
+
+    def expand_rows(self, L: int, seg: int, row_begin: int, row_end: int) -> np.ndarray:
+        """Packed element-mask bits [row_end-row_begin, ceil(L*K/8)] (uint8, little bit order)."""
+        K = self.info()["K"]
+        row_bytes = (L * K + 7) // 8
+        out = np.zeros((max(row_end - row_begin, 0), row_bytes), dtype=np.uint8)
+        rc = load_library().peagle_tilemap_expand_rows(self.handle, L, seg, row_begin, row_end,
+                                                       out.ctypes.data_as(C.c_void_p))
+        if rc != 0:
+            raise PeagleError(rc, "peagle_tilemap_expand_rows")
+        return out
+
+    def classes(self) -> np.ndarray:
+        inf = self.info()
+        out = np.zeros((inf["n_row_tiles"], inf["n_key_tiles"]), dtype=np.uint8)
+        rc = load_library().peagle_tilemap_classes(self.handle, out.ctypes.data_as(C.c_void_p))
+        if rc != 0:
+            raise PeagleError(rc, "peagle_tilemap_classes")
+        return out
+
+
+def peagle_build_tilemap(L_max: int, K: int, seg_bounds: Optional[Sequence[int]] = None, device: int = 0) -> TileMap:
+    lib = load_library()
+    out = C.c_void_p()
+    if seg_bounds is None:
+        rc = lib.peagle_build_tilemap(L_max, K, None, 1, device, C.byref(out))
+    else:
+        b = np.ascontiguousarray(seg_bounds, dtype=np.int32)
+        rc = lib.peagle_build_tilemap(L_max, K, b.ctypes.data_as(C.POINTER(C.c_int32)), len(b) - 1, device,
+                                      C.byref(out))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_build_tilemap")
+    return TileMap(out.value)
+
+
+def peagle_workspace_bytes(tm: TileMap, shape: Shape) -> int:
+    return int(load_library().peagle_workspace_bytes(tm.handle, shape.c()))
+
+
+# --------------------------------------------------------------------------- tensor marshalling
+
+def _ptr(t, name: str, dtype, shape):
+    """Device pointer of a torch tensor after checking dtype / shape / contiguity."""
+    if t is None:
+        return None
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must live on the GPU")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def peagle_attn_fwd(tm: TileMap, shape: Shape, seg: int, q, k, v, o, lse, stream=None) -> None:
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    T = shape.T
+    rc = load_library().peagle_attn_fwd(
+        tm.handle, shape.c(), seg,
+        _ptr(q, "q", bf, (T, shape.Hq, shape.D)), _ptr(k, "k", bf, (T, shape.Hkv, shape.D)),
+        _ptr(v, "v", bf, (T, shape.Hkv, shape.D)), _ptr(o, "o", bf, (T, shape.Hq, shape.D)),
+        _ptr(lse, "lse", f32, (shape.Hq, T)), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_fwd")
+
+
+def peagle_attn_bwd(tm: TileMap, shape: Shape, seg: int, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, accumulate: int,
+                    workspace, stream=None) -> None:
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    T = shape.T
+    qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
+    rc = load_library().peagle_attn_bwd(
+        tm.handle, shape.c(), seg, _ptr(q, "q", bf, qs), _ptr(k, "k", bf, ks), _ptr(v, "v", bf, ks),
+        _ptr(o, "o", bf, qs), _ptr(d_o, "d_o", bf, qs), _ptr(lse, "lse", f32, (shape.Hq, T)),
+        _ptr(dq, "dq", bf, qs), _ptr(dk_acc, "dk_acc", f32, ks), _ptr(dv_acc, "dv_acc", f32, ks), int(accumulate),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_bwd")
+
+
+def peagle_attn_step_partitioned(tm: TileMap, shape: Shape, seg_begin: int, seg_end: int, q, k, v, d_o, o, lse, dq,
+                                 dk_acc, dv_acc, dk_bf16, dv_bf16, workspace, stream=None) -> None:
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    T = shape.T
+    qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
+    rc = load_library().peagle_attn_step_partitioned(
+        tm.handle, shape.c(), seg_begin, seg_end, _ptr(q, "q", bf, qs), _ptr(k, "k", bf, ks), _ptr(v, "v", bf, ks),
+        _ptr(d_o, "d_o", bf, qs), _ptr(o, "o", bf, qs), _ptr(lse, "lse", f32, (shape.Hq, T)),
+        _ptr(dq, "dq", bf, qs), _ptr(dk_acc, "dk_acc", f32, ks), _ptr(dv_acc, "dv_acc", f32, ks),
+        _ptr(dk_bf16, "dk_bf16", bf, ks), _ptr(dv_bf16, "dv_bf16", bf, ks),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_step_partitioned")

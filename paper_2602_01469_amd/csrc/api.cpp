@@ -1,0 +1,165 @@
+// C-ABI entry points: host-side validation and the sequence-partition driver (Sec. 3.2 of the
+// paper: one forward+backward pass per segment, dK/dV accumulated across segments in fp32).
+#include <climits>
+#include <cmath>
+
+#include "attn_kernels.h"
+#include "peagle.h"
+#include "tilemap.h"
+
+using peagle::BwdParams;
+using peagle::FwdParams;
+using peagle::SegRange;
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t delta_off, dk_off, dv_off, total;
+  int L64;
+};
+
+WsLayout ws_layout(const peagle_shape_t* s) {
+  WsLayout w;
+  w.L64 = (s->L + 63) / 64 * 64;
+  const size_t T = (size_t)s->L * s->K;
+  const size_t part = (size_t)s->Hq * w.L64 * s->D * sizeof(float);
+  w.delta_off = 0;
+  w.dk_off = align256(T * s->Hq * sizeof(float));
+  w.dv_off = w.dk_off + align256(part);
+  w.total = w.dv_off + align256(part);
+  return w;
+}
+
+int check_shape(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
+  if (!tm || !s) return PEAGLE_ENULL;
+  if (s->L < 1 || s->Hq < 1 || s->Hkv < 1 || s->K < 1) return PEAGLE_EINVAL;
+  if (s->Hq % s->Hkv != 0) return PEAGLE_EINVAL;
+  if (!(s->scale > 0.f) || !std::isfinite(s->scale)) return PEAGLE_EINVAL;
+  if (s->layout != PEAGLE_LAYOUT_DEPTH_MAJOR) return PEAGLE_EUNSUPPORTED;
+  if (s->D != 64 && s->D != 128) return PEAGLE_EUNSUPPORTED;
+  if (s->K != tm->K || s->L > tm->L_max) return PEAGLE_ESHAPE;
+  return PEAGLE_OK;
+}
+
+FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
+                   const void* k, const void* v, void* o, float* lse) {
+  FwdParams p{};
+  p.q = (const __bf16*)q;
+  p.k = (const __bf16*)k;
+  p.v = (const __bf16*)v;
+  p.o = (__bf16*)o;
+  p.lse = lse;
+  p.tm = tm->dview;
+  p.L = s->L;
+  p.T = s->L * s->K;
+  p.Hq = s->Hq;
+  p.Hkv = s->Hkv;
+  p.rt_lo = sr.rt_lo;
+  p.rt_hi = sr.rt_hi;
+  p.c_log2 = s->scale * 1.4426950408889634f;
+  return p;
+}
+
+BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
+                   const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
+                   float* dk_acc, float* dv_acc, void* workspace, int chain_accumulate) {
+  const WsLayout w = ws_layout(s);
+  BwdParams p{};
+  p.q = (const __bf16*)q;
+  p.k = (const __bf16*)k;
+  p.v = (const __bf16*)v;
+  p.o = (const __bf16*)o;
+  p.d_o = (const __bf16*)d_o;
+  p.lse = lse;
+  p.dq = (__bf16*)dq;
+  p.dk_acc = dk_acc;
+  p.dv_acc = dv_acc;
+  p.delta = (float*)((char*)workspace + w.delta_off);
+  p.dk_part = (float*)((char*)workspace + w.dk_off);
+  p.dv_part = (float*)((char*)workspace + w.dv_off);
+  p.tm = tm->dview;
+  p.L = s->L;
+  p.T = s->L * s->K;
+  p.Hq = s->Hq;
+  p.Hkv = s->Hkv;
+  p.L64 = w.L64;
+  p.rt_lo = sr.rt_lo;
+  p.rt_hi = sr.rt_hi;
+  p.chain_accumulate = chain_accumulate;
+  p.c_log2 = s->scale * 1.4426950408889634f;
+  p.scale = s->scale;
+  return p;
+}
+
+}  // namespace
+
+extern "C" size_t peagle_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape) {
+  if (check_shape(tm, shape) != PEAGLE_OK) return 0;
+  return ws_layout(shape).total;
+}
+
+extern "C" int peagle_attn_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg, const void* q,
+                               const void* k, const void* v, void* o, float* lse, void* stream) {
+  int rc = check_shape(tm, shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q || !k || !v || !o || !lse) return PEAGLE_ENULL;
+  SegRange sr;
+  rc = peagle::resolve_segment(tm, shape->L, seg, &sr);
+  if (rc != PEAGLE_OK) return rc;
+  if (tm->device < 0) return PEAGLE_ENODEVICE;
+  const FwdParams p = make_fwd(tm, shape, sr, q, k, v, o, lse);
+  return peagle::launch_fwd(p, shape->D, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+}
+
+extern "C" int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg, const void* q,
+                               const void* k, const void* v, const void* o, const void* d_o, const float* lse,
+                               void* dq, float* dk_acc, float* dv_acc, int32_t accumulate, void* workspace,
+                               size_t ws_bytes, void* stream) {
+  int rc = check_shape(tm, shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
+  if (accumulate != 0 && accumulate != 1) return PEAGLE_EINVAL;
+  SegRange sr;
+  rc = peagle::resolve_segment(tm, shape->L, seg, &sr);
+  if (rc != PEAGLE_OK) return rc;
+  if (!workspace || ws_bytes < ws_layout(shape).total) return PEAGLE_EWORKSPACE;
+  if (tm->device < 0) return PEAGLE_ENODEVICE;
+  const BwdParams p = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, accumulate);
+  const int acc_below = accumulate ? INT_MAX : 0;
+  return peagle::launch_bwd(p, shape->D, sr.a_hi, acc_below, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK
+                                                                                                   : PEAGLE_EHIP;
+}
+
+extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
+                                            int32_t seg_begin, int32_t seg_end, const void* q, const void* k,
+                                            const void* v, const void* d_o, void* o, float* lse, void* dq,
+                                            float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
+                                            void* workspace, size_t ws_bytes, void* stream) {
+  int rc = check_shape(tm, shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
+  if (seg_begin < 0 || seg_end > tm->S || seg_begin > seg_end) return PEAGLE_EINVAL;
+  if (!workspace || ws_bytes < ws_layout(shape).total) return PEAGLE_EWORKSPACE;
+  if (tm->device < 0) return PEAGLE_ENODEVICE;
+  hipStream_t st = (hipStream_t)stream;
+  for (int32_t s = seg_begin; s < seg_end; ++s) {
+    SegRange sr;
+    rc = peagle::resolve_segment(tm, shape->L, s, &sr);
+    if (rc != PEAGLE_OK) return rc;
+    if (sr.a_lo >= sr.a_hi) continue;  // segment lies beyond the cropped length
+    const FwdParams fp = make_fwd(tm, shape, sr, q, k, v, o, lse);
+    if (peagle::launch_fwd(fp, shape->D, st) != hipSuccess) return PEAGLE_EHIP;
+    // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
+    // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
+    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
+    if (peagle::launch_bwd(bp, shape->D, sr.a_hi, sr.a_lo, st) != hipSuccess) return PEAGLE_EHIP;
+  }
+  if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
+    const size_t n = (size_t)shape->L * shape->K * shape->Hkv * shape->D;
+    if (dk_bf16 && peagle::launch_cast_bf16(dk_acc, dk_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
+    if (dv_bf16 && peagle::launch_cast_bf16(dv_acc, dv_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
+  }
+  return PEAGLE_OK;
+}

@@ -1,0 +1,49 @@
+// Kernel parameter blocks and host launchers of the attention path.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "tilemap.h"
+
+namespace peagle {
+
+struct FwdParams {
+  const __bf16* q;
+  const __bf16* k;
+  const __bf16* v;
+  __bf16* o;
+  float* lse;          // [Hq, T]
+  DeviceTileMap tm;
+  int L, T, Hq, Hkv;
+  int rt_lo, rt_hi;    // row tiles of the segment
+  float c_log2;        // softmax scale * log2(e)
+};
+
+struct BwdParams {
+  const __bf16* q;
+  const __bf16* k;
+  const __bf16* v;
+  const __bf16* o;
+  const __bf16* d_o;
+  const float* lse;    // [Hq, T]
+  __bf16* dq;
+  float* dk_acc;       // [T, Hkv, D]
+  float* dv_acc;
+  float* delta;        // workspace [Hq, T]
+  float* dk_part;      // workspace [Hq, L64, D]: per-query-head dK of the depth-0 keys
+  float* dv_part;
+  DeviceTileMap tm;
+  int L, T, Hq, Hkv, L64;
+  int rt_lo, rt_hi;
+  int n_d0_items;       // filled by the launcher
+  int chain_accumulate; // chain keys: add to dk_acc/dv_acc instead of overwriting
+  float c_log2, scale;
+};
+
+hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream);
+// a_hi: end anchor of the segment (depth-0 keys [0, a_hi) are visible); depth-0 keys with anchor
+// below acc_below are added to dk_acc/dv_acc, the others overwritten.
+hipError_t launch_bwd(const BwdParams& p, int D, int a_hi, int acc_below, hipStream_t stream);
+hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t stream);
+
+}  // namespace peagle

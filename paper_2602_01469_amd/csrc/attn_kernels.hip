@@ -1,0 +1,742 @@
+// Block-sparse flash attention forward / backward for the parallel-prediction mask (Sec. 3 of
+// the paper), gfx950 only.  Work is organised by the tile map: a row tile is A anchors at all K
+// depths (128 rows), key tiles are 64 wide; full pairs skip masking, partial pairs apply a
+// bitmask from the pool, empty pairs are never listed.
+//
+// All score matrices are produced transposed where that keeps the softmax reduction inside a
+// lane: in the forward and dQ kernels a lane owns one query row (S^T = K Q^T, lane <-> row,
+// registers <-> keys); in the dK/dV kernel a lane owns one key (S = Q K^T, lane <-> key,
+// registers <-> rows).  Operands whose contraction index is not contiguous in memory are read
+// from LDS with ds_read_b64_tr_b16.
+#include "attn_kernels.h"
+#include "mfma_util.h"
+
+namespace peagle {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRescaleThreshold = 8.0f;  // log2 units: the running reference max lags by at most 2^8
+constexpr float kNegInit = -1.0e30f;
+
+// Token (row of the [T, H, D] tensors) of key `row` of key tile `kt`; false if that key does not
+// exist in a length-L problem.
+__device__ __forceinline__ bool key_token(const DeviceTileMap& tm, int kt, int row, int L, int& tok) {
+  if (kt < tm.n_d0) {
+    tok = kt * kKeysPerTile + row;
+    return tok < L;
+  }
+  const int cid = kt - tm.n_d0;
+  const int R = cid / tm.n_csub;
+  const int ck = (cid - R * tm.n_csub) * kKeysPerTile + row;
+  const int e = ck / tm.A;
+  const int j = R * tm.A + (ck - e * tm.A);
+  tok = (1 + e) * L + j;
+  return ck < tm.A * (tm.K - 1) && j < L;
+}
+
+// Token of row `r` of row tile `rt`; false if the row is padding or beyond the sequence.
+__device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r, int L, int& tok) {
+  const int d = r / tm.A;
+  const int i = rt * tm.A + (r - d * tm.A);
+  tok = d * L + i;
+  return d < tm.K && i < L;
+}
+
+__device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+// Cooperative global -> register load of a (rows x D) bf16 tile, 16 bytes per thread per pass.
+template <int D, int ROWS, int NT>
+struct TileRegs {
+  static constexpr int kChunks = ROWS * D / 8;
+  static constexpr int kPasses = kChunks / NT;
+  static_assert(kChunks % NT == 0, "tile must split evenly over the workgroup");
+  uint4 v[kPasses];
+};
+
+template <int D, int ROWS, int NT>
+__device__ __forceinline__ void store_tile(char* lds, const TileRegs<D, ROWS, NT>& regs, int tid) {
+#pragma unroll
+  for (int p = 0; p < TileRegs<D, ROWS, NT>::kPasses; ++p) {
+    const int idx = tid + p * NT;
+    const int row = idx / (D / 8), ch = idx % (D / 8);
+    *reinterpret_cast<uint4*>(lds + tile_off<D>(row, ch)) = regs.v[p];
+  }
+}
+
+template <int D, int NT>
+__device__ __forceinline__ void load_key_tile(TileRegs<D, kKeysPerTile, NT>& regs, const __bf16* base, int Hkv,
+                                              int kvh, const DeviceTileMap& tm, int kt, int L, int tid) {
+#pragma unroll
+  for (int p = 0; p < TileRegs<D, kKeysPerTile, NT>::kPasses; ++p) {
+    const int idx = tid + p * NT;
+    const int row = idx / (D / 8), ch = idx % (D / 8);
+    int tok;
+    const bool ok = key_token(tm, kt, row, L, tok);
+    regs.v[p] = ok ? ld16(base + ((size_t)tok * Hkv + kvh) * D + ch * 8) : make_uint4(0, 0, 0, 0);
+  }
+}
+
+template <int D, int NT>
+__device__ __forceinline__ void load_row_tile(TileRegs<D, kRowsPerTile, NT>& regs, const __bf16* base, int Hq, int h,
+                                              const DeviceTileMap& tm, int rt, int L, int tid) {
+#pragma unroll
+  for (int p = 0; p < TileRegs<D, kRowsPerTile, NT>::kPasses; ++p) {
+    const int idx = tid + p * NT;
+    const int row = idx / (D / 8), ch = idx % (D / 8);
+    int tok;
+    const bool ok = row_token(tm, rt, row, L, tok);
+    regs.v[p] = ok ? ld16(base + ((size_t)tok * Hq + h) * D + ch * 8) : make_uint4(0, 0, 0, 0);
+  }
+}
+
+// Bit `pos` of w selects x, otherwise -inf.
+__device__ __forceinline__ float mask_sel(float x, uint32_t w, int pos) {
+  return ((w >> pos) & 1u) ? x : -__builtin_inff();
+}
+
+}  // namespace
+
+// =====================================================================================
+// Forward: O = softmax(scale Q K^T + mask) V, LSE.  One workgroup (4 waves) per
+// (row tile, NH query heads of one KV group); wave w owns rows [32w, 32w+32) of the tile.
+// =====================================================================================
+template <int D, int NH>
+__global__ __launch_bounds__(256) void fwd_kernel(FwdParams p) {
+  constexpr int NT = 256;
+  constexpr int kTileBytes = kKeysPerTile * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const DeviceTileMap& tm = p.tm;
+  const int group = p.Hq / p.Hkv;
+  const int hpg = group / NH;
+  int b = blockIdx.x;
+  const int kvh = b % p.Hkv;
+  b /= p.Hkv;
+  const int hc = b % hpg;
+  const int rt = p.rt_hi - 1 - b / hpg;  // heaviest row tiles first
+  const int h0 = kvh * group + hc * NH;
+
+  const int r = wave * 32 + ln;  // row of the tile owned by this lane (shared with lane^32)
+  int tq;
+  const bool row_ok = row_token(tm, rt, r, p.L, tq);
+
+  bf16x8 qf[NH][D / 16];
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st)
+      qf[hh][st] = as_frag(row_ok ? ld16(p.q + ((size_t)tq * p.Hq + h0 + hh) * D + st * 16 + g * 8)
+                                  : make_uint4(0, 0, 0, 0));
+
+  f32x16 o[NH][D / 32];
+  float m[NH], lsum[NH];
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh) {
+    m[hh] = kNegInit;
+    lsum[hh] = 0.f;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) o[hh][db] = zero16();
+  }
+
+  const TrLane tl = tr_lane(lane);
+  const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
+  TileRegs<D, kKeysPerTile, NT> kr, vr;
+  {
+    const int kt = tm.row_entries[e0].tile;
+    load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
+    load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
+  }
+  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, tid);
+  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, tid);
+  __syncthreads();
+
+  for (int e = e0; e < e1; ++e) {
+    const int buf = (e - e0) & 1;
+    if (e + 1 < e1) {
+      const int kt = tm.row_entries[e + 1].tile;
+      load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
+      load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
+    }
+    const int mask_id = tm.row_entries[e].mask_id;
+    const char* kt_lds = lds[buf][0];
+    const char* vt_lds = lds[buf][1];
+    uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+    if (mask_id >= 0) {
+      const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
+      mw[0] = w[0] >> (4 * g);
+      mw[1] = w[1] >> (4 * g);
+    }
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      // S^T block: 32 keys x 32 rows, lane <-> row, registers <-> keys 8*(i/4) + 4g + i%4
+      f32x16 s[NH];
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) s[hh] = zero16();
+#pragma unroll
+      for (int st = 0; st < D / 16; ++st) {
+        const bf16x8 a = frag_nat<D>(kt_lds, kb * 32 + ln, st, g);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) s[hh] = mfma32(a, qf[hh][st], s[hh]);
+      }
+      bf16x8 pb[NH][2];
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) {
+        if (mask_id >= 0) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[hh][i] = mask_sel(s[hh][i], mw[kb], 8 * (i / 4) + (i % 4));
+        }
+        float mx = s[hh][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = __builtin_fmaxf(mx, s[hh][i]);
+        mx = __builtin_fmaxf(mx, other_half(mx)) * p.c_log2;
+        // Lazy reference max: move it only when the block exceeds it by more than the threshold.
+        const bool need = mx > m[hh] + kRescaleThreshold;
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+          const float m_new = need ? mx : m[hh];
+          const float alpha = exp2_fast(m[hh] - m_new);
+          m[hh] = m_new;
+          lsum[hh] *= alpha;
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[hh][db][i] *= alpha;
+        }
+        const float mref = m[hh];
+        float ls = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          s[hh][i] = exp2_fast(__builtin_fmaf(s[hh][i], p.c_log2, -mref));
+          ls += s[hh][i];
+        }
+        lsum[hh] += ls;
+        pb[hh][0] = pack8(s[hh], 0);
+        pb[hh][1] = pack8(s[hh], 1);
+      }
+      // O^T += V^T P^T : A = V^T (lane <-> d, contraction over the block's 32 keys)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 a = frag_tr<D>(vt_lds, kb * 32 + t * 16, db * 32, tl);
+#pragma unroll
+          for (int hh = 0; hh < NH; ++hh) o[hh][db] = mfma32(a, pb[hh][t], o[hh][db]);
+        }
+    }
+
+    if (e + 1 < e1) {
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, tid);
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, tid);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh) {
+    const float l_tot = lsum[hh] + other_half(lsum[hh]);
+    const float inv = 1.0f / l_tot;
+    if (row_ok) {
+      __bf16* orow = p.o + ((size_t)tq * p.Hq + h0 + hh) * D;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = pack_bf16(o[hh][db][4 * q4 + 0] * inv, o[hh][db][4 * q4 + 1] * inv);
+          w[1] = pack_bf16(o[hh][db][4 * q4 + 2] * inv, o[hh][db][4 * q4 + 3] * inv);
+          *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * g) = w;
+        }
+      if (g == 0) p.lse[(size_t)(h0 + hh) * p.T + tq] = (m[hh] + __builtin_log2f(l_tot)) * kLn2;
+    }
+  }
+}
+
+// =====================================================================================
+// Backward, part 1: Delta = rowsum(dO * O) and dQ = scale * dS K, row-tile owned (same
+// decomposition as the forward).  Writes Delta [Hq, T] for part 2.
+// =====================================================================================
+template <int D, int NH>
+__global__ __launch_bounds__(256) void dq_kernel(BwdParams p) {
+  constexpr int NT = 256;
+  constexpr int kTileBytes = kKeysPerTile * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const DeviceTileMap& tm = p.tm;
+  const int group = p.Hq / p.Hkv;
+  const int hpg = group / NH;
+  int b = blockIdx.x;
+  const int kvh = b % p.Hkv;
+  b /= p.Hkv;
+  const int hc = b % hpg;
+  const int rt = p.rt_hi - 1 - b / hpg;
+  const int h0 = kvh * group + hc * NH;
+
+  const int r = wave * 32 + ln;
+  int tq;
+  const bool row_ok = row_token(tm, rt, r, p.L, tq);
+
+  bf16x8 qf[NH][D / 16], dof[NH][D / 16];
+  float lse2[NH], delta[NH];
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh) {
+    const size_t off = ((size_t)tq * p.Hq + h0 + hh) * D + g * 8;
+    float dl = 0.f;
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      qf[hh][st] = as_frag(row_ok ? ld16(p.q + off + st * 16) : z);
+      dof[hh][st] = as_frag(row_ok ? ld16(p.d_o + off + st * 16) : z);
+      const bf16x8 of = as_frag(row_ok ? ld16(p.o + off + st * 16) : z);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dl = __builtin_fmaf((float)dof[hh][st][j], (float)of[j], dl);
+    }
+    dl += other_half(dl);
+    delta[hh] = dl;
+    lse2[hh] = row_ok ? p.lse[(size_t)(h0 + hh) * p.T + tq] * kLog2e : 0.f;
+    if (row_ok && g == 0) p.delta[(size_t)(h0 + hh) * p.T + tq] = dl;
+  }
+
+  f32x16 dq[NH][D / 32];
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) dq[hh][db] = zero16();
+
+  const TrLane tl = tr_lane(lane);
+  const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
+  TileRegs<D, kKeysPerTile, NT> kr, vr;
+  {
+    const int kt = tm.row_entries[e0].tile;
+    load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
+    load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
+  }
+  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, tid);
+  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, tid);
+  __syncthreads();
+
+  for (int e = e0; e < e1; ++e) {
+    const int buf = (e - e0) & 1;
+    if (e + 1 < e1) {
+      const int kt = tm.row_entries[e + 1].tile;
+      load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
+      load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
+    }
+    const int mask_id = tm.row_entries[e].mask_id;
+    const char* kt_lds = lds[buf][0];
+    const char* vt_lds = lds[buf][1];
+    uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+    if (mask_id >= 0) {
+      const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
+      mw[0] = w[0] >> (4 * g);
+      mw[1] = w[1] >> (4 * g);
+    }
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 s[NH], dp[NH];
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) {
+        s[hh] = zero16();
+        dp[hh] = zero16();
+      }
+#pragma unroll
+      for (int st = 0; st < D / 16; ++st) {
+        const bf16x8 ak = frag_nat<D>(kt_lds, kb * 32 + ln, st, g);
+        const bf16x8 av = frag_nat<D>(vt_lds, kb * 32 + ln, st, g);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+          s[hh] = mfma32(ak, qf[hh][st], s[hh]);     // S^T  = K Q^T
+          dp[hh] = mfma32(av, dof[hh][st], dp[hh]);  // dP^T = V dO^T
+        }
+      }
+      bf16x8 dsb[NH][2];
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) {
+        if (mask_id >= 0) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[hh][i] = mask_sel(s[hh][i], mw[kb], 8 * (i / 4) + (i % 4));
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float pr = exp2_fast(__builtin_fmaf(s[hh][i], p.c_log2, -lse2[hh]));
+          s[hh][i] = pr * (dp[hh][i] - delta[hh]);
+        }
+        dsb[hh][0] = pack8(s[hh], 0);
+        dsb[hh][1] = pack8(s[hh], 1);
+      }
+      // dQ^T += K^T dS^T : A = K^T (lane <-> d, contraction over the block's keys)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 a = frag_tr<D>(kt_lds, kb * 32 + t * 16, db * 32, tl);
+#pragma unroll
+          for (int hh = 0; hh < NH; ++hh) dq[hh][db] = mfma32(a, dsb[hh][t], dq[hh][db]);
+        }
+    }
+
+    if (e + 1 < e1) {
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, tid);
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, tid);
+    }
+    __syncthreads();
+  }
+
+  if (row_ok) {
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      __bf16* drow = p.dq + ((size_t)tq * p.Hq + h0 + hh) * D;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = pack_bf16(dq[hh][db][4 * q4 + 0] * p.scale, dq[hh][db][4 * q4 + 1] * p.scale);
+          w[1] = pack_bf16(dq[hh][db][4 * q4 + 2] * p.scale, dq[hh][db][4 * q4 + 3] * p.scale);
+          *reinterpret_cast<u32x2*>(drow + db * 32 + 8 * q4 + 4 * g) = w;
+        }
+    }
+  }
+}
+
+// =====================================================================================
+// Backward, part 2: dK, dV, key-tile owned.  A workgroup holds one key tile (64 keys) of one
+// KV head in registers and loops over the row tiles that see it (clipped to the segment) for
+// the query heads [h_lo, h_hi) assigned to it.  Wave w owns rows [32w, 32w+32) of each row tile;
+// the four waves' partial dK^T / dV^T are summed through LDS at the end.
+//   depth-0 key tiles: one query head per workgroup, result to the per-head partial buffer;
+//   chain key tiles:   all heads of the KV group, result straight to dk_acc / dv_acc.
+// =====================================================================================
+template <int D>
+__global__ __launch_bounds__(256) void dkdv_kernel(BwdParams p) {
+  constexpr int NT = 256;
+  constexpr int kTileBytes = kRowsPerTile * D * 2;
+  constexpr int kBufBytes = 2 * kTileBytes + 2 * kRowsPerTile * 4;  // Q | dO | lse2 | delta
+  constexpr int kRedStride = D + 4;                                  // floats per key row in the reduction buffer
+  constexpr int kRedBytes = 4 * kKeysPerTile * kRedStride * 4;
+  constexpr int kLdsBytes = 2 * kBufBytes > kRedBytes ? 2 * kBufBytes : kRedBytes;
+  __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const DeviceTileMap& tm = p.tm;
+  const int group = p.Hq / p.Hkv;
+
+  int b = blockIdx.x;
+  int kt, kvh, h_lo, h_hi;
+  const bool chain = b >= p.n_d0_items;
+  if (!chain) {
+    kvh = b % p.Hkv;
+    b /= p.Hkv;
+    h_lo = kvh * group + b % group;
+    h_hi = h_lo + 1;
+    kt = b / group;  // low key tiles are seen by the most rows: heaviest first
+  } else {
+    b -= p.n_d0_items;
+    kvh = b % p.Hkv;
+    b /= p.Hkv;
+    kt = tm.n_d0 + (p.rt_lo + b / tm.n_csub) * tm.n_csub + b % tm.n_csub;
+    h_lo = kvh * group;
+    h_hi = h_lo + group;
+  }
+
+  // row tiles that see this key tile, clipped to [rt_lo, rt_hi): entries are ascending in row tile
+  int e_lo = tm.key_ptr[kt], e_hi = tm.key_ptr[kt + 1];
+  {
+    int lo = e_lo, hi = e_hi;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (tm.key_entries[mid].tile < p.rt_lo) lo = mid + 1; else hi = mid;
+    }
+    e_lo = lo;
+    hi = e_hi;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (tm.key_entries[mid].tile < p.rt_hi) lo = mid + 1; else hi = mid;
+    }
+    e_hi = lo;
+  }
+  const int n_rows_tiles = e_hi - e_lo;
+  const int n_iter = n_rows_tiles * (h_hi - h_lo);
+
+  // stationary K, V: B operands (lane <-> key, registers <-> d)
+  bf16x8 kf[2][D / 16], vf[2][D / 16];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    int tok;
+    const bool ok = key_token(tm, kt, kb * 32 + ln, p.L, tok);
+    const size_t off = ((size_t)tok * p.Hkv + kvh) * D + g * 8;
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      kf[kb][st] = as_frag(ok ? ld16(p.k + off + st * 16) : z);
+      vf[kb][st] = as_frag(ok ? ld16(p.v + off + st * 16) : z);
+    }
+  }
+
+  f32x16 dk[2][D / 32], dv[2][D / 32];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      dk[kb][db] = zero16();
+      dv[kb][db] = zero16();
+    }
+
+  const TrLane tl = tr_lane(lane);
+  TileRegs<D, kRowsPerTile, NT> qr, dor;
+  float lse_r = 0.f, delta_r = 0.f;  // threads 0..127 stage one row's statistics each
+
+  auto issue = [&](int it) {
+    const int hh = h_lo + it / n_rows_tiles;
+    const int rt = tm.key_entries[e_lo + it % n_rows_tiles].tile;
+    load_row_tile<D, NT>(qr, p.q, p.Hq, hh, tm, rt, p.L, tid);
+    load_row_tile<D, NT>(dor, p.d_o, p.Hq, hh, tm, rt, p.L, tid);
+    if (tid < kRowsPerTile) {
+      int tok;
+      const bool ok = row_token(tm, rt, tid, p.L, tok);
+      lse_r = ok ? p.lse[(size_t)hh * p.T + tok] * kLog2e : 0.f;
+      delta_r = ok ? p.delta[(size_t)hh * p.T + tok] : 0.f;
+    }
+  };
+  auto stage = [&](int buf) {
+    char* base = lds + buf * kBufBytes;
+    store_tile<D, kRowsPerTile, NT>(base, qr, tid);
+    store_tile<D, kRowsPerTile, NT>(base + kTileBytes, dor, tid);
+    if (tid < kRowsPerTile) {
+      reinterpret_cast<float*>(base + 2 * kTileBytes)[tid] = lse_r;
+      reinterpret_cast<float*>(base + 2 * kTileBytes + kRowsPerTile * 4)[tid] = delta_r;
+    }
+  };
+
+  if (n_iter > 0) {
+    issue(0);
+    stage(0);
+  }
+  __syncthreads();
+
+  for (int it = 0; it < n_iter; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < n_iter) issue(it + 1);
+    const int mask_id = tm.key_entries[e_lo + it % n_rows_tiles].mask_id;
+    const char* q_lds = lds + buf * kBufBytes;
+    const char* do_lds = q_lds + kTileBytes;
+    const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * kTileBytes);
+    const float* delta_lds = lse_lds + kRowsPerTile;
+    const int r0 = wave * 32;
+
+    // S = Q K^T and dP = dO V^T: lane <-> key, registers <-> rows r0 + 8*(i/4) + 4g + i%4
+    f32x16 s[2], dp[2];
+    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const bf16x8 aq = frag_nat<D>(q_lds, r0 + ln, st, g);
+      const bf16x8 ad = frag_nat<D>(do_lds, r0 + ln, st, g);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        s[kb] = mfma32(aq, kf[kb][st], s[kb]);
+        dp[kb] = mfma32(ad, vf[kb][st], dp[kb]);
+      }
+    }
+    float lse2[16], dl[16];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(lse_lds + r0 + 8 * q4 + 4 * g);
+      const f32x4 c = *reinterpret_cast<const f32x4*>(delta_lds + r0 + 8 * q4 + 4 * g);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lse2[4 * q4 + j] = a[j];
+        dl[4 * q4 + j] = c[j];
+      }
+    }
+    if (mask_id >= 0) {
+      const uint32_t* mrow = tm.masks + ((size_t)mask_id * kRowsPerTile + r0) * 2;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const u32x2 w = *reinterpret_cast<const u32x2*>(mrow + (8 * (i / 4) + 4 * g + (i % 4)) * 2);
+        s[0][i] = mask_sel(s[0][i], w[0], ln);
+        s[1][i] = mask_sel(s[1][i], w[1], ln);
+      }
+    }
+    bf16x8 pb[2][2], dsb[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pr = exp2_fast(__builtin_fmaf(s[kb][i], p.c_log2, -lse2[i]));
+        s[kb][i] = pr;
+        dp[kb][i] = pr * (dp[kb][i] - dl[i]);
+      }
+      pb[kb][0] = pack8(s[kb], 0);
+      pb[kb][1] = pack8(s[kb], 1);
+      dsb[kb][0] = pack8(dp[kb], 0);
+      dsb[kb][1] = pack8(dp[kb], 1);
+    }
+    // dV^T += dO^T P, dK^T += Q^T dS : A operands transposed from LDS (lane <-> d, contraction over rows)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 adt = frag_tr<D>(do_lds, r0 + t * 16, db * 32, tl);
+        const bf16x8 aqt = frag_tr<D>(q_lds, r0 + t * 16, db * 32, tl);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          dv[kb][db] = mfma32(adt, pb[kb][t], dv[kb][db]);
+          dk[kb][db] = mfma32(aqt, dsb[kb][t], dk[kb][db]);
+        }
+      }
+
+    if (it + 1 < n_iter) stage(buf ^ 1);
+    __syncthreads();
+  }
+
+  // cross-wave sum through LDS, then one owner thread per 16-byte piece writes the result
+  float* red = reinterpret_cast<float*>(lds);
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x16& acc = which == 0 ? dk[kb][db] : dv[kb][db];
+          f32x4 x;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) x[j] = acc[4 * q4 + j];
+          *reinterpret_cast<f32x4*>(red + ((size_t)wave * kKeysPerTile + kb * 32 + ln) * kRedStride + db * 32 + 8 * q4 + 4 * g) = x;
+        }
+    __syncthreads();
+    const float mul = which == 0 ? p.scale : 1.0f;
+    for (int idx = tid; idx < kKeysPerTile * (D / 4); idx += NT) {
+      const int key = idx / (D / 4), c4 = idx % (D / 4);
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) sum += *reinterpret_cast<const f32x4*>(red + ((size_t)w * kKeysPerTile + key) * kRedStride + c4 * 4);
+      sum *= mul;
+      if (!chain) {
+        float* dst = (which == 0 ? p.dk_part : p.dv_part) + (((size_t)h_lo * p.L64 + (size_t)kt * kKeysPerTile + key) * D + c4 * 4);
+        *reinterpret_cast<f32x4*>(dst) = sum;
+      } else {
+        int tok;
+        if (key_token(tm, kt, key, p.L, tok)) {
+          float* dst = (which == 0 ? p.dk_acc : p.dv_acc) + (((size_t)tok * p.Hkv + kvh) * D + c4 * 4);
+          if (p.chain_accumulate) sum += *reinterpret_cast<const f32x4*>(dst);
+          *reinterpret_cast<f32x4*>(dst) = sum;
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Sum the per-head partials of the depth-0 keys [0, n_keys) over each KV group into dk_acc /
+// dv_acc; keys with anchor < acc_below are added to, the others overwritten.
+template <int D>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(BwdParams p, int n_keys, int acc_below) {
+  const int group = p.Hq / p.Hkv;
+  const size_t per = (size_t)n_keys * p.Hkv * (D / 4);
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < 2 * per; idx += (size_t)gridDim.x * blockDim.x) {
+    const int which = idx >= per;
+    size_t rem = which ? idx - per : idx;
+    const int c4 = rem % (D / 4);
+    rem /= (D / 4);
+    const int kvh = rem % p.Hkv;
+    const int j = (int)(rem / p.Hkv);
+    const float* part = which ? p.dv_part : p.dk_part;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int hh = 0; hh < group; ++hh)
+      sum += *reinterpret_cast<const f32x4*>(part + (((size_t)(kvh * group + hh) * p.L64 + j) * D + c4 * 4));
+    float* dst = (which ? p.dv_acc : p.dk_acc) + (((size_t)j * p.Hkv + kvh) * D + c4 * 4);
+    if (j < acc_below) sum += *reinterpret_cast<const f32x4*>(dst);
+    *reinterpret_cast<f32x4*>(dst) = sum;
+  }
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* src, __bf16* dst, size_t n4) {
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n4; idx += (size_t)gridDim.x * blockDim.x) {
+    const f32x4 x = *reinterpret_cast<const f32x4*>(src + idx * 4);
+    u32x2 w;
+    w[0] = pack_bf16(x[0], x[1]);
+    w[1] = pack_bf16(x[2], x[3]);
+    *reinterpret_cast<u32x2*>(dst + idx * 4) = w;
+  }
+}
+
+// ------------------------------------------------------------------------------------- launchers
+
+namespace {
+inline int pick_nh(int group) { return group % 2 == 0 ? 2 : 1; }
+}  // namespace
+
+hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream) {
+  const int n_rt = p.rt_hi - p.rt_lo;
+  if (n_rt <= 0) return hipSuccess;
+  const int group = p.Hq / p.Hkv;
+  const int nh = pick_nh(group);
+  const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
+  if (D == 64) {
+    if (nh == 2) hipLaunchKernelGGL((fwd_kernel<64, 2>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((fwd_kernel<64, 1>), grid, block, 0, stream, p);
+  } else {
+    if (nh == 2) hipLaunchKernelGGL((fwd_kernel<128, 2>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((fwd_kernel<128, 1>), grid, block, 0, stream, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipStream_t stream) {
+  BwdParams p = pin;
+  const int n_rt = p.rt_hi - p.rt_lo;
+  if (n_rt <= 0) return hipSuccess;
+  const int group = p.Hq / p.Hkv;
+  const int nh = pick_nh(group);
+  {
+    const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
+    if (D == 64) {
+      if (nh == 2) hipLaunchKernelGGL((dq_kernel<64, 2>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((dq_kernel<64, 1>), grid, block, 0, stream, p);
+    } else {
+      if (nh == 2) hipLaunchKernelGGL((dq_kernel<128, 2>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((dq_kernel<128, 1>), grid, block, 0, stream, p);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi
+  p.n_d0_items = n_d0_tiles * p.Hq;
+  const int n_chain_items = n_rt * p.tm.n_csub * p.Hkv;
+  {
+    const dim3 grid((unsigned)(p.n_d0_items + n_chain_items)), block(256);
+    if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((dkdv_kernel<128>), grid, block, 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  {
+    const size_t n = 2 * (size_t)a_hi * p.Hkv * (D / 4);
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    const dim3 grid((unsigned)blocks), block(256);
+    if (D == 64) hipLaunchKernelGGL((reduce_partials_kernel<64>), grid, block, 0, stream, p, a_hi, acc_below);
+    else hipLaunchKernelGGL((reduce_partials_kernel<128>), grid, block, 0, stream, p, a_hi, acc_below);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_cast_bf16(const float* src, void* dst, size_t n, hipStream_t stream) {
+  const size_t n4 = n / 4;
+  if (n4 == 0) return hipSuccess;
+  size_t blocks = (n4 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, (__bf16*)dst, n4);
+  return hipGetLastError();
+}
+
+}  // namespace peagle

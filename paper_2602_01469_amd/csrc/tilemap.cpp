@@ -1,0 +1,318 @@
+// Mask -> tile map (amortized mask construction, Sec. 3.1 of the paper; segment boundaries of
+// Sec. 3.2).  Host code only, apart from the one upload of the finished map.
+//
+// The builder never touches the O((nK)^2) element mask: every (row tile, key tile) pair is
+// classified with interval tests, and only the O(1) distinct partial patterns are expanded
+// element by element (from the visibility rule) into the de-duplicated mask pool.
+#include "tilemap.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <new>
+
+using peagle::kKeysPerTile;
+using peagle::kMaskWords;
+using peagle::kMaskWordsPerRow;
+using peagle::kRowsPerTile;
+using peagle::TileEntry;
+
+namespace {
+
+// Visibility rule of the parallel-prediction mask in anchor coordinates (Sec. 3; Sec. 3.2,
+// dependency of (p, d) on (p-1, d-1)): depth-0 keys are causal in the anchor, keys of depth
+// e >= 1 are visible only on the row's own anchor and only up to the row's depth.
+inline bool sees(int64_t i, int d, int64_t j, int e) {
+  return e == 0 ? (j <= i) : (j == i && e <= d);
+}
+
+struct MaskPool {
+  std::map<std::vector<uint32_t>, int32_t> index;
+  std::vector<uint32_t>* storage;
+  int32_t intern(const std::vector<uint32_t>& bits) {
+    auto it = index.find(bits);
+    if (it != index.end()) return it->second;
+    int32_t id = (int32_t)index.size();
+    index.emplace(bits, id);
+    storage->insert(storage->end(), bits.begin(), bits.end());
+    return id;
+  }
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg_bounds, int32_t S, int32_t device,
+                                    peagle_tilemap_t** out) {
+  if (!out) return PEAGLE_ENULL;
+  *out = nullptr;
+  if (L_max < 1 || S < 1 || K < 1) return PEAGLE_EINVAL;
+  if (K > kRowsPerTile) return PEAGLE_EUNSUPPORTED;
+  if ((int64_t)L_max * K > (int64_t)1 << 30) return PEAGLE_EUNSUPPORTED;
+  if (!seg_bounds && S != 1) return PEAGLE_ENULL;
+  const int32_t A = kRowsPerTile / K;
+
+  peagle_tilemap* tm = new (std::nothrow) peagle_tilemap();
+  if (!tm) return PEAGLE_EINVAL;
+  tm->L_max = L_max;
+  tm->K = K;
+  tm->S = S;
+  tm->A = A;
+  if (seg_bounds) {
+    tm->seg_bounds.assign(seg_bounds, seg_bounds + S + 1);
+  } else {
+    tm->seg_bounds = {0, L_max};
+  }
+  const std::vector<int32_t>& b = tm->seg_bounds;
+  bool ok = b[0] == 0 && b[S] == L_max;
+  for (int s = 0; s < S && ok; ++s) ok = b[s] < b[s + 1];
+  for (int s = 1; s < S && ok; ++s) ok = (b[s] % A) == 0;
+  if (!ok) {
+    delete tm;
+    return PEAGLE_EBOUNDS;
+  }
+
+  tm->n_row_tiles = (L_max + A - 1) / A;
+  tm->n_d0 = (L_max + kKeysPerTile - 1) / kKeysPerTile;
+  const int32_t chain_keys = A * (K - 1);
+  tm->n_csub = (chain_keys + kKeysPerTile - 1) / kKeysPerTile;
+  const int64_t n_kt = (int64_t)tm->n_d0 + (int64_t)tm->n_row_tiles * tm->n_csub;
+  if (n_kt > (int64_t)1 << 30) {
+    delete tm;
+    return PEAGLE_EUNSUPPORTED;
+  }
+  tm->n_key_tiles = (int32_t)n_kt;
+
+  MaskPool pool;
+  pool.storage = &tm->masks;
+  std::vector<uint32_t> bits(kMaskWords);
+  const int rows_used = A * K;
+
+  tm->row_ptr.assign(tm->n_row_tiles + 1, 0);
+  std::vector<int32_t> key_count(tm->n_key_tiles, 0);
+  for (int32_t R = 0; R < tm->n_row_tiles; ++R) {
+    const int64_t i0 = (int64_t)R * A;        // first anchor of the row tile
+    const int64_t i1 = i0 + A - 1;            // last anchor (position-invariant: not clipped to L_max)
+    // depth-0 stream: key tile c holds anchors [64c, 64c+63]
+    for (int32_t c = 0; c < tm->n_d0; ++c) {
+      const int64_t j0 = (int64_t)c * kKeysPerTile, j1 = j0 + kKeysPerTile - 1;
+      if (j0 > i1) break;                     // every key is in the future of every row: empty
+      TileEntry en{c, -1};
+      if (j1 <= i0) {                         // every key is visible to every row: full
+        ++tm->n_full;
+      } else {
+        std::fill(bits.begin(), bits.end(), 0u);
+        for (int r = 0; r < rows_used; ++r) {
+          const int d = r / A;
+          const int64_t i = i0 + r % A;
+          for (int kk = 0; kk < kKeysPerTile; ++kk)
+            if (sees(i, d, j0 + kk, 0)) bits[r * kMaskWordsPerRow + kk / 32] |= 1u << (kk % 32);
+        }
+        en.mask_id = pool.intern(bits);
+        ++tm->n_partial;
+      }
+      tm->row_entries.push_back(en);
+      ++key_count[c];
+    }
+    // chain stream: key kk of the stream is depth 1 + kk/A, anchor i0 + kk%A
+    for (int32_t s = 0; s < tm->n_csub; ++s) {
+      std::fill(bits.begin(), bits.end(), 0u);
+      bool any = false;
+      for (int r = 0; r < rows_used; ++r) {
+        const int d = r / A;
+        const int64_t i = i0 + r % A;
+        for (int kk = 0; kk < kKeysPerTile; ++kk) {
+          const int ck = s * kKeysPerTile + kk;
+          if (ck >= chain_keys) break;
+          if (sees(i, d, i0 + ck % A, 1 + ck / A)) {
+            bits[r * kMaskWordsPerRow + kk / 32] |= 1u << (kk % 32);
+            any = true;
+          }
+        }
+      }
+      if (!any) continue;
+      const int32_t kt = tm->n_d0 + R * tm->n_csub + s;
+      tm->row_entries.push_back(TileEntry{kt, pool.intern(bits)});
+      ++tm->n_partial;
+      ++key_count[kt];
+    }
+    tm->row_ptr[R + 1] = (int32_t)tm->row_entries.size();
+  }
+  tm->n_masks = (int32_t)pool.index.size();
+
+  // key tile -> row tiles (ascending), same mask ids
+  tm->key_ptr.assign(tm->n_key_tiles + 1, 0);
+  for (int32_t t = 0; t < tm->n_key_tiles; ++t) tm->key_ptr[t + 1] = tm->key_ptr[t] + key_count[t];
+  tm->key_entries.resize(tm->row_entries.size());
+  std::vector<int32_t> fill(tm->key_ptr.begin(), tm->key_ptr.end() - 1);
+  for (int32_t R = 0; R < tm->n_row_tiles; ++R)
+    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
+      const TileEntry& en = tm->row_entries[e];
+      tm->key_entries[fill[en.tile]++] = TileEntry{R, en.mask_id};
+    }
+
+  tm->device = device;
+  if (device >= 0) {
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) {
+      delete tm;
+      return PEAGLE_EHIP;
+    }
+    const size_t sz[5] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
+                          tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
+                          tm->masks.size() * sizeof(uint32_t)};
+    const void* src[5] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(), tm->key_entries.data(),
+                          tm->masks.data()};
+    size_t off[5], total = 0;
+    for (int i = 0; i < 5; ++i) {
+      off[i] = total;
+      total += align256(sz[i] ? sz[i] : 4);
+    }
+    hipError_t err = hipMalloc(&tm->dev_blob, total);
+    for (int i = 0; i < 5 && err == hipSuccess; ++i)
+      if (sz[i]) err = hipMemcpy((char*)tm->dev_blob + off[i], src[i], sz[i], hipMemcpyHostToDevice);
+    if (err == hipSuccess) err = hipDeviceSynchronize();
+    (void)hipSetDevice(prev);
+    if (err != hipSuccess) {
+      if (tm->dev_blob) (void)hipFree(tm->dev_blob);
+      delete tm;
+      return PEAGLE_EHIP;
+    }
+    tm->dev_bytes = (int64_t)total;
+    char* base = (char*)tm->dev_blob;
+    tm->dview.row_ptr = (const int32_t*)(base + off[0]);
+    tm->dview.row_entries = (const TileEntry*)(base + off[1]);
+    tm->dview.key_ptr = (const int32_t*)(base + off[2]);
+    tm->dview.key_entries = (const TileEntry*)(base + off[3]);
+    tm->dview.masks = (const uint32_t*)(base + off[4]);
+    tm->dview.A = A;
+    tm->dview.K = K;
+    tm->dview.n_row_tiles = tm->n_row_tiles;
+    tm->dview.n_d0 = tm->n_d0;
+    tm->dview.n_csub = tm->n_csub;
+    tm->dview.n_key_tiles = tm->n_key_tiles;
+  }
+  *out = tm;
+  return PEAGLE_OK;
+}
+
+extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
+  if (!tm) return;
+  if (tm->dev_blob) {
+    int prev = -1;
+    if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(tm->device) == hipSuccess) {
+      (void)hipFree(tm->dev_blob);
+      (void)hipSetDevice(prev);
+    }
+  }
+  delete tm;
+}
+
+extern "C" int peagle_tilemap_info(const peagle_tilemap_t* tm, peagle_tilemap_info_t* info) {
+  if (!tm || !info) return PEAGLE_ENULL;
+  info->L_max = tm->L_max;
+  info->K = tm->K;
+  info->S = tm->S;
+  info->anchors_per_row_tile = tm->A;
+  info->rows_per_tile = kRowsPerTile;
+  info->keys_per_tile = kKeysPerTile;
+  info->n_row_tiles = tm->n_row_tiles;
+  info->n_depth0_key_tiles = tm->n_d0;
+  info->n_chain_sub_tiles = tm->n_csub;
+  info->n_key_tiles = tm->n_key_tiles;
+  info->n_full = tm->n_full;
+  info->n_partial = tm->n_partial;
+  info->n_masks = tm->n_masks;
+  info->device_bytes = tm->dev_bytes;
+  return PEAGLE_OK;
+}
+
+int peagle::resolve_segment(const peagle_tilemap* tm, int32_t L, int32_t seg, SegRange* out) {
+  if (L < 1 || L > tm->L_max) return PEAGLE_ESHAPE;
+  if (seg < -1 || seg >= tm->S) return PEAGLE_EINVAL;
+  int32_t lo = 0, hi = L;
+  if (seg >= 0) {
+    lo = tm->seg_bounds[seg];
+    hi = tm->seg_bounds[seg + 1] < L ? tm->seg_bounds[seg + 1] : L;
+    if (lo > hi) lo = hi;  // segment lies beyond the cropped length: empty
+  }
+  out->a_lo = lo;
+  out->a_hi = hi;
+  out->rt_lo = lo / tm->A;
+  out->rt_hi = (hi + tm->A - 1) / tm->A;
+  if (lo == hi) out->rt_hi = out->rt_lo;
+  return PEAGLE_OK;
+}
+
+extern "C" int peagle_tilemap_expand_rows(const peagle_tilemap_t* tm, int32_t L, int32_t seg, int64_t row_begin,
+                                          int64_t row_end, uint8_t* bits_out) {
+  if (!tm || !bits_out) return PEAGLE_ENULL;
+  peagle::SegRange sr;
+  int rc = peagle::resolve_segment(tm, L, seg, &sr);
+  if (rc != PEAGLE_OK) return rc;
+  const int64_t T = (int64_t)L * tm->K;
+  if (row_begin < 0 || row_end < row_begin || row_end > T) return PEAGLE_EINVAL;
+  const int64_t row_bytes = (T + 7) / 8;
+  const int A = tm->A;
+  const int chain_keys = A * (tm->K - 1);
+  std::memset(bits_out, 0, (size_t)((row_end - row_begin) * row_bytes));
+  for (int64_t t = row_begin; t < row_end; ++t) {
+    const int64_t i = t % L;
+    const int d = (int)(t / L);
+    if (i < sr.a_lo || i >= sr.a_hi) continue;
+    uint8_t* dst = bits_out + (t - row_begin) * row_bytes;
+    const int32_t R = (int32_t)(i / A);
+    const int r = d * A + (int)(i % A);  // row inside the tile
+    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
+      const TileEntry& en = tm->row_entries[e];
+      const uint32_t* mw = en.mask_id < 0 ? nullptr : &tm->masks[(size_t)en.mask_id * kMaskWords + r * kMaskWordsPerRow];
+      for (int kk = 0; kk < kKeysPerTile; ++kk) {
+        if (mw && !((mw[kk / 32] >> (kk % 32)) & 1u)) continue;
+        int64_t tok;
+        if (en.tile < tm->n_d0) {
+          const int64_t j = (int64_t)en.tile * kKeysPerTile + kk;
+          if (j >= L) continue;
+          tok = j;
+        } else {
+          const int32_t cid = en.tile - tm->n_d0;
+          const int ck = (cid % tm->n_csub) * kKeysPerTile + kk;
+          if (ck >= chain_keys) continue;
+          const int64_t j = (int64_t)(cid / tm->n_csub) * A + ck % A;
+          if (j >= L) continue;
+          tok = (int64_t)(1 + ck / A) * L + j;
+        }
+        dst[tok >> 3] |= (uint8_t)(1u << (tok & 7));
+      }
+    }
+  }
+  return PEAGLE_OK;
+}
+
+extern "C" int peagle_tilemap_classes(const peagle_tilemap_t* tm, uint8_t* classes_out) {
+  if (!tm || !classes_out) return PEAGLE_ENULL;
+  const size_t n = (size_t)tm->n_row_tiles * tm->n_key_tiles;
+  std::memset(classes_out, PEAGLE_TILE_EMPTY, n);
+  for (int32_t R = 0; R < tm->n_row_tiles; ++R)
+    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
+      const TileEntry& en = tm->row_entries[e];
+      classes_out[(size_t)R * tm->n_key_tiles + en.tile] = en.mask_id < 0 ? PEAGLE_TILE_FULL : PEAGLE_TILE_PARTIAL;
+    }
+  return PEAGLE_OK;
+}
+
+extern "C" const char* peagle_strerror(int status) {
+  switch (status) {
+    case PEAGLE_OK: return "ok";
+    case PEAGLE_EINVAL: return "invalid argument";
+    case PEAGLE_ENULL: return "required pointer is NULL";
+    case PEAGLE_ESHAPE: return "shape does not fit the tile map (L > L_max or K mismatch)";
+    case PEAGLE_EBOUNDS: return "segment bounds must rise strictly from 0 to L_max with inner bounds multiples of 128/K";
+    case PEAGLE_EUNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128, K <= 128, depth-major layout)";
+    case PEAGLE_EWORKSPACE: return "workspace missing or too small";
+    case PEAGLE_EHIP: return "HIP runtime call failed";
+    case PEAGLE_ENODEVICE: return "tile map was built host-only";
+    default: return "unknown status";
+  }
+}

@@ -1,0 +1,62 @@
+// Internal representation of the tile map (host side) and the device view handed to kernels.
+//
+// Geometry (see include/peagle.h): a row tile is A = 128/K anchors at all K depths; key tiles are
+// 64 wide and come from two streams (depth-0 anchors, and the chain positions of a row tile's own
+// anchors).  The classification follows the parallel-prediction mask of Sec. 3 of the paper.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "peagle.h"
+
+namespace peagle {
+
+constexpr int kRowsPerTile = 128;
+constexpr int kKeysPerTile = 64;
+constexpr int kMaskWordsPerRow = kKeysPerTile / 32;                   // 2 x u32 per row
+constexpr int kMaskWords = kRowsPerTile * kMaskWordsPerRow;           // 256 x u32 = 1 KiB per mask
+
+struct TileEntry {
+  int32_t tile;     // key-tile id in the row-tile lists, row-tile id in the key-tile lists
+  int32_t mask_id;  // -1: every element of the pair is visible; else index into the mask pool
+};
+
+// Pointers into device memory; passed to kernels by value.
+struct DeviceTileMap {
+  const int32_t* row_ptr;     // [n_row_tiles + 1]  offsets into row_entries
+  const TileEntry* row_entries;
+  const int32_t* key_ptr;     // [n_key_tiles + 1]  offsets into key_entries (row tiles ascending)
+  const TileEntry* key_entries;
+  const uint32_t* masks;      // [n_masks][128][2]
+  int32_t A, K, n_row_tiles, n_d0, n_csub, n_key_tiles;
+};
+
+}  // namespace peagle
+
+struct peagle_tilemap {
+  int32_t L_max = 0, K = 0, S = 0, A = 0;
+  int32_t n_row_tiles = 0, n_d0 = 0, n_csub = 0, n_key_tiles = 0;
+  std::vector<int32_t> seg_bounds;               // [S+1] anchors
+  std::vector<int32_t> row_ptr;
+  std::vector<peagle::TileEntry> row_entries;
+  std::vector<int32_t> key_ptr;
+  std::vector<peagle::TileEntry> key_entries;
+  std::vector<uint32_t> masks;                   // n_masks * kMaskWords
+  int64_t n_full = 0, n_partial = 0;
+  int32_t n_masks = 0;
+  int32_t device = -1;
+  void* dev_blob = nullptr;                      // one allocation holding all device arrays
+  int64_t dev_bytes = 0;
+  peagle::DeviceTileMap dview{};
+};
+
+namespace peagle {
+
+// Anchor range [lo, hi) of a segment clipped to a length-L problem, and the row tiles covering it.
+struct SegRange {
+  int32_t a_lo, a_hi, rt_lo, rt_hi;
+};
+int resolve_segment(const peagle_tilemap* tm, int32_t L, int32_t seg, SegRange* out);
+
+}  // namespace peagle

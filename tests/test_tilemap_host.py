@@ -1,0 +1,211 @@
+"""Host-only tests (no GPU): the C-ABI library loads and exports every declared symbol, argument
+validation returns the documented codes, and the tile map expands bit-exactly to the oracle's
+element mask (parallel-prediction mask of Sec. 3; crop invariance of Sec. 3.1; segments of Sec. 3.2)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2602_01469_amd as pe
+from paper_2602_01469_amd import binding
+from oracle import peagle_oracle as orc
+from peagle_inputs import CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _expanded(tm, L, K, seg, rows):
+    """Element mask rows (bool [len(rows), T]) from the tile map, for sorted contiguous row blocks."""
+    T = L * K
+    out = np.zeros((len(rows), T), dtype=bool)
+    rows = np.asarray(rows)
+    # contiguous runs
+    starts = np.flatnonzero(np.diff(np.concatenate([[-2], rows])) != 1)
+    ends = np.concatenate([starts[1:], [len(rows)]])
+    for s, e in zip(starts, ends):
+        bits = tm.expand_rows(L, seg, int(rows[s]), int(rows[e - 1]) + 1)
+        out[s:e] = np.unpackbits(bits, axis=1, bitorder="little")[:, :T].astype(bool)
+    return out
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pe.load_library()
+    header = open(os.path.join(ROOT, "include", "peagle.h")).read()
+    declared = set(re.findall(r"\b(peagle_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("L,K", [(1, 1), (1, 8), (17, 4), (128, 4), (100, 8), (50, 3), (300, 1), (129, 5), (70, 16),
+                                 (40, 128), (333, 7)])
+def test_tilemap_expands_to_oracle_mask_bit_exact(L, K):
+    tm = pe.peagle_build_tilemap(L, K, None, device=-1)
+    T = L * K
+    got = _expanded(tm, L, K, -1, np.arange(T))
+    assert np.array_equal(got, orc.element_mask(L, K))
+    inf = tm.info()
+    assert inf["anchors_per_row_tile"] == 128 // K
+    assert inf["n_masks"] <= 2 * 64 + inf["n_chain_sub_tiles"]   # O(1): one per residue of the tile offset
+
+
+@pytest.mark.parametrize("L_max,L,K", [(256, 219, 8), (256, 1, 8), (256, 64, 4), (500, 333, 3), (512, 500, 1)])
+def test_crop_is_prefix_view(L_max, L, K):
+    """Per-example mask = crop of the maximum-length mask (Sec. 3.1): same tile map, shorter L."""
+    tm = pe.peagle_build_tilemap(L_max, K, None, device=-1)
+    got = _expanded(tm, L, K, -1, np.arange(L * K))
+    assert np.array_equal(got, orc.element_mask(L, K))
+
+
+def test_segments_partition_rows_and_union_is_full_mask():
+    L, K = 256, 8
+    bounds = [0, 64, 128, 256]
+    tm = pe.peagle_build_tilemap(L, K, bounds, device=-1)
+    T = L * K
+    full = orc.element_mask(L, K)
+    union = np.zeros((T, T), dtype=bool)
+    for s in range(3):
+        got = _expanded(tm, L, K, s, np.arange(T))
+        rows = orc.segment_rows(L, K, bounds[s], bounds[s + 1])
+        cols = orc.segment_keys(L, K, bounds[s], bounds[s + 1])
+        other = np.setdiff1d(np.arange(T), rows)
+        assert not got[other].any()                       # rows outside the segment are untouched
+        assert np.array_equal(got[rows], full[rows])      # its rows carry their full visible set
+        assert not got[:, np.setdiff1d(np.arange(T), cols)].any()  # only cumulative depth-0 + own chains
+        assert not (union & got).any()
+        union |= got
+    assert np.array_equal(union, full)
+
+
+def test_segments_with_crop():
+    L_max, L, K = 256, 150, 8
+    tm = pe.peagle_build_tilemap(L_max, K, [0, 64, 128, 256], device=-1)
+    full = orc.element_mask(L, K)
+    union = np.zeros_like(full)
+    for s in range(3):
+        union |= _expanded(tm, L, K, s, np.arange(L * K))
+    assert np.array_equal(union, full)
+
+
+@pytest.mark.parametrize("name", ["c2_gptoss", "c3_median", "c4_p90", "c5_p99"])
+def test_tilemap_full_size_configs_sampled_rows(name):
+    """Full-size tile maps against the oracle mask on whole row tiles sampled over the sequence
+    (first, last, around every segment boundary, random), plus closed-form pair counts."""
+    cfg = CONFIGS[name]
+    b = cfg.seg_bounds()
+    tm = pe.peagle_build_tilemap(cfg.L, cfg.K, b, device=-1)
+    inf = tm.info()
+    A = inf["anchors_per_row_tile"]
+    rng = np.random.default_rng(0)
+    anchors = {0, cfg.L - A, (cfg.L // 2 // A) * A}
+    for x in b[1:-1]:
+        anchors |= {int(x) - A, int(x)}
+    anchors |= {int(a) * A for a in rng.integers(0, cfg.L // A, size=4)}
+    for a0 in sorted(anchors):
+        rows = np.concatenate([d * cfg.L + np.arange(a0, min(a0 + A, cfg.L)) for d in range(cfg.K)])
+        rows.sort()
+        got = _expanded(tm, cfg.L, cfg.K, -1, rows)
+        ref = orc.element_mask(cfg.L, cfg.K, rows=rows)
+        assert np.array_equal(got, ref), (name, a0)
+    n_rt, n_d0 = inf["n_row_tiles"], inf["n_depth0_key_tiles"]
+    assert n_rt == -(-cfg.L // A) and n_d0 == -(-cfg.L // 64)
+    # closed forms: key tile c is full for row tile R iff 64c+63 <= R*A; each row tile adds the
+    # depth-0 tile(s) its anchors straddle and its chain sub-tiles as partial pairs
+    assert inf["n_full"] == sum((R * A + 1) // 64 for R in range(n_rt))
+    n_partial_d0 = sum(min((R * A + A - 1) // 64, n_d0 - 1) - (R * A + 1) // 64 + 1 for R in range(n_rt))
+    assert inf["n_partial"] == n_partial_d0 + n_rt * inf["n_chain_sub_tiles"]
+    assert inf["n_masks"] <= 64 // A + 1 + inf["n_chain_sub_tiles"] + 2
+
+
+def test_mask_pool_does_not_grow_with_length():
+    """Position invariance (Sec. 3.1) at tile level: the pool of distinct bitmasks is the same for any length."""
+    small = pe.peagle_build_tilemap(1024, 8, None, device=-1).info()["n_masks"]
+    large = pe.peagle_build_tilemap(20480, 8, None, device=-1).info()["n_masks"]
+    assert small == large == 6
+
+
+def test_classes_map_small():
+    L, K = 128, 4
+    tm = pe.peagle_build_tilemap(L, K, None, device=-1)
+    cls = tm.classes()
+    inf = tm.info()
+    A, n_d0, n_cs = inf["anchors_per_row_tile"], inf["n_depth0_key_tiles"], inf["n_chain_sub_tiles"]
+    M = orc.element_mask(L, K)
+    for R in range(inf["n_row_tiles"]):
+        rows = np.concatenate([d * L + np.arange(R * A, R * A + A) for d in range(K)])
+        for c in range(n_d0):
+            blk = M[np.ix_(rows, np.arange(64 * c, min(64 * c + 64, L)))]
+            want = 0 if not blk.any() else (1 if blk.all() else 2)
+            assert cls[R, c] == want
+        for R2 in range(inf["n_row_tiles"]):
+            for s in range(n_cs):
+                ck = np.arange(64 * s, min(64 * s + 64, A * (K - 1)))
+                cols = (1 + ck // A) * L + R2 * A + ck % A
+                blk = M[np.ix_(rows, cols)]
+                want = 0 if not blk.any() else (1 if blk.all() else 2)
+                assert cls[R, n_d0 + R2 * n_cs + s] == want
+
+
+def test_build_errors():
+    lib = pe.load_library()
+    out = C.c_void_p()
+    i32p = C.POINTER(C.c_int32)
+
+    def build(L, K, b, S, dev=-1, outp=C.byref(out)):
+        arr = None if b is None else (C.c_int32 * len(b))(*b)
+        return lib.peagle_build_tilemap(L, K, arr, S, dev, outp)
+
+    assert build(128, 4, None, 1, -1, None) == -2            # ENULL
+    assert build(0, 4, None, 1) == -1                        # EINVAL
+    assert build(128, 0, None, 1) == -1
+    assert build(128, 200, None, 1) == -5                    # K > 128
+    assert build(128, 4, None, 2) == -2                      # bounds missing
+    assert build(128, 4, [0, 64, 100], 2) == -4              # does not end at L_max
+    assert build(128, 4, [0, 64, 64, 128], 3) == -4          # not strictly increasing
+    assert build(128, 4, [0, 40, 128], 2) == -4              # inner bound not a multiple of A = 32
+    assert build(128, 4, [0, 64, 128], 2) == 0
+    lib.peagle_tilemap_destroy(out)
+    for code in range(0, -10, -1):
+        assert len(pe.peagle_strerror(code)) > 0
+
+
+def test_compute_entry_points_validate_before_launch():
+    """Every error path of the compute calls is reachable without a GPU (host-only tile map)."""
+    lib = pe.load_library()
+    tm = pe.peagle_build_tilemap(256, 8, [0, 128, 256], device=-1)
+    one = C.c_void_p(16)  # never dereferenced: validation fails first
+
+    def fwd(shape, seg=-1, q=one):
+        return lib.peagle_attn_fwd(tm.handle, shape.c(), seg, q, one, one, one, one, None)
+
+    ok = pe.Shape(256, 8, 4, 2, 64)
+    assert fwd(pe.Shape(256, 8, 4, 3, 64)) == -1             # Hq % Hkv
+    assert fwd(pe.Shape(256, 8, 4, 2, 96)) == -5             # head_dim
+    assert fwd(pe.Shape(300, 8, 4, 2, 64)) == -3             # L > L_max
+    assert fwd(pe.Shape(256, 4, 4, 2, 64)) == -3             # K mismatch
+    assert fwd(pe.Shape(256, 8, 4, 2, 64, scale=-1.0)) == -1
+    assert fwd(pe.Shape(256, 8, 4, 2, 64, layout=1)) == -5
+    assert fwd(ok, q=None) == -2
+    assert fwd(ok, seg=2) == -1
+    assert fwd(ok) == -8                                     # host-only map cannot launch
+    assert pe.peagle_workspace_bytes(tm, ok) > 256 * 8 * 4 * 4
+    assert pe.peagle_workspace_bytes(tm, pe.Shape(256, 8, 4, 2, 96)) == 0
+    rc = lib.peagle_attn_bwd(tm.handle, ok.c(), -1, one, one, one, one, one, one, one, one, one, 0, one, 16, None)
+    assert rc == -6                                          # workspace too small
+    rc = lib.peagle_attn_bwd(tm.handle, ok.c(), -1, one, one, one, one, one, one, one, one, one, 2, one, 1 << 40, None)
+    assert rc == -1                                          # accumulate flag
+    rc = lib.peagle_attn_step_partitioned(tm.handle, ok.c(), 1, 0, one, one, one, one, one, one, one, one, one, None,
+                                          None, one, 1 << 40, None)
+    assert rc == -1                                          # seg range
+    rc = lib.peagle_attn_step_partitioned(tm.handle, ok.c(), 0, 2, one, one, one, one, one, one, one, one, one, None,
+                                          None, None, 0, None)
+    assert rc == -6
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_NAME", "libdoes_not_exist.so")
+    with pytest.raises(ImportError):
+        binding.load_library()
