@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the parallel-drafting attention hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic sequence: for every query-row segment,
+forward (O, LSE) then backward (dQ, dK, dV) with dK/dV accumulated across segments in fp32
+(peagle_attn_step_partitioned).  The tile map is built once before the timed region (amortized
+mask construction) and its build time is reported separately.  Inputs are resident in HBM when
+the timed region starts.
+
+Prints ONE JSON line: effective (useful, unmasked-pair) TFLOP/s of forward+backward, the
+roofline of the dominant kernel from HIP-event launch durations measured in this run, and the
+fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+
+
+def _read_traffic(workload: str):
+    """HBM bytes per dk/dv-kernel launch from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"dkdv_kernel_{workload}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def cpu_baseline(cfg, sample_anchors: int):
+    """The oracle as it stands, on the first `sample_anchors` anchors of the workload (all depths),
+    one whole KV group, dense fp64 forward+backward.  Returns useful TFLOP/s on the host cores."""
+    import numpy as np
+    from oracle import peagle_oracle as orc
+    from peagle_inputs import bf16_bits_to_f64, f32_to_bf16_bits, useful_pairs
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Ls, K, D = sample_anchors, cfg.K, cfg.D
+    grp = cfg.Hq // cfg.Hkv
+    rng = np.random.default_rng(cfg.seed)
+    T = Ls * K
+    q = bf16_bits_to_f64(f32_to_bf16_bits(rng.standard_normal((T, grp, D), dtype=np.float32)))
+    k = bf16_bits_to_f64(f32_to_bf16_bits(rng.standard_normal((T, 1, D), dtype=np.float32)))
+    v = bf16_bits_to_f64(f32_to_bf16_bits(rng.standard_normal((T, 1, D), dtype=np.float32)))
+    do = bf16_bits_to_f64(f32_to_bf16_bits(rng.standard_normal((T, grp, D), dtype=np.float32)))
+    t0 = time.perf_counter()
+    orc.attn_backward(q, k, v, do, Ls, K, cfg.scale)
+    dt = time.perf_counter() - t0
+    flops = 14 * D * grp * useful_pairs(Ls, K)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {Ls} anchors x K={K} depths (T={T} rows), one KV group ({grp} query heads), "
+                      f"dense fp64 forward+backward, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3_median")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-anchors", type=int, default=2048)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2602_01469_amd as pe
+    from peagle_inputs import CONFIGS, make_inputs, useful_flops, useful_pairs
+
+    pe.load_library()  # fails loudly if the HIP extension is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.workload]
+    bounds = cfg.seg_bounds()
+    S = len(bounds) - 1
+
+    t0 = time.perf_counter()
+    tm = pe.peagle_build_tilemap(cfg.L, cfg.K, bounds, device=0)
+    tilemap_ms = (time.perf_counter() - t0) * 1e3
+    info = tm.info()
+
+    import numpy as np
+    qb, kb, vb, dob = make_inputs(cfg)
+    dev = lambda x: torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v, do = dev(qb), dev(kb), dev(vb), dev(dob)
+    del qb, kb, vb, dob
+    shape = pe.Shape(cfg.L, cfg.K, cfg.Hq, cfg.Hkv, cfg.D, cfg.scale)
+    T = cfg.T
+    o = torch.empty((T, cfg.Hq, cfg.D), dtype=torch.bfloat16, device="cuda")
+    dq = torch.empty_like(o)
+    lse = torch.empty((cfg.Hq, T), dtype=torch.float32, device="cuda")
+    dk = torch.empty((T, cfg.Hkv, cfg.D), dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    ws = torch.empty(pe.peagle_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        pe.peagle_attn_step_partitioned(tm, shape, 0, S, q, k, v, do, o, lse, dq, dk, dv, None, None, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+
+    # per-kernel launch durations: HIP events on the launch stream, same workload, same launches
+    prof_reps = 5
+    acc = {}
+    for _ in range(prof_reps):
+        pr = pe.peagle_attn_step_profiled(tm, shape, 0, S, q, k, v, do, o, lse, dq, dk, dv, ws, stream)
+        for name, (ms, n) in pr.items():
+            a = acc.setdefault(name, [0.0, 0])
+            a[0] += ms
+            a[1] += n
+    kernels = {name: {"ms_per_step": a[0] / prof_reps, "launches_per_step": a[1] // prof_reps,
+                      "avg_launch_ms": a[0] / max(a[1], 1)} for name, a in acc.items()}
+    mfma_ceiling = pe.peagle_measure_mfma_ceiling(stream)
+    torch.cuda.synchronize()
+
+    flops = useful_flops(cfg.L, cfg.K, cfg.Hq, cfg.D)
+    pairs = useful_pairs(cfg.L, cfg.K)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    # dominant kernel: dK/dV.  Algorithmic flops per unmasked pair per query head: S and dP
+    # recompute (2D each) + dV (2D) + dK (2D) = 8D; the dQ kernel carries 2D, the forward 4D.
+    dkdv = kernels["dkdv"]
+    dkdv_flops_per_launch = 8 * cfg.D * cfg.Hq * pairs / max(dkdv["launches_per_step"], 1)
+    achieved = dkdv_flops_per_launch / (dkdv["avg_launch_ms"] * 1e-3) / 1e12
+    props = torch.cuda.get_device_properties(0)
+    # tile pairs actually computed (128 rows x 64 keys each) vs useful pairs
+    computed_pairs = (info["n_full"] + info["n_partial"]) * 128 * 64
+    out = {
+        "metric": "effective masked-attn TFLOP/s fwd+bwd (useful FLOPs) & % of bf16 MFMA peak",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: L={cfg.L} K={cfg.K} T={cfg.T} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D}, "
+                               f"{S} query-row segments of {cfg.seg_anchors or cfg.L} anchors, fwd+bwd, seed {cfg.seed}",
+                   "L": cfg.L, "K": cfg.K, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "segments": S},
+        "pct_of_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "pct_of_measured_mfma_ceiling": 100.0 * value / mfma_ceiling if mfma_ceiling > 0 else None,
+        "measured_mfma_ceiling_tflops": mfma_ceiling,
+        "useful_flops_per_step": flops,
+        "useful_over_computed_pairs": pairs / computed_pairs,
+        "tilemap_build_ms": tilemap_ms,
+        "tilemap": {"device_bytes": info["device_bytes"], "n_masks": info["n_masks"], "n_full": info["n_full"],
+                    "n_partial": info["n_partial"]},
+        "kernels": kernels,
+        "device": {"name": props.name, "cus": props.multi_processor_count,
+                   "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
+        "roofline": {"bound": "mfma", "kernel": "dkdv_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": _read_traffic(cfg.name)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_anchors)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

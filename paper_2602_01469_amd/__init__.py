@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     peagle_attn_bwd,
     peagle_attn_fwd,
     peagle_attn_step_partitioned,
+    peagle_attn_step_profiled,
+    peagle_measure_mfma_ceiling,
     peagle_build_tilemap,
     peagle_strerror,
     peagle_workspace_bytes,

@@ -33,8 +33,14 @@ class _InfoC(C.Structure):
 EXPORTS = [
     "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
-    "peagle_attn_step_partitioned", "peagle_strerror",
+    "peagle_attn_step_partitioned", "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_strerror",
 ]
+
+KERNEL_KINDS = ("fwd", "dq", "dkdv", "reduce")
+
+
+class _ProfileC(C.Structure):
+    _fields_ = [("ms", C.c_float * 4), ("launches", C.c_int32 * 4)]
 
 
 def lib_path() -> str:
@@ -71,6 +77,11 @@ def load_library():
     lib.peagle_attn_step_partitioned.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                  vp, vp, vp, sz, vp]
     lib.peagle_attn_step_partitioned.restype = C.c_int
+    lib.peagle_attn_step_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                              sz, vp, C.POINTER(_ProfileC)]
+    lib.peagle_attn_step_profiled.restype = C.c_int
+    lib.peagle_measure_mfma_ceiling.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.peagle_measure_mfma_ceiling.restype = C.c_int
     lib.peagle_strerror.argtypes = [C.c_int]
     lib.peagle_strerror.restype = C.c_char_p
     _lib = lib
@@ -234,3 +245,29 @@ def peagle_attn_step_partitioned(tm: TileMap, shape: Shape, seg_begin: int, seg_
         C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
     if rc != 0:
         raise PeagleError(rc, "peagle_attn_step_partitioned")
+
+
+def peagle_attn_step_profiled(tm: TileMap, shape: Shape, seg_begin: int, seg_end: int, q, k, v, d_o, o, lse, dq,
+                              dk_acc, dv_acc, workspace, stream=None) -> dict:
+    """Same work as peagle_attn_step_partitioned; returns {kind: (ms, launches)} from HIP events."""
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    T = shape.T
+    qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
+    prof = _ProfileC()
+    rc = load_library().peagle_attn_step_profiled(
+        tm.handle, shape.c(), seg_begin, seg_end, _ptr(q, "q", bf, qs), _ptr(k, "k", bf, ks), _ptr(v, "v", bf, ks),
+        _ptr(d_o, "d_o", bf, qs), _ptr(o, "o", bf, qs), _ptr(lse, "lse", f32, (shape.Hq, T)),
+        _ptr(dq, "dq", bf, qs), _ptr(dk_acc, "dk_acc", f32, ks), _ptr(dv_acc, "dv_acc", f32, ks),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream), C.byref(prof))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_step_profiled")
+    return {name: (float(prof.ms[i]), int(prof.launches[i])) for i, name in enumerate(KERNEL_KINDS)}
+
+
+def peagle_measure_mfma_ceiling(stream=None) -> float:
+    out = C.c_float(0.0)
+    rc = load_library().peagle_measure_mfma_ceiling(_stream_ptr(stream), C.byref(out))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_measure_mfma_ceiling")
+    return float(out.value)

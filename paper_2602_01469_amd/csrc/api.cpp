@@ -132,11 +132,10 @@ extern "C" int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t*
                                                                                                    : PEAGLE_EHIP;
 }
 
-extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
-                                            int32_t seg_begin, int32_t seg_end, const void* q, const void* k,
-                                            const void* v, const void* d_o, void* o, float* lse, void* dq,
-                                            float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
-                                            void* workspace, size_t ws_bytes, void* stream) {
+static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin, int32_t seg_end,
+                     const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
+                     float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes,
+                     void* stream, peagle::KernelTimer* timer) {
   int rc = check_shape(tm, shape);
   if (rc != PEAGLE_OK) return rc;
   if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
@@ -150,11 +149,11 @@ extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const pe
     if (rc != PEAGLE_OK) return rc;
     if (sr.a_lo >= sr.a_hi) continue;  // segment lies beyond the cropped length
     const FwdParams fp = make_fwd(tm, shape, sr, q, k, v, o, lse);
-    if (peagle::launch_fwd(fp, shape->D, st) != hipSuccess) return PEAGLE_EHIP;
+    if (peagle::launch_fwd(fp, shape->D, st, timer) != hipSuccess) return PEAGLE_EHIP;
     // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
     // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
     const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
-    if (peagle::launch_bwd(bp, shape->D, sr.a_hi, sr.a_lo, st) != hipSuccess) return PEAGLE_EHIP;
+    if (peagle::launch_bwd(bp, shape->D, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
   }
   if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
     const size_t n = (size_t)shape->L * shape->K * shape->Hkv * shape->D;
@@ -162,4 +161,36 @@ extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const pe
     if (dv_bf16 && peagle::launch_cast_bf16(dv_acc, dv_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
   }
   return PEAGLE_OK;
+}
+
+extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
+                                            int32_t seg_begin, int32_t seg_end, const void* q, const void* k,
+                                            const void* v, const void* d_o, void* o, float* lse, void* dq,
+                                            float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
+                                            void* workspace, size_t ws_bytes, void* stream) {
+  return step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
+                   workspace, ws_bytes, stream, nullptr);
+}
+
+extern "C" int peagle_attn_step_profiled(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin,
+                                         int32_t seg_end, const void* q, const void* k, const void* v,
+                                         const void* d_o, void* o, float* lse, void* dq, float* dk_acc,
+                                         float* dv_acc, void* workspace, size_t ws_bytes, void* stream,
+                                         peagle_profile_t* profile) {
+  if (!profile) return PEAGLE_ENULL;
+  for (int i = 0; i < PEAGLE_NUM_KERNEL_KINDS; ++i) {
+    profile->ms[i] = 0.f;
+    profile->launches[i] = 0;
+  }
+  peagle::KernelTimer timer;
+  int rc = step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr,
+                     workspace, ws_bytes, stream, &timer);
+  if (rc != PEAGLE_OK) return rc;
+  return timer.collect(profile->ms, profile->launches) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+}
+
+extern "C" int peagle_measure_mfma_ceiling(void* stream, float* tflops) {
+  if (!tflops) return PEAGLE_ENULL;
+  *tflops = 0.f;
+  return peagle::measure_mfma_ceiling((hipStream_t)stream, tflops) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }

@@ -3,6 +3,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "tilemap.h"
 
 namespace peagle {
@@ -40,10 +42,25 @@ struct BwdParams {
   float c_log2, scale;
 };
 
-hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream);
+// Optional per-kernel timing: an event pair is recorded around every launch on the launch stream.
+enum KernelKind { kKindFwd = 0, kKindDq = 1, kKindDkDv = 2, kKindReduce = 3, kNumKinds = 4 };
+struct KernelTimer {
+  struct Span { hipEvent_t start, stop; int kind; };
+  std::vector<Span> spans;
+  hipError_t begin(int kind, hipStream_t stream);
+  hipError_t end(hipStream_t stream);
+  // Waits for the recorded work, adds the elapsed ms per kind into ms[] / launches[], frees the events.
+  hipError_t collect(float* ms, int32_t* launches);
+  ~KernelTimer();
+};
+
+hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer* timer = nullptr);
 // a_hi: end anchor of the segment (depth-0 keys [0, a_hi) are visible); depth-0 keys with anchor
 // below acc_below are added to dk_acc/dv_acc, the others overwritten.
-hipError_t launch_bwd(const BwdParams& p, int D, int a_hi, int acc_below, hipStream_t stream);
+hipError_t launch_bwd(const BwdParams& p, int D, int a_hi, int acc_below, hipStream_t stream,
+                      KernelTimer* timer = nullptr);
+// Dense bf16 MFMA issue loop on every CU: the measured matrix-core ceiling of the device, in TFLOP/s.
+hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t stream);
 
 }  // namespace peagle

@@ -669,16 +669,95 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* src, __bf16
 
 // ------------------------------------------------------------------------------------- launchers
 
+// Pure MFMA issue loop (no memory traffic): four independent accumulator chains per wave,
+// 8 workgroups x 4 waves per CU.  Used only to report the measured matrix-core ceiling.
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = (__bf16)(float)(threadIdx.x % 3);
+    b[j] = (__bf16)(float)(threadIdx.x % 5);
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = zero16();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = mfma32(a, b, acc[i]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 namespace {
+
 inline int pick_nh(int group) { return group % 2 == 0 ? 2 : 1; }
+
+struct TimedSpan {
+  KernelTimer* t;
+  hipStream_t stream;
+  hipError_t err = hipSuccess;
+  TimedSpan(KernelTimer* timer, int kind, hipStream_t s) : t(timer), stream(s) {
+    if (t) err = t->begin(kind, s);
+  }
+  hipError_t finish() {
+    hipError_t e = hipGetLastError();
+    if (t && err == hipSuccess) err = t->end(stream);
+    return e != hipSuccess ? e : err;
+  }
+};
+
 }  // namespace
 
-hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream) {
+hipError_t KernelTimer::begin(int kind, hipStream_t stream) {
+  Span sp{nullptr, nullptr, kind};
+  hipError_t e = hipEventCreate(&sp.start);
+  if (e != hipSuccess) return e;
+  e = hipEventCreate(&sp.stop);
+  if (e != hipSuccess) {
+    (void)hipEventDestroy(sp.start);
+    return e;
+  }
+  spans.push_back(sp);
+  return hipEventRecord(sp.start, stream);
+}
+
+hipError_t KernelTimer::end(hipStream_t stream) { return hipEventRecord(spans.back().stop, stream); }
+
+hipError_t KernelTimer::collect(float* ms, int32_t* launches) {
+  hipError_t rc = hipSuccess;
+  for (Span& sp : spans) {
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(sp.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, sp.start, sp.stop);
+    if (e == hipSuccess) {
+      ms[sp.kind] += t;
+      launches[sp.kind] += 1;
+    } else {
+      rc = e;
+    }
+  }
+  return rc;
+}
+
+KernelTimer::~KernelTimer() {
+  for (Span& sp : spans) {
+    (void)hipEventDestroy(sp.start);
+    (void)hipEventDestroy(sp.stop);
+  }
+}
+
+hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer* timer) {
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
   const int nh = pick_nh(group);
   const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
+  TimedSpan span(timer, kKindFwd, stream);
   if (D == 64) {
     if (nh == 2) hipLaunchKernelGGL((fwd_kernel<64, 2>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((fwd_kernel<64, 1>), grid, block, 0, stream, p);
@@ -686,10 +765,10 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream) {
     if (nh == 2) hipLaunchKernelGGL((fwd_kernel<128, 2>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((fwd_kernel<128, 1>), grid, block, 0, stream, p);
   }
-  return hipGetLastError();
+  return span.finish();
 }
 
-hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipStream_t stream) {
+hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipStream_t stream, KernelTimer* timer) {
   BwdParams p = pin;
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
@@ -697,6 +776,7 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
   const int nh = pick_nh(group);
   {
     const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
+    TimedSpan span(timer, kKindDq, stream);
     if (D == 64) {
       if (nh == 2) hipLaunchKernelGGL((dq_kernel<64, 2>), grid, block, 0, stream, p);
       else hipLaunchKernelGGL((dq_kernel<64, 1>), grid, block, 0, stream, p);
@@ -704,7 +784,7 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
       if (nh == 2) hipLaunchKernelGGL((dq_kernel<128, 2>), grid, block, 0, stream, p);
       else hipLaunchKernelGGL((dq_kernel<128, 1>), grid, block, 0, stream, p);
     }
-    hipError_t e = hipGetLastError();
+    hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
   const int n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi
@@ -712,9 +792,10 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
   const int n_chain_items = n_rt * p.tm.n_csub * p.Hkv;
   {
     const dim3 grid((unsigned)(p.n_d0_items + n_chain_items)), block(256);
+    TimedSpan span(timer, kKindDkDv, stream);
     if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((dkdv_kernel<128>), grid, block, 0, stream, p);
-    hipError_t e = hipGetLastError();
+    hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
   {
@@ -722,9 +803,10 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
     size_t blocks = (n + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     const dim3 grid((unsigned)blocks), block(256);
+    TimedSpan span(timer, kKindReduce, stream);
     if (D == 64) hipLaunchKernelGGL((reduce_partials_kernel<64>), grid, block, 0, stream, p, a_hi, acc_below);
     else hipLaunchKernelGGL((reduce_partials_kernel<128>), grid, block, 0, stream, p, a_hi, acc_below);
-    hipError_t e = hipGetLastError();
+    hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
@@ -737,6 +819,34 @@ hipError_t launch_cast_bf16(const float* src, void* dst, size_t n, hipStream_t s
   if (blocks > 256 * 16) blocks = 256 * 16;
   hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, (__bf16*)dst, n4);
   return hipGetLastError();
+}
+
+hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops) {
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  const int blocks = cus * 8, iters = 4000;
+  float* out = nullptr;
+  e = hipMalloc(&out, (size_t)blocks * 256 * sizeof(float));
+  if (e != hipSuccess) return e;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, stream, out, iters);  // warm-up
+    (void)hipEventRecord(e0, stream);
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, stream, out, iters);
+    (void)hipEventRecord(e1, stream);
+    e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) *tflops = (float)((double)blocks * 4 * iters * 4 * 32768.0 / ((double)ms * 1e9));
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(out);
+  return e;
 }
 
 }  // namespace peagle
