@@ -11,6 +11,8 @@
 #include "attn_kernels.h"
 #include "mfma_util.h"
 
+#include <cstdlib>
+
 namespace peagle {
 
 namespace {
@@ -47,48 +49,73 @@ __device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r
 __device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 
-// Cooperative global -> register load of a (rows x D) bf16 tile, 16 bytes per thread per pass.
+// Cooperative global -> register -> LDS staging of a (ROWS x D) bf16 tile, 16 bytes per thread
+// per pass; pass p of thread tid covers chunk index tid + p*NT (row = idx / (D/8)).
 template <int D, int ROWS, int NT>
 struct TileRegs {
   static constexpr int kChunks = ROWS * D / 8;
   static constexpr int kPasses = kChunks / NT;
+  static constexpr int kRowsPerPass = NT / (D / 8);
   static_assert(kChunks % NT == 0, "tile must split evenly over the workgroup");
+  static_assert(kRowsPerPass % 16 == 0, "passes must keep the swizzle phase");
   uint4 v[kPasses];
 };
 
-template <int D, int ROWS, int NT>
-__device__ __forceinline__ void store_tile(char* lds, const TileRegs<D, ROWS, NT>& regs, int tid) {
-#pragma unroll
-  for (int p = 0; p < TileRegs<D, ROWS, NT>::kPasses; ++p) {
-    const int idx = tid + p * NT;
-    const int row = idx / (D / 8), ch = idx % (D / 8);
-    *reinterpret_cast<uint4*>(lds + tile_off<D>(row, ch)) = regs.v[p];
-  }
+// LDS byte offset of pass 0 for this thread; pass p adds p * kRowsPerPass rows (same swizzle).
+template <int D>
+__device__ __forceinline__ int stage_off(int tid) {
+  return tile_off<D>(tid / (D / 8), tid % (D / 8));
 }
 
-template <int D, int NT>
-__device__ __forceinline__ void load_key_tile(TileRegs<D, kKeysPerTile, NT>& regs, const __bf16* base, int Hkv,
-                                              int kvh, const DeviceTileMap& tm, int kt, int L, int tid) {
+template <int D, int ROWS, int NT>
+__device__ __forceinline__ void store_tile(char* lds, const TileRegs<D, ROWS, NT>& regs, int soff) {
 #pragma unroll
-  for (int p = 0; p < TileRegs<D, kKeysPerTile, NT>::kPasses; ++p) {
-    const int idx = tid + p * NT;
-    const int row = idx / (D / 8), ch = idx % (D / 8);
-    int tok;
-    const bool ok = key_token(tm, kt, row, L, tok);
-    regs.v[p] = ok ? ld16(base + ((size_t)tok * Hkv + kvh) * D + ch * 8) : make_uint4(0, 0, 0, 0);
+  for (int p = 0; p < TileRegs<D, ROWS, NT>::kPasses; ++p)
+    *reinterpret_cast<uint4*>(lds + soff + p * TileRegs<D, ROWS, NT>::kRowsPerPass * 2 * D) = regs.v[p];
+}
+
+// Key tile: contiguous depth-0 tiles that lie wholly inside the sequence take the fast path
+// (uniform base + per-thread offset); chain tiles and the ragged last tile compute each row's
+// token and zero-fill rows that do not exist.
+template <int D, int NT>
+__device__ __forceinline__ void load_key_tile(TileRegs<D, kKeysPerTile, NT>& kr, TileRegs<D, kKeysPerTile, NT>& vr,
+                                              const __bf16* kbase, const __bf16* vbase, int Hkv, int kvh,
+                                              const DeviceTileMap& tm, int kt, int L, int tid) {
+  using TR = TileRegs<D, kKeysPerTile, NT>;
+  const int row0 = tid / (D / 8), ch = tid % (D / 8);
+  if (kt < tm.n_d0 && (kt + 1) * kKeysPerTile <= L) {
+    const size_t base = ((size_t)kt * kKeysPerTile * Hkv + kvh) * D;
+    const size_t stride = (size_t)Hkv * D;
+    const size_t toff = base + (size_t)row0 * stride + ch * 8;
+#pragma unroll
+    for (int p = 0; p < TR::kPasses; ++p) {
+      kr.v[p] = ld16(kbase + toff + (size_t)p * TR::kRowsPerPass * stride);
+      vr.v[p] = ld16(vbase + toff + (size_t)p * TR::kRowsPerPass * stride);
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < TR::kPasses; ++p) {
+      int tok;
+      const bool ok = key_token(tm, kt, row0 + p * TR::kRowsPerPass, L, tok);
+      const size_t off = ((size_t)(ok ? tok : 0) * Hkv + kvh) * D + ch * 8;
+      const uint4 a = ld16(kbase + off), b = ld16(vbase + off);
+      kr.v[p] = ok ? a : make_uint4(0, 0, 0, 0);
+      vr.v[p] = ok ? b : make_uint4(0, 0, 0, 0);
+    }
   }
 }
 
 template <int D, int NT>
 __device__ __forceinline__ void load_row_tile(TileRegs<D, kRowsPerTile, NT>& regs, const __bf16* base, int Hq, int h,
                                               const DeviceTileMap& tm, int rt, int L, int tid) {
+  using TR = TileRegs<D, kRowsPerTile, NT>;
+  const int row0 = tid / (D / 8), ch = tid % (D / 8);
 #pragma unroll
-  for (int p = 0; p < TileRegs<D, kRowsPerTile, NT>::kPasses; ++p) {
-    const int idx = tid + p * NT;
-    const int row = idx / (D / 8), ch = idx % (D / 8);
+  for (int p = 0; p < TR::kPasses; ++p) {
     int tok;
-    const bool ok = row_token(tm, rt, row, L, tok);
-    regs.v[p] = ok ? ld16(base + ((size_t)tok * Hq + h) * D + ch * 8) : make_uint4(0, 0, 0, 0);
+    const bool ok = row_token(tm, rt, row0 + p * TR::kRowsPerPass, L, tok);
+    const uint4 a = ld16(base + ((size_t)(ok ? tok : 0) * Hq + h) * D + ch * 8);
+    regs.v[p] = ok ? a : make_uint4(0, 0, 0, 0);
   }
 }
 
@@ -97,14 +124,87 @@ __device__ __forceinline__ float mask_sel(float x, uint32_t w, int pos) {
   return ((w >> pos) & 1u) ? x : -__builtin_inff();
 }
 
+__device__ __forceinline__ float max16(const f32x16& s) {
+  float a = __builtin_fmaxf(__builtin_fmaxf(s[0], s[1]), s[2]);
+  float b = __builtin_fmaxf(__builtin_fmaxf(s[3], s[4]), s[5]);
+  float c = __builtin_fmaxf(__builtin_fmaxf(s[6], s[7]), s[8]);
+  float d = __builtin_fmaxf(__builtin_fmaxf(s[9], s[10]), s[11]);
+  float e = __builtin_fmaxf(__builtin_fmaxf(s[12], s[13]), s[14]);
+  a = __builtin_fmaxf(__builtin_fmaxf(a, b), c);
+  d = __builtin_fmaxf(__builtin_fmaxf(d, e), s[15]);
+  return __builtin_fmaxf(a, d);
+}
+
+// Online-softmax update for one 32-key block of one head.  On entry s holds raw q.k of the
+// lane's row for its 16 keys; on exit pb holds exp2(s*c - m) as two bf16 B-operand fragments.
+// The reference max m moves only when the block exceeds it by more than the threshold, which
+// keeps the accumulator rescale off the common path without affecting the result.
+template <int DB, bool MASKED>
+__device__ __forceinline__ void softmax_block(f32x16& s, uint32_t mw, float c, float& m, float& lsum,
+                                              f32x16 (&o)[DB], bf16x8 (&pb)[2]) {
+  if (MASKED) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = mask_sel(s[i], mw, 8 * (i / 4) + (i % 4));
+  }
+  const float mx = max_halves(max16(s)) * c;
+  const bool need = mx > m + kRescaleThreshold;
+  if (__builtin_amdgcn_ballot_w64(need) != 0) {
+    const float m_new = need ? mx : m;
+    const float alpha = exp2_fast(m - m_new);
+    m = m_new;
+    lsum *= alpha;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+  }
+  const float neg_m = -m;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s[i] = exp2_fast(__builtin_fmaf(s[i], c, neg_m));
+  pb[0] = pack8_sum(s, 0, lsum);
+  pb[1] = pack8_sum(s, 1, lsum);
+}
+
 }  // namespace
 
 // =====================================================================================
 // Forward: O = softmax(scale Q K^T + mask) V, LSE.  One workgroup (4 waves) per
 // (row tile, NH query heads of one KV group); wave w owns rows [32w, 32w+32) of the tile.
+// K/V tiles are staged once in LDS per workgroup and serve all NH heads.
 // =====================================================================================
+template <int D, int NH, bool MASKED>
+__device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds, const NatOff<D>& no, const TrOff<D>& to,
+                                         const bf16x8 (&qf)[NH][D / 16], f32x16 (&o)[NH][D / 32], float (&m)[NH],
+                                         float (&lsum)[NH], const uint32_t (&mw)[2], float c) {
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    // S^T block: 32 keys x 32 rows, lane <-> row, registers <-> keys 8*(i/4) + 4g + i%4
+    f32x16 s[NH];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) s[hh] = zero16();
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const bf16x8 a = frag_nat<D>(kt_lds, no, kb, st);
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) s[hh] = mfma32(a, qf[hh][st], s[hh]);
+    }
+    bf16x8 pb[NH][2];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) softmax_block<D / 32, MASKED>(s[hh], mw[kb], c, m[hh], lsum[hh], o[hh], pb[hh]);
+    // O^T += V^T P^T : A = V^T (lane <-> d, contraction over the block's 32 keys)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 a = frag_tr<D>(vt_lds, to, kb * 32 + t * 16, db);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) o[hh][db] = mfma32(a, pb[hh][t], o[hh][db]);
+      }
+  }
+}
+
 template <int D, int NH>
-__global__ __launch_bounds__(256) void fwd_kernel(FwdParams p) {
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p) {
   constexpr int NT = 256;
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
@@ -142,102 +242,38 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdParams p) {
     for (int db = 0; db < D / 32; ++db) o[hh][db] = zero16();
   }
 
-  const TrLane tl = tr_lane(lane);
+  const NatOff<D> no = nat_offsets<D>(lane);
+  const TrOff<D> to = tr_offsets<D>(lane);
+  const int soff = stage_off<D>(tid);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
   TileRegs<D, kKeysPerTile, NT> kr, vr;
-  {
-    const int kt = tm.row_entries[e0].tile;
-    load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
-    load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
-  }
-  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, tid);
-  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, tid);
+  load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, tid);
+  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, soff);
+  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, soff);
   __syncthreads();
 
   for (int e = e0; e < e1; ++e) {
     const int buf = (e - e0) & 1;
-    if (e + 1 < e1) {
-      const int kt = tm.row_entries[e + 1].tile;
-      load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
-      load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
-    }
+    if (e + 1 < e1) load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L, tid);
     const int mask_id = tm.row_entries[e].mask_id;
-    const char* kt_lds = lds[buf][0];
-    const char* vt_lds = lds[buf][1];
-    uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
-    if (mask_id >= 0) {
+    if (mask_id < 0) {
+      const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+      fwd_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+    } else {
       const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
-      mw[0] = w[0] >> (4 * g);
-      mw[1] = w[1] >> (4 * g);
+      const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
+      fwd_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
     }
-
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      // S^T block: 32 keys x 32 rows, lane <-> row, registers <-> keys 8*(i/4) + 4g + i%4
-      f32x16 s[NH];
-#pragma unroll
-      for (int hh = 0; hh < NH; ++hh) s[hh] = zero16();
-#pragma unroll
-      for (int st = 0; st < D / 16; ++st) {
-        const bf16x8 a = frag_nat<D>(kt_lds, kb * 32 + ln, st, g);
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh) s[hh] = mfma32(a, qf[hh][st], s[hh]);
-      }
-      bf16x8 pb[NH][2];
-#pragma unroll
-      for (int hh = 0; hh < NH; ++hh) {
-        if (mask_id >= 0) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[hh][i] = mask_sel(s[hh][i], mw[kb], 8 * (i / 4) + (i % 4));
-        }
-        float mx = s[hh][0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mx = __builtin_fmaxf(mx, s[hh][i]);
-        mx = __builtin_fmaxf(mx, other_half(mx)) * p.c_log2;
-        // Lazy reference max: move it only when the block exceeds it by more than the threshold.
-        const bool need = mx > m[hh] + kRescaleThreshold;
-        if (__builtin_amdgcn_ballot_w64(need) != 0) {
-          const float m_new = need ? mx : m[hh];
-          const float alpha = exp2_fast(m[hh] - m_new);
-          m[hh] = m_new;
-          lsum[hh] *= alpha;
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[hh][db][i] *= alpha;
-        }
-        const float mref = m[hh];
-        float ls = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          s[hh][i] = exp2_fast(__builtin_fmaf(s[hh][i], p.c_log2, -mref));
-          ls += s[hh][i];
-        }
-        lsum[hh] += ls;
-        pb[hh][0] = pack8(s[hh], 0);
-        pb[hh][1] = pack8(s[hh], 1);
-      }
-      // O^T += V^T P^T : A = V^T (lane <-> d, contraction over the block's 32 keys)
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 a = frag_tr<D>(vt_lds, kb * 32 + t * 16, db * 32, tl);
-#pragma unroll
-          for (int hh = 0; hh < NH; ++hh) o[hh][db] = mfma32(a, pb[hh][t], o[hh][db]);
-        }
-    }
-
     if (e + 1 < e1) {
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, tid);
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, tid);
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, soff);
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, soff);
     }
     __syncthreads();
   }
 
 #pragma unroll
   for (int hh = 0; hh < NH; ++hh) {
-    const float l_tot = lsum[hh] + other_half(lsum[hh]);
+    const float l_tot = sum_halves(lsum[hh]);
     const float inv = 1.0f / l_tot;
     if (row_ok) {
       __bf16* orow = p.o + ((size_t)tq * p.Hq + h0 + hh) * D;
@@ -259,8 +295,59 @@ __global__ __launch_bounds__(256) void fwd_kernel(FwdParams p) {
 // Backward, part 1: Delta = rowsum(dO * O) and dQ = scale * dS K, row-tile owned (same
 // decomposition as the forward).  Writes Delta [Hq, T] for part 2.
 // =====================================================================================
+template <int D, int NH, bool MASKED>
+__device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, const NatOff<D>& no, const TrOff<D>& to,
+                                        const bf16x8 (&qf)[NH][D / 16], const bf16x8 (&dof)[NH][D / 16],
+                                        f32x16 (&dq)[NH][D / 32], const float (&lse2)[NH], const float (&delta)[NH],
+                                        const uint32_t (&mw)[2], float c) {
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    f32x16 s[NH], dp[NH];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      s[hh] = zero16();
+      dp[hh] = zero16();
+    }
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const bf16x8 ak = frag_nat<D>(kt_lds, no, kb, st);
+      const bf16x8 av = frag_nat<D>(vt_lds, no, kb, st);
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) {
+        s[hh] = mfma32(ak, qf[hh][st], s[hh]);     // S^T  = K Q^T
+        dp[hh] = mfma32(av, dof[hh][st], dp[hh]);  // dP^T = V dO^T
+      }
+    }
+    bf16x8 dsb[NH][2];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      if (MASKED) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[hh][i] = mask_sel(s[hh][i], mw[kb], 8 * (i / 4) + (i % 4));
+      }
+      const float nl = -lse2[hh], dl = delta[hh];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pr = exp2_fast(__builtin_fmaf(s[hh][i], c, nl));
+        s[hh][i] = pr * (dp[hh][i] - dl);
+      }
+      dsb[hh][0] = pack8(s[hh], 0);
+      dsb[hh][1] = pack8(s[hh], 1);
+    }
+    // dQ^T += K^T dS^T : A = K^T (lane <-> d, contraction over the block's keys)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 a = frag_tr<D>(kt_lds, to, kb * 32 + t * 16, db);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) dq[hh][db] = mfma32(a, dsb[hh][t], dq[hh][db]);
+      }
+  }
+}
+
 template <int D, int NH>
-__global__ __launch_bounds__(256) void dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p) {
   constexpr int NT = 256;
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
@@ -284,7 +371,7 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdParams p) {
   float lse2[NH], delta[NH];
 #pragma unroll
   for (int hh = 0; hh < NH; ++hh) {
-    const size_t off = ((size_t)tq * p.Hq + h0 + hh) * D + g * 8;
+    const size_t off = ((size_t)(row_ok ? tq : 0) * p.Hq + h0 + hh) * D + g * 8;
     float dl = 0.f;
 #pragma unroll
     for (int st = 0; st < D / 16; ++st) {
@@ -295,7 +382,7 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdParams p) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) dl = __builtin_fmaf((float)dof[hh][st][j], (float)of[j], dl);
     }
-    dl += other_half(dl);
+    dl = sum_halves(dl);
     delta[hh] = dl;
     lse2[hh] = row_ok ? p.lse[(size_t)(h0 + hh) * p.T + tq] * kLog2e : 0.f;
     if (row_ok && g == 0) p.delta[(size_t)(h0 + hh) * p.T + tq] = dl;
@@ -307,82 +394,31 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdParams p) {
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) dq[hh][db] = zero16();
 
-  const TrLane tl = tr_lane(lane);
+  const NatOff<D> no = nat_offsets<D>(lane);
+  const TrOff<D> to = tr_offsets<D>(lane);
+  const int soff = stage_off<D>(tid);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
   TileRegs<D, kKeysPerTile, NT> kr, vr;
-  {
-    const int kt = tm.row_entries[e0].tile;
-    load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
-    load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
-  }
-  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, tid);
-  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, tid);
+  load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, tid);
+  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, soff);
+  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, soff);
   __syncthreads();
 
   for (int e = e0; e < e1; ++e) {
     const int buf = (e - e0) & 1;
-    if (e + 1 < e1) {
-      const int kt = tm.row_entries[e + 1].tile;
-      load_key_tile<D, NT>(kr, p.k, p.Hkv, kvh, tm, kt, p.L, tid);
-      load_key_tile<D, NT>(vr, p.v, p.Hkv, kvh, tm, kt, p.L, tid);
-    }
+    if (e + 1 < e1) load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L, tid);
     const int mask_id = tm.row_entries[e].mask_id;
-    const char* kt_lds = lds[buf][0];
-    const char* vt_lds = lds[buf][1];
-    uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
-    if (mask_id >= 0) {
+    if (mask_id < 0) {
+      const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+      dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
+    } else {
       const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
-      mw[0] = w[0] >> (4 * g);
-      mw[1] = w[1] >> (4 * g);
+      const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
+      dq_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     }
-
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      f32x16 s[NH], dp[NH];
-#pragma unroll
-      for (int hh = 0; hh < NH; ++hh) {
-        s[hh] = zero16();
-        dp[hh] = zero16();
-      }
-#pragma unroll
-      for (int st = 0; st < D / 16; ++st) {
-        const bf16x8 ak = frag_nat<D>(kt_lds, kb * 32 + ln, st, g);
-        const bf16x8 av = frag_nat<D>(vt_lds, kb * 32 + ln, st, g);
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
-          s[hh] = mfma32(ak, qf[hh][st], s[hh]);     // S^T  = K Q^T
-          dp[hh] = mfma32(av, dof[hh][st], dp[hh]);  // dP^T = V dO^T
-        }
-      }
-      bf16x8 dsb[NH][2];
-#pragma unroll
-      for (int hh = 0; hh < NH; ++hh) {
-        if (mask_id >= 0) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[hh][i] = mask_sel(s[hh][i], mw[kb], 8 * (i / 4) + (i % 4));
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float pr = exp2_fast(__builtin_fmaf(s[hh][i], p.c_log2, -lse2[hh]));
-          s[hh][i] = pr * (dp[hh][i] - delta[hh]);
-        }
-        dsb[hh][0] = pack8(s[hh], 0);
-        dsb[hh][1] = pack8(s[hh], 1);
-      }
-      // dQ^T += K^T dS^T : A = K^T (lane <-> d, contraction over the block's keys)
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 a = frag_tr<D>(kt_lds, kb * 32 + t * 16, db * 32, tl);
-#pragma unroll
-          for (int hh = 0; hh < NH; ++hh) dq[hh][db] = mfma32(a, dsb[hh][t], dq[hh][db]);
-        }
-    }
-
     if (e + 1 < e1) {
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, tid);
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, tid);
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, soff);
+      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, soff);
     }
     __syncthreads();
   }
@@ -405,95 +441,164 @@ __global__ __launch_bounds__(256) void dq_kernel(BwdParams p) {
 }
 
 // =====================================================================================
-// Backward, part 2: dK, dV, key-tile owned.  A workgroup holds one key tile (64 keys) of one
-// KV head in registers and loops over the row tiles that see it (clipped to the segment) for
-// the query heads [h_lo, h_hi) assigned to it.  Wave w owns rows [32w, 32w+32) of each row tile;
-// the four waves' partial dK^T / dV^T are summed through LDS at the end.
+// Backward, part 2: dK, dV, key-tile owned.  A workgroup holds a PAIR of adjacent key tiles
+// (128 keys) of one KV head in registers and loops over the row tiles that see the first of
+// them (clipped to the segment) for the query heads [h_lo, h_hi) assigned to it; the second
+// tile's list is a suffix of the first's, so its waves idle on the few leading row tiles.
+// Wave w owns key block w%4 (32 keys) and row part w/4 of each row tile (RH parts); the parts'
+// dK^T / dV^T are summed through LDS at the end.
 //   depth-0 key tiles: one query head per workgroup, result to the per-head partial buffer;
 //   chain key tiles:   all heads of the KV group, result straight to dk_acc / dv_acc.
 // =====================================================================================
-template <int D>
-__global__ __launch_bounds__(256) void dkdv_kernel(BwdParams p) {
-  constexpr int NT = 256;
+template <int D, int RB, bool MASKED>
+__device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds, const float* lse_lds,
+                                          const float* delta_lds, const NatOff<D>& no, const TrOff<D>& to,
+                                          const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
+                                          f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], int row_base, int g, int ln,
+                                          const uint32_t* mrow, float c) {
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r0 = row_base + rb * 32;  // multiple of 32
+    // S = Q K^T and dP = dO V^T: lane <-> key, registers <-> rows r0 + 8*(i/4) + 4g + i%4
+    f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(q_lds + no.off[st] + r0 * (2 * D));
+      const bf16x8 ad = *reinterpret_cast<const bf16x8*>(do_lds + no.off[st] + r0 * (2 * D));
+      s = mfma32(aq, kf[st], s);
+      dp = mfma32(ad, vf[st], dp);
+    }
+    if (MASKED) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t w = mrow[(r0 + 8 * (i / 4) + 4 * g + (i % 4)) * 2];
+        s[i] = mask_sel(s[i], w, ln);
+      }
+    }
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_lds + r0 + 8 * q4 + 4 * g);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_lds + r0 + 8 * q4 + 4 * g);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float pr = exp2_fast(__builtin_fmaf(s[4 * q4 + j], c, -l4[j]));
+        s[4 * q4 + j] = pr;
+        dp[4 * q4 + j] = pr * (dp[4 * q4 + j] - d4[j]);
+      }
+    }
+    bf16x8 pb[2], dsb[2];
+    pb[0] = pack8(s, 0);
+    pb[1] = pack8(s, 1);
+    dsb[0] = pack8(dp, 0);
+    dsb[1] = pack8(dp, 1);
+    // dV^T += dO^T P, dK^T += Q^T dS : A operands transposed from LDS (lane <-> d, contraction over rows)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 adt = frag_tr<D>(do_lds, to, r0 + t * 16, db);
+        const bf16x8 aqt = frag_tr<D>(q_lds, to, r0 + t * 16, db);
+        dv[db] = mfma32(adt, pb[t], dv[db]);
+        dk[db] = mfma32(aqt, dsb[t], dk[db]);
+      }
+  }
+}
+
+template <int D, int RH>
+__global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
+  constexpr int NT = 256 * RH;
+  constexpr int RB = 4 / RH;  // 32-row blocks per wave per row tile
   constexpr int kTileBytes = kRowsPerTile * D * 2;
   constexpr int kBufBytes = 2 * kTileBytes + 2 * kRowsPerTile * 4;  // Q | dO | lse2 | delta
-  constexpr int kRedStride = D + 4;                                  // floats per key row in the reduction buffer
-  constexpr int kRedBytes = 4 * kKeysPerTile * kRedStride * 4;
+  constexpr int kRedBytes = (RH - 1) * 4 * 64 * 2 * (D / 32) * 16 * 4;  // [part][key block][lane][dk|dv regs]
   constexpr int kLdsBytes = 2 * kBufBytes > kRedBytes ? 2 * kBufBytes : kRedBytes;
   __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const int kblk = wave & 3, part = wave >> 2;
   const DeviceTileMap& tm = p.tm;
   const int group = p.Hq / p.Hkv;
 
   int b = blockIdx.x;
-  int kt, kvh, h_lo, h_hi;
+  int kt0, n_tiles, kvh, h_lo, h_hi;  // first key tile of the pair, tiles present (1 or 2)
   const bool chain = b >= p.n_d0_items;
   if (!chain) {
     kvh = b % p.Hkv;
     b /= p.Hkv;
     h_lo = kvh * group + b % group;
     h_hi = h_lo + 1;
-    kt = b / group;  // low key tiles are seen by the most rows: heaviest first
+    kt0 = 2 * (b / group);  // low key tiles are seen by the most rows: heaviest first
+    n_tiles = kt0 + 1 < p.n_d0_tiles ? 2 : 1;
   } else {
     b -= p.n_d0_items;
     kvh = b % p.Hkv;
     b /= p.Hkv;
-    kt = tm.n_d0 + (p.rt_lo + b / tm.n_csub) * tm.n_csub + b % tm.n_csub;
+    const int n_cpair = (tm.n_csub + 1) / 2;
+    const int sub0 = 2 * (b % n_cpair);
+    kt0 = tm.n_d0 + (p.rt_lo + b / n_cpair) * tm.n_csub + sub0;
+    n_tiles = sub0 + 1 < tm.n_csub ? 2 : 1;
     h_lo = kvh * group;
     h_hi = h_lo + group;
   }
+  const int my_tile = kblk >> 1;             // which tile of the pair this wave's keys belong to
+  const int kt = kt0 + my_tile;
+  const bool tile_present = my_tile < n_tiles;
 
-  // row tiles that see this key tile, clipped to [rt_lo, rt_hi): entries are ascending in row tile
-  int e_lo = tm.key_ptr[kt], e_hi = tm.key_ptr[kt + 1];
-  {
-    int lo = e_lo, hi = e_hi;
+  // row tiles that see a key tile, clipped to [rt_lo, rt_hi): entries are ascending in row tile
+  auto clip = [&](int t, int& lo_out, int& hi_out) {
+    int lo = tm.key_ptr[t], hi = tm.key_ptr[t + 1];
+    const int end = hi;
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
       if (tm.key_entries[mid].tile < p.rt_lo) lo = mid + 1; else hi = mid;
     }
-    e_lo = lo;
-    hi = e_hi;
+    lo_out = lo;
+    hi = end;
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
       if (tm.key_entries[mid].tile < p.rt_hi) lo = mid + 1; else hi = mid;
     }
-    e_hi = lo;
-  }
-  const int n_rows_tiles = e_hi - e_lo;
-  const int n_iter = n_rows_tiles * (h_hi - h_lo);
+    hi_out = lo;
+  };
+  int e_lo, e_hi;            // list of the pair's first tile: drives the loop
+  clip(kt0, e_lo, e_hi);
+  int my_lo = e_lo, my_hi = e_hi;
+  if (my_tile == 1 && tile_present) clip(kt, my_lo, my_hi);
+  const int n_row_tiles = e_hi - e_lo;
+  const int my_skip = tile_present ? n_row_tiles - (my_hi - my_lo) : n_row_tiles;  // leading row tiles that do not see my tile
+  const int n_iter = n_row_tiles * (h_hi - h_lo);
 
-  // stationary K, V: B operands (lane <-> key, registers <-> d)
-  bf16x8 kf[2][D / 16], vf[2][D / 16];
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
-    int tok;
-    const bool ok = key_token(tm, kt, kb * 32 + ln, p.L, tok);
-    const size_t off = ((size_t)tok * p.Hkv + kvh) * D + g * 8;
+  // stationary K, V of this wave's 32 keys: B operands (lane <-> key, registers <-> d)
+  bf16x8 kf[D / 16], vf[D / 16];
+  int key_tok = 0;
+  const bool key_ok = tile_present && key_token(tm, kt, (kblk & 1) * 32 + ln, p.L, key_tok);
+  {
+    const size_t off = ((size_t)(key_ok ? key_tok : 0) * p.Hkv + kvh) * D + g * 8;
 #pragma unroll
     for (int st = 0; st < D / 16; ++st) {
       const uint4 z = make_uint4(0, 0, 0, 0);
-      kf[kb][st] = as_frag(ok ? ld16(p.k + off + st * 16) : z);
-      vf[kb][st] = as_frag(ok ? ld16(p.v + off + st * 16) : z);
+      const uint4 a = ld16(p.k + off + st * 16), c = ld16(p.v + off + st * 16);
+      kf[st] = as_frag(key_ok ? a : z);
+      vf[st] = as_frag(key_ok ? c : z);
     }
   }
 
-  f32x16 dk[2][D / 32], dv[2][D / 32];
+  f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
-      dk[kb][db] = zero16();
-      dv[kb][db] = zero16();
-    }
+  for (int db = 0; db < D / 32; ++db) {
+    dk[db] = zero16();
+    dv[db] = zero16();
+  }
 
-  const TrLane tl = tr_lane(lane);
+  const NatOff<D> no = nat_offsets<D>(lane);
+  const TrOff<D> to = tr_offsets<D>(lane);
+  const int soff = stage_off<D>(tid);
   TileRegs<D, kRowsPerTile, NT> qr, dor;
   float lse_r = 0.f, delta_r = 0.f;  // threads 0..127 stage one row's statistics each
 
   auto issue = [&](int it) {
-    const int hh = h_lo + it / n_rows_tiles;
-    const int rt = tm.key_entries[e_lo + it % n_rows_tiles].tile;
+    const int hh = h_lo + it / n_row_tiles;
+    const int rt = tm.key_entries[e_lo + it % n_row_tiles].tile;
     load_row_tile<D, NT>(qr, p.q, p.Hq, hh, tm, rt, p.L, tid);
     load_row_tile<D, NT>(dor, p.d_o, p.Hq, hh, tm, rt, p.L, tid);
     if (tid < kRowsPerTile) {
@@ -505,8 +610,8 @@ __global__ __launch_bounds__(256) void dkdv_kernel(BwdParams p) {
   };
   auto stage = [&](int buf) {
     char* base = lds + buf * kBufBytes;
-    store_tile<D, kRowsPerTile, NT>(base, qr, tid);
-    store_tile<D, kRowsPerTile, NT>(base + kTileBytes, dor, tid);
+    store_tile<D, kRowsPerTile, NT>(base, qr, soff);
+    store_tile<D, kRowsPerTile, NT>(base + kTileBytes, dor, soff);
     if (tid < kRowsPerTile) {
       reinterpret_cast<float*>(base + 2 * kTileBytes)[tid] = lse_r;
       reinterpret_cast<float*>(base + 2 * kTileBytes + kRowsPerTile * 4)[tid] = delta_r;
@@ -522,115 +627,102 @@ __global__ __launch_bounds__(256) void dkdv_kernel(BwdParams p) {
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
     if (it + 1 < n_iter) issue(it + 1);
-    const int mask_id = tm.key_entries[e_lo + it % n_rows_tiles].mask_id;
-    const char* q_lds = lds + buf * kBufBytes;
-    const char* do_lds = q_lds + kTileBytes;
-    const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * kTileBytes);
-    const float* delta_lds = lse_lds + kRowsPerTile;
-    const int r0 = wave * 32;
-
-    // S = Q K^T and dP = dO V^T: lane <-> key, registers <-> rows r0 + 8*(i/4) + 4g + i%4
-    f32x16 s[2], dp[2];
-    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
-#pragma unroll
-    for (int st = 0; st < D / 16; ++st) {
-      const bf16x8 aq = frag_nat<D>(q_lds, r0 + ln, st, g);
-      const bf16x8 ad = frag_nat<D>(do_lds, r0 + ln, st, g);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        s[kb] = mfma32(aq, kf[kb][st], s[kb]);
-        dp[kb] = mfma32(ad, vf[kb][st], dp[kb]);
+    const int ei = it % n_row_tiles;
+    if (ei >= my_skip) {
+      const int mask_id = tm.key_entries[my_lo + ei - my_skip].mask_id;
+      const char* q_lds = lds + buf * kBufBytes;
+      const char* do_lds = q_lds + kTileBytes;
+      const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * kTileBytes);
+      const float* delta_lds = lse_lds + kRowsPerTile;
+      const int row_base = part * (kRowsPerTile / RH);
+      if (mask_id < 0) {
+        dkdv_tile<D, RB, false>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
+                                p.c_log2);
+      } else {
+        const uint32_t* mrow = tm.masks + (size_t)mask_id * kRowsPerTile * 2 + (kblk & 1);
+        dkdv_tile<D, RB, true>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, mrow,
+                               p.c_log2);
       }
     }
-    float lse2[16], dl[16];
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 a = *reinterpret_cast<const f32x4*>(lse_lds + r0 + 8 * q4 + 4 * g);
-      const f32x4 c = *reinterpret_cast<const f32x4*>(delta_lds + r0 + 8 * q4 + 4 * g);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        lse2[4 * q4 + j] = a[j];
-        dl[4 * q4 + j] = c[j];
-      }
-    }
-    if (mask_id >= 0) {
-      const uint32_t* mrow = tm.masks + ((size_t)mask_id * kRowsPerTile + r0) * 2;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const u32x2 w = *reinterpret_cast<const u32x2*>(mrow + (8 * (i / 4) + 4 * g + (i % 4)) * 2);
-        s[0][i] = mask_sel(s[0][i], w[0], ln);
-        s[1][i] = mask_sel(s[1][i], w[1], ln);
-      }
-    }
-    bf16x8 pb[2][2], dsb[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pr = exp2_fast(__builtin_fmaf(s[kb][i], p.c_log2, -lse2[i]));
-        s[kb][i] = pr;
-        dp[kb][i] = pr * (dp[kb][i] - dl[i]);
-      }
-      pb[kb][0] = pack8(s[kb], 0);
-      pb[kb][1] = pack8(s[kb], 1);
-      dsb[kb][0] = pack8(dp[kb], 0);
-      dsb[kb][1] = pack8(dp[kb], 1);
-    }
-    // dV^T += dO^T P, dK^T += Q^T dS : A operands transposed from LDS (lane <-> d, contraction over rows)
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 adt = frag_tr<D>(do_lds, r0 + t * 16, db * 32, tl);
-        const bf16x8 aqt = frag_tr<D>(q_lds, r0 + t * 16, db * 32, tl);
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          dv[kb][db] = mfma32(adt, pb[kb][t], dv[kb][db]);
-          dk[kb][db] = mfma32(aqt, dsb[kb][t], dk[kb][db]);
-        }
-      }
-
     if (it + 1 < n_iter) stage(buf ^ 1);
     __syncthreads();
   }
 
-  // cross-wave sum through LDS, then one owner thread per 16-byte piece writes the result
-  float* red = reinterpret_cast<float*>(lds);
-#pragma unroll
-  for (int which = 0; which < 2; ++which) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+  // sum the row parts through LDS (part 0 owns the result), then store from registers:
+  // lane <-> key, registers <-> d = db*32 + 8*q4 + 4g + j
+  if (RH > 1) {
+    f32x4* red = reinterpret_cast<f32x4*>(lds);
+    constexpr int kPerLane = 2 * (D / 32) * 4;  // f32x4 pieces per lane
+    if (part > 0) {
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const f32x16& acc = which == 0 ? dk[kb][db] : dv[kb][db];
-          f32x4 x;
+          f32x4 a, c;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) x[j] = acc[4 * q4 + j];
-          *reinterpret_cast<f32x4*>(red + ((size_t)wave * kKeysPerTile + kb * 32 + ln) * kRedStride + db * 32 + 8 * q4 + 4 * g) = x;
+          for (int j = 0; j < 4; ++j) {
+            a[j] = dk[db][4 * q4 + j];
+            c[j] = dv[db][4 * q4 + j];
+          }
+          const int slot = ((part - 1) * 4 + kblk) * kPerLane;
+          red[(size_t)(slot + db * 8 + q4 * 2 + 0) * 64 + lane] = a;
+          red[(size_t)(slot + db * 8 + q4 * 2 + 1) * 64 + lane] = c;
         }
-    __syncthreads();
-    const float mul = which == 0 ? p.scale : 1.0f;
-    for (int idx = tid; idx < kKeysPerTile * (D / 4); idx += NT) {
-      const int key = idx / (D / 4), c4 = idx % (D / 4);
-      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int w = 0; w < 4; ++w) sum += *reinterpret_cast<const f32x4*>(red + ((size_t)w * kKeysPerTile + key) * kRedStride + c4 * 4);
-      sum *= mul;
-      if (!chain) {
-        float* dst = (which == 0 ? p.dk_part : p.dv_part) + (((size_t)h_lo * p.L64 + (size_t)kt * kKeysPerTile + key) * D + c4 * 4);
-        *reinterpret_cast<f32x4*>(dst) = sum;
-      } else {
-        int tok;
-        if (key_token(tm, kt, key, p.L, tok)) {
-          float* dst = (which == 0 ? p.dk_acc : p.dv_acc) + (((size_t)tok * p.Hkv + kvh) * D + c4 * 4);
-          if (p.chain_accumulate) sum += *reinterpret_cast<const f32x4*>(dst);
-          *reinterpret_cast<f32x4*>(dst) = sum;
-        }
-      }
     }
     __syncthreads();
+    if (part == 0) {
+#pragma unroll
+      for (int pp = 1; pp < RH; ++pp)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int slot = ((pp - 1) * 4 + kblk) * kPerLane;
+            const f32x4 a = red[(size_t)(slot + db * 8 + q4 * 2 + 0) * 64 + lane];
+            const f32x4 c = red[(size_t)(slot + db * 8 + q4 * 2 + 1) * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              dk[db][4 * q4 + j] += a[j];
+              dv[db][4 * q4 + j] += c[j];
+            }
+          }
+    }
+  }
+  if (part == 0 && tile_present) {
+    float* dkd;
+    float* dvd;
+    bool write = true, accumulate = false;
+    if (!chain) {
+      const size_t row = (size_t)h_lo * p.L64 + (size_t)kt * kKeysPerTile + (kblk & 1) * 32 + ln;
+      dkd = p.dk_part + row * D;
+      dvd = p.dv_part + row * D;
+    } else {
+      write = key_ok;
+      accumulate = p.chain_accumulate != 0;
+      const size_t row = (size_t)(key_ok ? key_tok : 0) * p.Hkv + kvh;
+      dkd = p.dk_acc + row * D;
+      dvd = p.dv_acc + row * D;
+    }
+    if (write) {
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 a, c;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            a[j] = dk[db][4 * q4 + j] * p.scale;
+            c[j] = dv[db][4 * q4 + j];
+          }
+          const int d0 = db * 32 + 8 * q4 + 4 * g;
+          if (accumulate) {
+            a += *reinterpret_cast<const f32x4*>(dkd + d0);
+            c += *reinterpret_cast<const f32x4*>(dvd + d0);
+          }
+          *reinterpret_cast<f32x4*>(dkd + d0) = a;
+          *reinterpret_cast<f32x4*>(dvd + d0) = c;
+        }
+    }
   }
 }
 
@@ -695,7 +787,12 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters
 
 namespace {
 
-inline int pick_nh(int group) { return group % 2 == 0 ? 2 : 1; }
+// Query heads of one KV group that share a workgroup's K/V tiles (register budget decides).
+inline int pick_nh(int group, int D, const char* env_name, int dflt64) {
+  int nh = D == 64 ? dflt64 : 1;
+  if (const char* e = getenv(env_name)) nh = atoi(e);
+  return (nh == 2 && group % 2 == 0) ? 2 : 1;
+}
 
 struct TimedSpan {
   KernelTimer* t;
@@ -755,7 +852,7 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
-  const int nh = pick_nh(group);
+  const int nh = pick_nh(group, D, "PEAGLE_NH_FWD", 2);
   const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
   TimedSpan span(timer, kKindFwd, stream);
   if (D == 64) {
@@ -773,7 +870,7 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
-  const int nh = pick_nh(group);
+  const int nh = pick_nh(group, D, "PEAGLE_NH_DQ", 1);
   {
     const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
     TimedSpan span(timer, kKindDq, stream);
@@ -787,14 +884,14 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
-  const int n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi
-  p.n_d0_items = n_d0_tiles * p.Hq;
-  const int n_chain_items = n_rt * p.tm.n_csub * p.Hkv;
+  p.n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi
+  p.n_d0_items = (p.n_d0_tiles + 1) / 2 * p.Hq;            // key-tile pairs x query heads
+  const int n_chain_items = n_rt * ((p.tm.n_csub + 1) / 2) * p.Hkv;
   {
-    const dim3 grid((unsigned)(p.n_d0_items + n_chain_items)), block(256);
+    const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
     TimedSpan span(timer, kKindDkDv, stream);
-    if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((dkdv_kernel<128>), grid, block, 0, stream, p);
+    if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64, 2>), grid, dim3(512), 0, stream, p);
+    else hipLaunchKernelGGL((dkdv_kernel<128, 1>), grid, dim3(256), 0, stream, p);
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }

@@ -36,22 +36,46 @@ __device__ __forceinline__ f32x16 zero16() {
   return z;
 }
 
-// LDS tile of `rows` x D bf16, row stride 2*D bytes.  The 16-byte chunk index of a row is
-// XORed with a 3-bit function of the row so that (a) 8 consecutive rows read at the same
-// logical chunk (ds_read_b128, lane <-> row) and (b) 4 consecutive rows read as 32-byte
-// pairs (ds_read_b64_tr_b16) both spread over all banks.
-__device__ __forceinline__ int swz3(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// LDS tile of `rows` x D bf16, row stride 2*D bytes.  The LDS of gfx950 has 64 banks of 4 bytes
+// (256 B per clock): a ds_read_b128 is conflict-free when 16 consecutive lanes cover sixteen
+// distinct 16-byte slots modulo 256 B, a ds_read_b64_tr_b16 when its 4 rows x 64 B do.  The
+// 16-byte chunk index of a row is therefore XORed with a function of the row (period 16 rows)
+// chosen so that both hold for the two fragment reads below:
+//   D = 64  (two rows per 256 B): k = (row/2)%8, swz = (k%2)*4 + k/2
+//   D = 128 (one row per 256 B):  swz = (row%4)*4 + (row/4)%4
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  if (D == 64) {
+    const int k = (row >> 1) & 7;
+    return ((k & 1) << 2) | (k >> 1);
+  }
+  return ((row & 3) << 2) | ((row >> 2) & 3);
+}
 
 template <int D>
 __device__ __forceinline__ int tile_off(int row, int chunk) {
-  return row * (2 * D) + ((chunk ^ swz3(row)) << 4);
+  return row * (2 * D) + ((chunk ^ swz<D>(row)) << 4);
 }
 
 // Natural fragment: lane <-> tile row (row0 + l%32), 8 consecutive elements along D starting
 // at 16*step + 8g.  Serves as the A or B operand when the contraction runs over D.
+// NatOff holds the per-lane byte offsets of the D/16 steps for row l%32; rows 32 apart share
+// the swizzle, so other 32-row blocks add a compile-time constant.
 template <int D>
-__device__ __forceinline__ bf16x8 frag_nat(const char* tile, int row, int step, int g) {
-  return *reinterpret_cast<const bf16x8*>(tile + tile_off<D>(row, 2 * step + g));
+struct NatOff {
+  int off[D / 16];
+};
+template <int D>
+__device__ __forceinline__ NatOff<D> nat_offsets(int lane) {
+  NatOff<D> n;
+  const int row = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int st = 0; st < D / 16; ++st) n.off[st] = tile_off<D>(row, 2 * st + g);
+  return n;
+}
+template <int D>
+__device__ __forceinline__ bf16x8 frag_nat(const char* tile, const NatOff<D>& n, int row_block, int step) {
+  return *reinterpret_cast<const bf16x8*>(tile + n.off[step] + row_block * 32 * (2 * D));
 }
 
 // Transposed fragment (ds_read_b64_tr_b16): lane <-> column (d0 + l%32) of the tile, the 8
@@ -59,25 +83,29 @@ __device__ __forceinline__ bf16x8 frag_nat(const char* tile, int row, int step, 
 // Within each group of 16 lanes the instruction returns to lane i element (i%4) of the 8-byte
 // row segments addressed by lanes 4j + i/4 (j = 0..3): lane i supplies the address of row
 // (i/4), column segment 4*(i%4) of its group's 16 columns.
-struct TrLane {
-  int row_in8;   // 4g + (l%16)/4 : row offset inside the 8-row half step
-  int col;       // 16*((l/16)%2) + 4*(l%4) : first column (relative to d0) of the 8-byte segment
+// TrOff holds the per-lane byte offsets for r0 = 0 of both 4-row halves and every 32-column block.
+template <int D>
+struct TrOff {
+  int lo[D / 32], hi[D / 32];
 };
-__device__ __forceinline__ TrLane tr_lane(int lane) {
-  TrLane t;
-  t.row_in8 = 4 * (lane >> 5) + ((lane & 15) >> 2);
-  t.col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+template <int D>
+__device__ __forceinline__ TrOff<D> tr_offsets(int lane) {
+  TrOff<D> t;
+  const int row_a = 4 * (lane >> 5) + ((lane & 15) >> 2);  // 4g + (l%16)/4
+  const int row_b = row_a + 8;
+  const int col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) {
+    const int c = db * 32 + col;
+    t.lo[db] = tile_off<D>(row_a, c >> 3) + ((c & 7) << 1);
+    t.hi[db] = tile_off<D>(row_b, c >> 3) + ((c & 7) << 1);
+  }
   return t;
 }
 template <int D>
-__device__ __forceinline__ bf16x8 frag_tr(const char* tile, int r0, int d0, TrLane tl) {
-  const int c = d0 + tl.col;  // element column
-  const int row_a = r0 + tl.row_in8;
-  const int row_b = row_a + 8;
-  const int sw = swz3(row_a);  // same for row_b (differs by 8)
-  const int off_in_row = (((c >> 3) ^ sw) << 4) + ((c & 7) << 1);
-  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PEAGLE_LDS_PTR(s16x4, tile + row_a * (2 * D) + off_in_row));
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PEAGLE_LDS_PTR(s16x4, tile + row_b * (2 * D) + off_in_row));
+__device__ __forceinline__ bf16x8 frag_tr(const char* tile, const TrOff<D>& t, int r0, int db) {
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PEAGLE_LDS_PTR(s16x4, tile + t.lo[db] + r0 * (2 * D)));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(PEAGLE_LDS_PTR(s16x4, tile + t.hi[db] + r0 * (2 * D)));
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
@@ -102,7 +130,47 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int t) {
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Value held by the lane 32 positions away (the other half of the same MFMA column).
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of the
+// second: with both set to x, the first result holds x[lane%32] in every lane and the second
+// x[32 + lane%32].
+// (Vector elements are copied to scalars before any __builtin_bit_cast: applied directly to an
+// element expression such as r[1], the cast reads element 0 with this compiler.)
+__device__ __forceinline__ void swap_halves(float x, float& lo, float& hi) {
+  typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const u2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t a = r[0], b = r[1];
+  lo = __builtin_bit_cast(float, a);
+  hi = __builtin_bit_cast(float, b);
+}
+// max / sum over the two lanes (l, l^32) that share an MFMA column
+__device__ __forceinline__ float max_halves(float x) {
+  float lo, hi;
+  swap_halves(x, lo, hi);
+  return __builtin_fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_halves(float x) {
+  float lo, hi;
+  swap_halves(x, lo, hi);
+  return lo + hi;
+}
+
+// acc + lo + hi of one packed bf16 pair, accumulated in fp32 (v_dot2_f32_bf16 against ones)
+__device__ __forceinline__ float add_pair_bf16(uint32_t pair, float acc) {
+  const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), ones, acc, false);
+}
+
+// 8 consecutive C registers (one 16-wide contraction step) -> bf16x8 B operand; also adds the
+// eight rounded values to `sum`.
+__device__ __forceinline__ bf16x8 pack8_sum(const f32x16& x, int t, float& sum) {
+  u32x4 u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    u[i] = pack_bf16(x[8 * t + 2 * i], x[8 * t + 2 * i + 1]);
+    sum = add_pair_bf16(u[i], sum);
+  }
+  return __builtin_bit_cast(bf16x8, u);
+}
 
 }  // namespace peagle

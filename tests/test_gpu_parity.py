@@ -14,6 +14,9 @@ from peagle_inputs import CONFIGS, bf16_bits_to_f64, make_inputs
 pytestmark = pytest.mark.gpu
 
 FWD_MAX_ABS, FWD_REL, GRAD_REL, PART_REL = 1e-2, 5e-3, 1e-2, 1e-3
+# LSE = m + log(sum of the bf16-rounded probabilities that also enter P V): the sum carries the
+# bf16 rounding of its terms (8-bit significand: at most 2^-8 relative), i.e. 2^-8 in the logarithm.
+LSE_ABS = 4e-3
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -27,9 +30,11 @@ V_MAX = 5.5  # largest |V| drawn by the generators here (N(0,1), up to ~1e8 draw
 
 def _check_o_abs(o, ref, what):
     """|O - ref| <= 1e-2 wherever the bf16 output format allows it.  O is stored in bf16 and the
-    probabilities enter the PV product in bf16, so an element carries up to half an output ulp
-    (2^-8 |O|) plus 2^-9 max|V| of probability rounding; for |O| < ~1.2 that stays below 1e-2 and
-    the fixed bound applies, above it the derived bound does."""
+    probabilities enter the PV product in bf16 (8-bit significand), so an element carries up to
+    half an output ulp (<= 2^-8 |O|) plus the effect of probability rounding, at worst
+    2^-8 max|V| (two equally weighted keys rounded in opposite directions with opposite V); the
+    check allows half of that worst case.  Where this derived bound is below 1e-2 the fixed
+    bound applies."""
     err = np.abs(o - ref)
     bound = np.maximum(FWD_MAX_ABS, np.abs(ref) * 2.0 ** -8 + V_MAX * 2.0 ** -9)
     bad = err > bound
@@ -44,7 +49,7 @@ def _check_against_oracle(got, ref, what=""):
     assert not any(np.isnan(got[n]).any() for n in got), what
     assert rel_l2(got["O"], ref["O"]) <= FWD_REL, what
     _check_o_abs(got["O"], ref["O"], what)
-    assert max_abs(got["LSE"], ref["LSE"]) <= 1e-3, what
+    assert max_abs(got["LSE"], ref["LSE"]) <= LSE_ABS, what
     for n in ("dQ", "dK", "dV"):
         assert rel_l2(got[n], ref[n]) <= GRAD_REL, (what, n)
 
@@ -149,7 +154,7 @@ def test_zero_query_closed_form_on_gpu():
     got = r.results()
     v = bf16_bits_to_f64(vb)[:, 0]
     i, d = np.arange(T) % L, np.arange(T) // L
-    assert np.abs(got["LSE"] - np.log(i + 1 + d)[None, :]).max() < 1e-5
+    assert np.abs(got["LSE"] - np.log(i + 1 + d)[None, :]).max() < 1e-5   # every p is exactly 1
     csum = np.cumsum(v[:L], axis=0)
     for t in range(0, T, 37):
         mean = (csum[i[t]] + sum(v[e * L + i[t]] for e in range(1, d[t] + 1))) / (i[t] + 1 + d[t])
@@ -215,7 +220,7 @@ def _sampled_check(cfg, got, qb, kb, vb, dob, g, n_anchor_samples=6, seed=0):
     ref = orc.attn_backward(q, k, v, do, L, K, cfg.scale, rows=rows, row_block=256)
     assert rel_l2(got["O"][rows][:, hs], ref["O"]) <= FWD_REL
     _check_o_abs(got["O"][rows][:, hs], ref["O"], cfg.name if hasattr(cfg, "name") else "sampled")
-    assert max_abs(got["LSE"][hs][:, rows], ref["LSE"]) <= 1e-3
+    assert max_abs(got["LSE"][hs][:, rows], ref["LSE"]) <= LSE_ABS
     assert rel_l2(got["dQ"][rows][:, hs], ref["dQ"]) <= GRAD_REL
     # keys of the last `tail` anchors are seen only by rows of those anchors
     tail = 40
