@@ -87,6 +87,9 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   p.L64 = w.L64;
   p.rt_lo = sr.rt_lo;
   p.rt_hi = sr.rt_hi;
+  p.s_lo = sr.s_lo;
+  p.s_hi = sr.s_hi;
+  p.cropped = sr.cropped;
   p.chain_accumulate = chain_accumulate;
   p.c_log2 = s->scale * 1.4426950408889634f;
   p.scale = s->scale;

@@ -37,6 +37,7 @@ struct BwdParams {
   DeviceTileMap tm;
   int L, T, Hq, Hkv, L64;
   int rt_lo, rt_hi;
+  int s_lo, s_hi, cropped;  // segment boundary indices of the row range; cropped: rt_hi cuts the last segment short
   int n_d0_items;       // filled by the launcher: depth-0 work items (key-tile pairs x query heads)
   int n_d0_tiles;       // filled by the launcher: depth-0 key tiles visible to the segment
   int chain_accumulate; // chain keys: add to dk_acc/dv_acc instead of overwriting

@@ -451,16 +451,28 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p)
 //   chain key tiles:   all heads of the KV group, result straight to dk_acc / dv_acc.
 // =====================================================================================
 template <int D, int RB, bool MASKED>
-__device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds, const float* lse_lds,
-                                          const float* delta_lds, const NatOff<D>& no, const TrOff<D>& to,
+__device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds, const float* nlse_lds,
+                                          const float* ndelta_lds, const NatOff<D>& no, const TrOff<D>& to,
                                           const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
                                           f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], int row_base, int g, int ln,
                                           const uint32_t* mrow, float c) {
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int r0 = row_base + rb * 32;  // multiple of 32
-    // S = Q K^T and dP = dO V^T: lane <-> key, registers <-> rows r0 + 8*(i/4) + 4g + i%4
-    f32x16 s = zero16(), dp = zero16();
+    // S = Q K^T - lse/scale and dP - Delta = dO V^T - Delta: lane <-> key, registers <-> rows
+    // r0 + 8*(i/4) + 4g + i%4.  The per-row terms are the initial accumulator values, read
+    // from LDS in exactly the C layout, so they cost no vector instruction.
+    f32x16 s, dp;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(nlse_lds + r0 + 8 * q4 + 4 * g);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(ndelta_lds + r0 + 8 * q4 + 4 * g);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        s[4 * q4 + j] = l4[j];
+        dp[4 * q4 + j] = d4[j];
+      }
+    }
 #pragma unroll
     for (int st = 0; st < D / 16; ++st) {
       const bf16x8 aq = *reinterpret_cast<const bf16x8*>(q_lds + no.off[st] + r0 * (2 * D));
@@ -476,15 +488,10 @@ __device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds,
       }
     }
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_lds + r0 + 8 * q4 + 4 * g);
-      const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_lds + r0 + 8 * q4 + 4 * g);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float pr = exp2_fast(__builtin_fmaf(s[4 * q4 + j], c, -l4[j]));
-        s[4 * q4 + j] = pr;
-        dp[4 * q4 + j] = pr * (dp[4 * q4 + j] - d4[j]);
-      }
+    for (int i = 0; i < 16; ++i) {
+      const float pr = exp2_fast(s[i] * c);
+      s[i] = pr;
+      dp[i] *= pr;
     }
     bf16x8 pb[2], dsb[2];
     pb[0] = pack8(s, 0);
@@ -544,21 +551,20 @@ __global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
   const int kt = kt0 + my_tile;
   const bool tile_present = my_tile < n_tiles;
 
-  // row tiles that see a key tile, clipped to [rt_lo, rt_hi): entries are ascending in row tile
+  // row tiles that see a key tile, clipped to [rt_lo, rt_hi): the map stores where each segment
+  // starts inside a key tile's (ascending) list; only a cropped range needs a search for its end
   auto clip = [&](int t, int& lo_out, int& hi_out) {
-    int lo = tm.key_ptr[t], hi = tm.key_ptr[t + 1];
-    const int end = hi;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (tm.key_entries[mid].tile < p.rt_lo) lo = mid + 1; else hi = mid;
-    }
+    const int32_t* sp = tm.key_seg_ptr + (size_t)t * (tm.S + 1);
+    int lo = sp[p.s_lo], hi = sp[p.s_hi];
     lo_out = lo;
-    hi = end;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (tm.key_entries[mid].tile < p.rt_hi) lo = mid + 1; else hi = mid;
+    if (p.cropped) {
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (tm.key_entries[mid].tile < p.rt_hi) lo = mid + 1; else hi = mid;
+      }
+      hi = lo;
     }
-    hi_out = lo;
+    hi_out = hi;
   };
   int e_lo, e_hi;            // list of the pair's first tile: drives the loop
   clip(kt0, e_lo, e_hi);
@@ -595,6 +601,7 @@ __global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
   const int soff = stage_off<D>(tid);
   TileRegs<D, kRowsPerTile, NT> qr, dor;
   float lse_r = 0.f, delta_r = 0.f;  // threads 0..127 stage one row's statistics each
+  const float inv_scale = 1.0f / p.scale;
 
   auto issue = [&](int it) {
     const int hh = h_lo + it / n_row_tiles;
@@ -604,8 +611,8 @@ __global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
     if (tid < kRowsPerTile) {
       int tok;
       const bool ok = row_token(tm, rt, tid, p.L, tok);
-      lse_r = ok ? p.lse[(size_t)hh * p.T + tok] * kLog2e : 0.f;
-      delta_r = ok ? p.delta[(size_t)hh * p.T + tok] : 0.f;
+      lse_r = ok ? -p.lse[(size_t)hh * p.T + tok] * inv_scale : 0.f;  // -lse/scale: S - lse/scale = log(P)/scale
+      delta_r = ok ? -p.delta[(size_t)hh * p.T + tok] : 0.f;
     }
   };
   auto stage = [&](int buf) {

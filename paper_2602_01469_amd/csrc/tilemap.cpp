@@ -153,6 +153,17 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
       tm->key_entries[fill[en.tile]++] = TileEntry{R, en.mask_id};
     }
 
+  // per key tile: where the row tiles of each segment start inside its list
+  tm->key_seg_ptr.resize((size_t)tm->n_key_tiles * (S + 1));
+  for (int32_t t = 0; t < tm->n_key_tiles; ++t) {
+    int32_t e = tm->key_ptr[t];
+    for (int32_t sg = 0; sg <= S; ++sg) {
+      const int32_t first_rt = sg == S ? tm->n_row_tiles : b[sg] / A;
+      while (e < tm->key_ptr[t + 1] && tm->key_entries[e].tile < first_rt) ++e;
+      tm->key_seg_ptr[(size_t)t * (S + 1) + sg] = e;
+    }
+  }
+
   tm->device = device;
   if (device >= 0) {
     int prev = -1;
@@ -160,18 +171,19 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
       delete tm;
       return PEAGLE_EHIP;
     }
-    const size_t sz[5] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
-                          tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
-                          tm->masks.size() * sizeof(uint32_t)};
-    const void* src[5] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(), tm->key_entries.data(),
-                          tm->masks.data()};
-    size_t off[5], total = 0;
-    for (int i = 0; i < 5; ++i) {
+    constexpr int kArrays = 6;
+    const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
+                                tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
+                                tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t)};
+    const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
+                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data()};
+    size_t off[kArrays], total = 0;
+    for (int i = 0; i < kArrays; ++i) {
       off[i] = total;
       total += align256(sz[i] ? sz[i] : 4);
     }
     hipError_t err = hipMalloc(&tm->dev_blob, total);
-    for (int i = 0; i < 5 && err == hipSuccess; ++i)
+    for (int i = 0; i < kArrays && err == hipSuccess; ++i)
       if (sz[i]) err = hipMemcpy((char*)tm->dev_blob + off[i], src[i], sz[i], hipMemcpyHostToDevice);
     if (err == hipSuccess) err = hipDeviceSynchronize();
     (void)hipSetDevice(prev);
@@ -187,8 +199,10 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
     tm->dview.key_ptr = (const int32_t*)(base + off[2]);
     tm->dview.key_entries = (const TileEntry*)(base + off[3]);
     tm->dview.masks = (const uint32_t*)(base + off[4]);
+    tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
     tm->dview.A = A;
     tm->dview.K = K;
+    tm->dview.S = S;
     tm->dview.n_row_tiles = tm->n_row_tiles;
     tm->dview.n_d0 = tm->n_d0;
     tm->dview.n_csub = tm->n_csub;
@@ -233,11 +247,16 @@ int peagle::resolve_segment(const peagle_tilemap* tm, int32_t L, int32_t seg, Se
   if (L < 1 || L > tm->L_max) return PEAGLE_ESHAPE;
   if (seg < -1 || seg >= tm->S) return PEAGLE_EINVAL;
   int32_t lo = 0, hi = L;
+  out->s_lo = 0;
+  out->s_hi = tm->S;
   if (seg >= 0) {
     lo = tm->seg_bounds[seg];
     hi = tm->seg_bounds[seg + 1] < L ? tm->seg_bounds[seg + 1] : L;
     if (lo > hi) lo = hi;  // segment lies beyond the cropped length: empty
+    out->s_lo = seg;
+    out->s_hi = seg + 1;
   }
+  out->cropped = hi < tm->seg_bounds[out->s_hi];
   out->a_lo = lo;
   out->a_hi = hi;
   out->rt_lo = lo / tm->A;

@@ -28,8 +28,9 @@ struct DeviceTileMap {
   const TileEntry* row_entries;
   const int32_t* key_ptr;     // [n_key_tiles + 1]  offsets into key_entries (row tiles ascending)
   const TileEntry* key_entries;
+  const int32_t* key_seg_ptr; // [n_key_tiles][S + 1]  offsets into key_entries: where each segment's row tiles start
   const uint32_t* masks;      // [n_masks][128][2]
-  int32_t A, K, n_row_tiles, n_d0, n_csub, n_key_tiles;
+  int32_t A, K, S, n_row_tiles, n_d0, n_csub, n_key_tiles;
 };
 
 }  // namespace peagle
@@ -42,6 +43,7 @@ struct peagle_tilemap {
   std::vector<peagle::TileEntry> row_entries;
   std::vector<int32_t> key_ptr;
   std::vector<peagle::TileEntry> key_entries;
+  std::vector<int32_t> key_seg_ptr;              // n_key_tiles * (S+1)
   std::vector<uint32_t> masks;                   // n_masks * kMaskWords
   int64_t n_full = 0, n_partial = 0;
   int32_t n_masks = 0;
@@ -56,6 +58,8 @@ namespace peagle {
 // Anchor range [lo, hi) of a segment clipped to a length-L problem, and the row tiles covering it.
 struct SegRange {
   int32_t a_lo, a_hi, rt_lo, rt_hi;
+  int32_t s_lo, s_hi;  // segment boundary indices spanned: [bounds[s_lo], bounds[s_hi])
+  int32_t cropped;     // the range ends before bounds[s_hi] (L < L_max cuts it short)
 };
 int resolve_segment(const peagle_tilemap* tm, int32_t L, int32_t seg, SegRange* out);
 
