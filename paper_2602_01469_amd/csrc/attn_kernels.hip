@@ -105,6 +105,39 @@ __device__ __forceinline__ void load_key_tile(TileRegs<D, kKeysPerTile, NT>& kr,
   }
 }
 
+// Key tile straight into its swizzled LDS image (K and V): wave w of NW fills the 1 KiB blocks
+// w, w + NW, ...; lane l of block b owns LDS bytes [1024 b + 16 l, +16), i.e. tile row
+// b*(512/D) + l/(D/8) and physical chunk l%(D/8), and fetches the logical chunk that lives there.
+template <int D, int NW>
+__device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __bf16* kbase, const __bf16* vbase,
+                                             int Hkv, int kvh, const DeviceTileMap& tm, int kt, int L, int wave,
+                                             int lane) {
+  constexpr int kBlocks = kKeysPerTile * D * 2 / 1024;
+  static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
+  const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
+  if (kt < tm.n_d0 && (kt + 1) * kKeysPerTile <= L) {
+#pragma unroll
+    for (int i = 0; i < kBlocks / NW; ++i) {
+      const int blk = i * NW + wave;
+      const int row = blk * (512 / D) + row_in_blk;
+      const size_t off = ((size_t)(kt * kKeysPerTile + row) * Hkv + kvh) * D + ((phys ^ swz<D>(row)) << 3);
+      dma16(kbase + off, k_lds + blk * 1024);
+      dma16(vbase + off, v_lds + blk * 1024);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kBlocks / NW; ++i) {
+      const int blk = i * NW + wave;
+      const int row = blk * (512 / D) + row_in_blk;
+      int tok;
+      const bool ok = key_token(tm, kt, row, L, tok);
+      const size_t off = ((size_t)(ok ? tok : 0) * Hkv + kvh) * D + ((phys ^ swz<D>(row)) << 3);
+      dma16(ok ? (const void*)(kbase + off) : tm.zeros, k_lds + blk * 1024);
+      dma16(ok ? (const void*)(vbase + off) : tm.zeros, v_lds + blk * 1024);
+    }
+  }
+}
+
 template <int D, int NT>
 __device__ __forceinline__ void load_row_tile(TileRegs<D, kRowsPerTile, NT>& regs, const __bf16* base, int Hq, int h,
                                               const DeviceTileMap& tm, int rt, int L, int tid) {
@@ -244,17 +277,15 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p
 
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
-  const int soff = stage_off<D>(tid);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
-  TileRegs<D, kKeysPerTile, NT> kr, vr;
-  load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, tid);
-  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, soff);
-  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, soff);
+  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
   __syncthreads();
 
   for (int e = e0; e < e1; ++e) {
     const int buf = (e - e0) & 1;
-    if (e + 1 < e1) load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L, tid);
+    if (e + 1 < e1)
+      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
+                         wave, lane);
     const int mask_id = tm.row_entries[e].mask_id;
     if (mask_id < 0) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
@@ -263,10 +294,6 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p
       const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
       const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
       fwd_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
-    }
-    if (e + 1 < e1) {
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, soff);
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, soff);
     }
     __syncthreads();
   }

@@ -111,6 +111,14 @@ __device__ __forceinline__ bf16x8 frag_tr(const char* tile, const TrOff<D>& t, i
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// Asynchronous global -> LDS copy, 16 bytes per lane (global_load_lds_dwordx4): lane l's bytes
+// land at lds_wave_base + 16*l, so one call fills 1 KiB of LDS per wave; lds_wave_base must be
+// wave-uniform.  Completion is tracked by vmcnt (a __syncthreads() waits for it).
+__device__ __forceinline__ void dma16(const void* gsrc, char* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
+                                   PEAGLE_LDS_PTR(void, lds_wave_base), 16, 0, 0);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   bf16x2 p;
   p[0] = (__bf16)a;

@@ -171,12 +171,14 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
       delete tm;
       return PEAGLE_EHIP;
     }
-    constexpr int kArrays = 6;
+    constexpr int kArrays = 7;
+    static const char kZeros[256] = {0};
     const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
                                 tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
-                                tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t)};
+                                tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
+                                sizeof(kZeros)};
     const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
-                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data()};
+                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros};
     size_t off[kArrays], total = 0;
     for (int i = 0; i < kArrays; ++i) {
       off[i] = total;
@@ -200,6 +202,7 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
     tm->dview.key_entries = (const TileEntry*)(base + off[3]);
     tm->dview.masks = (const uint32_t*)(base + off[4]);
     tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
+    tm->dview.zeros = base + off[6];
     tm->dview.A = A;
     tm->dview.K = K;
     tm->dview.S = S;

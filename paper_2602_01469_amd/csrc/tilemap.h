@@ -30,6 +30,7 @@ struct DeviceTileMap {
   const TileEntry* key_entries;
   const int32_t* key_seg_ptr; // [n_key_tiles][S + 1]  offsets into key_entries: where each segment's row tiles start
   const uint32_t* masks;      // [n_masks][128][2]
+  const void* zeros;          // 256 zero bytes: source of rows that do not exist, for direct-to-LDS loads
   int32_t A, K, S, n_row_tiles, n_d0, n_csub, n_key_tiles;
 };
 
