@@ -16,7 +16,7 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t delta_off, dk_off, dv_off, total;
+  size_t delta_off, nlse_off, dk_off, dv_off, total;
   int L64;
 };
 
@@ -26,7 +26,8 @@ WsLayout ws_layout(const peagle_shape_t* s) {
   const size_t T = (size_t)s->L * s->K;
   const size_t part = (size_t)s->Hq * w.L64 * s->D * sizeof(float);
   w.delta_off = 0;
-  w.dk_off = align256(T * s->Hq * sizeof(float));
+  w.nlse_off = align256(T * s->Hq * sizeof(float));
+  w.dk_off = w.nlse_off + align256(T * s->Hq * sizeof(float));
   w.dv_off = w.dk_off + align256(part);
   w.total = w.dv_off + align256(part);
   return w;
@@ -77,6 +78,7 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   p.dk_acc = dk_acc;
   p.dv_acc = dv_acc;
   p.delta = (float*)((char*)workspace + w.delta_off);
+  p.nlse = (float*)((char*)workspace + w.nlse_off);
   p.dk_part = (float*)((char*)workspace + w.dk_off);
   p.dv_part = (float*)((char*)workspace + w.dv_off);
   p.tm = tm->dview;

@@ -31,7 +31,8 @@ struct BwdParams {
   __bf16* dq;
   float* dk_acc;       // [T, Hkv, D]
   float* dv_acc;
-  float* delta;        // workspace [Hq, T]
+  float* delta;        // workspace [Hq, T]: -rowsum(dO * O), written by the dQ kernel
+  float* nlse;         // workspace [Hq, T]: -lse / scale, written by the dQ kernel
   float* dk_part;      // workspace [Hq, L64, D]: per-query-head dK of the depth-0 keys
   float* dv_part;
   DeviceTileMap tm;

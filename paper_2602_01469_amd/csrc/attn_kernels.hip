@@ -138,6 +138,35 @@ __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __b
   }
 }
 
+// Row tile (128 rows of one query head) straight into its swizzled LDS image, same block/lane
+// assignment as dma_key_tile; rows that do not exist are filled from the zero page.
+template <int D, int NW>
+__device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base, int Hq, int h, const DeviceTileMap& tm,
+                                             int rt, int L, int wave, int lane) {
+  constexpr int kBlocks = kRowsPerTile * D * 2 / 1024;
+  static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
+  const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
+#pragma unroll
+  for (int i = 0; i < kBlocks / NW; ++i) {
+    const int blk = i * NW + wave;
+    const int row = blk * (512 / D) + row_in_blk;
+    int tok;
+    const bool ok = row_token(tm, rt, row, L, tok);
+    const size_t off = ((size_t)(ok ? tok : 0) * Hq + h) * D + ((phys ^ swz<D>(row)) << 3);
+    dma16(ok ? (const void*)(base + off) : tm.zeros, lds_tile + blk * 1024);
+  }
+}
+
+// Per-row fp32 statistic of a row tile (128 values, [Hq, T] array) into LDS: waves 0 and 1 of
+// the caller each fill 64 rows.
+__device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base, int T, int h, const DeviceTileMap& tm,
+                                             int rt, int L, int half, int lane) {
+  const int row = half * 64 + lane;
+  int tok;
+  const bool ok = row_token(tm, rt, row, L, tok);
+  dma4(ok ? (const void*)(base + (size_t)h * T + tok) : tm.zeros, reinterpret_cast<char*>(lds_stat + half * 64));
+}
+
 template <int D, int NT>
 __device__ __forceinline__ void load_row_tile(TileRegs<D, kRowsPerTile, NT>& regs, const __bf16* base, int Hq, int h,
                                               const DeviceTileMap& tm, int rt, int L, int tid) {
@@ -412,7 +441,10 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p)
     dl = sum_halves(dl);
     delta[hh] = dl;
     lse2[hh] = row_ok ? p.lse[(size_t)(h0 + hh) * p.T + tq] * kLog2e : 0.f;
-    if (row_ok && g == 0) p.delta[(size_t)(h0 + hh) * p.T + tq] = dl;
+    if (row_ok && g == 0) {  // per-row terms in the form the dK/dV kernel consumes
+      p.delta[(size_t)(h0 + hh) * p.T + tq] = -dl;
+      p.nlse[(size_t)(h0 + hh) * p.T + tq] = -lse2[hh] / p.c_log2;
+    }
   }
 
   f32x16 dq[NH][D / 32];
@@ -539,7 +571,7 @@ __device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds,
 }
 
 template <int D, int RH>
-__global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
+__global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_kernel(BwdParams p) {
   constexpr int NT = 256 * RH;
   constexpr int RB = 4 / RH;  // 32-row blocks per wave per row tile
   constexpr int kTileBytes = kRowsPerTile * D * 2;
@@ -625,42 +657,26 @@ __global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
 
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
-  const int soff = stage_off<D>(tid);
-  TileRegs<D, kRowsPerTile, NT> qr, dor;
-  float lse_r = 0.f, delta_r = 0.f;  // threads 0..127 stage one row's statistics each
-  const float inv_scale = 1.0f / p.scale;
 
-  auto issue = [&](int it) {
+  // Q / dO row tiles and their per-row terms (-lse/scale, -Delta, prepared by the dQ kernel) go
+  // straight from global memory into the LDS buffer that the next iteration reads.
+  auto issue = [&](int it, int buf) {
     const int hh = h_lo + it / n_row_tiles;
     const int rt = tm.key_entries[e_lo + it % n_row_tiles].tile;
-    load_row_tile<D, NT>(qr, p.q, p.Hq, hh, tm, rt, p.L, tid);
-    load_row_tile<D, NT>(dor, p.d_o, p.Hq, hh, tm, rt, p.L, tid);
-    if (tid < kRowsPerTile) {
-      int tok;
-      const bool ok = row_token(tm, rt, tid, p.L, tok);
-      lse_r = ok ? -p.lse[(size_t)hh * p.T + tok] * inv_scale : 0.f;  // -lse/scale: S - lse/scale = log(P)/scale
-      delta_r = ok ? -p.delta[(size_t)hh * p.T + tok] : 0.f;
-    }
-  };
-  auto stage = [&](int buf) {
     char* base = lds + buf * kBufBytes;
-    store_tile<D, kRowsPerTile, NT>(base, qr, soff);
-    store_tile<D, kRowsPerTile, NT>(base + kTileBytes, dor, soff);
-    if (tid < kRowsPerTile) {
-      reinterpret_cast<float*>(base + 2 * kTileBytes)[tid] = lse_r;
-      reinterpret_cast<float*>(base + 2 * kTileBytes + kRowsPerTile * 4)[tid] = delta_r;
-    }
+    dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rt, p.L, wave, lane);
+    dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rt, p.L, wave, lane);
+    float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
+    if (wave < 2) dma_row_stat(stat, p.nlse, p.T, hh, tm, rt, p.L, wave, lane);
+    else if (wave < 4) dma_row_stat(stat + kRowsPerTile, p.delta, p.T, hh, tm, rt, p.L, wave - 2, lane);
   };
 
-  if (n_iter > 0) {
-    issue(0);
-    stage(0);
-  }
+  if (n_iter > 0) issue(0, 0);
   __syncthreads();
 
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
-    if (it + 1 < n_iter) issue(it + 1);
+    if (it + 1 < n_iter) issue(it + 1, buf ^ 1);
     const int ei = it % n_row_tiles;
     if (ei >= my_skip) {
       const int mask_id = tm.key_entries[my_lo + ei - my_skip].mask_id;
@@ -678,7 +694,6 @@ __global__ __launch_bounds__(256 * RH) void dkdv_kernel(BwdParams p) {
                                p.c_log2);
       }
     }
-    if (it + 1 < n_iter) stage(buf ^ 1);
     __syncthreads();
   }
 
@@ -924,7 +939,9 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
   {
     const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
     TimedSpan span(timer, kKindDkDv, stream);
-    if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64, 2>), grid, dim3(512), 0, stream, p);
+    const int rh = getenv("PEAGLE_DKDV_RH") ? atoi(getenv("PEAGLE_DKDV_RH")) : 1;
+    if (D == 64 && rh == 2) hipLaunchKernelGGL((dkdv_kernel<64, 2>), grid, dim3(512), 0, stream, p);
+    else if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64, 1>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((dkdv_kernel<128, 1>), grid, dim3(256), 0, stream, p);
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;

@@ -119,6 +119,12 @@ __device__ __forceinline__ void dma16(const void* gsrc, char* lds_wave_base) {
                                    PEAGLE_LDS_PTR(void, lds_wave_base), 16, 0, 0);
 }
 
+// Same, 4 bytes per lane (global_load_lds_dword): lane l's dword lands at lds_wave_base + 4*l.
+__device__ __forceinline__ void dma4(const void* gsrc, char* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
+                                   PEAGLE_LDS_PTR(void, lds_wave_base), 4, 0, 0);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   bf16x2 p;
   p[0] = (__bf16)a;
