@@ -139,32 +139,58 @@ __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __b
 }
 
 // Row tile (128 rows of one query head) straight into its swizzled LDS image, same block/lane
-// assignment as dma_key_tile; rows that do not exist are filled from the zero page.
+// assignment as dma_key_tile; rows that do not exist are filled from the zero page.  The rows a
+// lane copies are the same for every row tile, so their (depth, anchor) split - which costs an
+// integer division by A - is done once per kernel (RowDmaLane) and a copy only adds rt*A.
 template <int D, int NW>
-__device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base, int Hq, int h, const DeviceTileMap& tm,
-                                             int rt, int L, int wave, int lane) {
-  constexpr int kBlocks = kRowsPerTile * D * 2 / 1024;
+struct RowDmaLane {
+  static constexpr int kBlocks = kRowsPerTile * D * 2 / 1024;
+  static constexpr int kPer = kBlocks / NW;
   static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
+  int tok0[kPer];    // d*L + a : token of the row in row tile 0
+  int a[kPer];       // anchor offset inside the row tile; >= A*K... marks a padding row via a huge value
+  int chunk[kPer];   // element offset of the logical 16-byte chunk this lane fetches
+  int stat_tok0, stat_a;  // same for the row whose per-row statistic this lane copies (waves 0..3)
+};
+template <int D, int NW>
+__device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& tm, int L, int wave, int lane) {
+  RowDmaLane<D, NW> r;
   const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
 #pragma unroll
-  for (int i = 0; i < kBlocks / NW; ++i) {
-    const int blk = i * NW + wave;
-    const int row = blk * (512 / D) + row_in_blk;
-    int tok;
-    const bool ok = row_token(tm, rt, row, L, tok);
-    const size_t off = ((size_t)(ok ? tok : 0) * Hq + h) * D + ((phys ^ swz<D>(row)) << 3);
-    dma16(ok ? (const void*)(base + off) : tm.zeros, lds_tile + blk * 1024);
+  for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
+    const int row = (i * NW + wave) * (512 / D) + row_in_blk;
+    const int d = row / tm.A, a = row - d * tm.A;
+    r.tok0[i] = d * L + a;
+    r.a[i] = d < tm.K ? a : (1 << 30);
+    r.chunk[i] = (phys ^ swz<D>(row)) << 3;
+  }
+  const int srow = (wave & 1) * 64 + lane;
+  const int sd = srow / tm.A, sa = srow - sd * tm.A;
+  r.stat_tok0 = sd * L + sa;
+  r.stat_a = sd < tm.K ? sa : (1 << 30);
+  return r;
+}
+template <int D, int NW>
+__device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base, int Hq, int h, const DeviceTileMap& tm,
+                                             const RowDmaLane<D, NW>& rl, int rt, int L, int wave) {
+  const int i0 = rt * tm.A;
+#pragma unroll
+  for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
+    const bool ok = i0 + rl.a[i] < L;  // padding rows carry a huge anchor offset
+    const size_t off = ((size_t)(ok ? rl.tok0[i] + i0 : 0) * Hq + h) * D + rl.chunk[i];
+    dma16(ok ? (const void*)(base + off) : tm.zeros, lds_tile + (i * NW + wave) * 1024);
   }
 }
 
-// Per-row fp32 statistic of a row tile (128 values, [Hq, T] array) into LDS: waves 0 and 1 of
-// the caller each fill 64 rows.
+// Per-row fp32 statistic of a row tile (128 values, [Hq, T] array) into LDS: two waves of the
+// caller each fill 64 rows (half = wave & 1).
+template <int D, int NW>
 __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base, int T, int h, const DeviceTileMap& tm,
-                                             int rt, int L, int half, int lane) {
-  const int row = half * 64 + lane;
-  int tok;
-  const bool ok = row_token(tm, rt, row, L, tok);
-  dma4(ok ? (const void*)(base + (size_t)h * T + tok) : tm.zeros, reinterpret_cast<char*>(lds_stat + half * 64));
+                                             const RowDmaLane<D, NW>& rl, int rt, int L, int half) {
+  const int i0 = rt * tm.A;
+  const bool ok = i0 + rl.stat_a < L;
+  dma4(ok ? (const void*)(base + (size_t)h * T + rl.stat_tok0 + i0) : tm.zeros,
+       reinterpret_cast<char*>(lds_stat + half * 64));
 }
 
 template <int D, int NT>
@@ -660,15 +686,16 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
 
   // Q / dO row tiles and their per-row terms (-lse/scale, -Delta, prepared by the dQ kernel) go
   // straight from global memory into the LDS buffer that the next iteration reads.
+  const RowDmaLane<D, 4 * RH> rl = row_dma_lane<D, 4 * RH>(tm, p.L, wave, lane);
   auto issue = [&](int it, int buf) {
     const int hh = h_lo + it / n_row_tiles;
     const int rt = tm.key_entries[e_lo + it % n_row_tiles].tile;
     char* base = lds + buf * kBufBytes;
-    dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rt, p.L, wave, lane);
-    dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rt, p.L, wave, lane);
+    dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rl, rt, p.L, wave);
+    dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rl, rt, p.L, wave);
     float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
-    if (wave < 2) dma_row_stat(stat, p.nlse, p.T, hh, tm, rt, p.L, wave, lane);
-    else if (wave < 4) dma_row_stat(stat + kRowsPerTile, p.delta, p.T, hh, tm, rt, p.L, wave - 2, lane);
+    if (wave < 2) dma_row_stat<D, 4 * RH>(stat, p.nlse, p.T, hh, tm, rl, rt, p.L, wave & 1);
+    else if (wave < 4) dma_row_stat<D, 4 * RH>(stat + kRowsPerTile, p.delta, p.T, hh, tm, rl, rt, p.L, wave & 1);
   };
 
   if (n_iter > 0) issue(0, 0);
