@@ -73,6 +73,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3_median")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-anchors", type=int, default=2048)
+    ap.add_argument("--seg-anchors", type=int, default=None,
+                    help="override the anchors per query-row segment (diagnostic; the default is the workload's)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -89,6 +91,9 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     cfg = CONFIGS[args.workload]
+    if args.seg_anchors is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, seg_anchors=args.seg_anchors)
     bounds = cfg.seg_bounds()
     S = len(bounds) - 1
 

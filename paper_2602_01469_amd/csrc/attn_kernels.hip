@@ -12,6 +12,7 @@
 #include "mfma_util.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace peagle {
 
@@ -48,62 +49,6 @@ __device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r
 
 __device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
-
-// Cooperative global -> register -> LDS staging of a (ROWS x D) bf16 tile, 16 bytes per thread
-// per pass; pass p of thread tid covers chunk index tid + p*NT (row = idx / (D/8)).
-template <int D, int ROWS, int NT>
-struct TileRegs {
-  static constexpr int kChunks = ROWS * D / 8;
-  static constexpr int kPasses = kChunks / NT;
-  static constexpr int kRowsPerPass = NT / (D / 8);
-  static_assert(kChunks % NT == 0, "tile must split evenly over the workgroup");
-  static_assert(kRowsPerPass % 16 == 0, "passes must keep the swizzle phase");
-  uint4 v[kPasses];
-};
-
-// LDS byte offset of pass 0 for this thread; pass p adds p * kRowsPerPass rows (same swizzle).
-template <int D>
-__device__ __forceinline__ int stage_off(int tid) {
-  return tile_off<D>(tid / (D / 8), tid % (D / 8));
-}
-
-template <int D, int ROWS, int NT>
-__device__ __forceinline__ void store_tile(char* lds, const TileRegs<D, ROWS, NT>& regs, int soff) {
-#pragma unroll
-  for (int p = 0; p < TileRegs<D, ROWS, NT>::kPasses; ++p)
-    *reinterpret_cast<uint4*>(lds + soff + p * TileRegs<D, ROWS, NT>::kRowsPerPass * 2 * D) = regs.v[p];
-}
-
-// Key tile: contiguous depth-0 tiles that lie wholly inside the sequence take the fast path
-// (uniform base + per-thread offset); chain tiles and the ragged last tile compute each row's
-// token and zero-fill rows that do not exist.
-template <int D, int NT>
-__device__ __forceinline__ void load_key_tile(TileRegs<D, kKeysPerTile, NT>& kr, TileRegs<D, kKeysPerTile, NT>& vr,
-                                              const __bf16* kbase, const __bf16* vbase, int Hkv, int kvh,
-                                              const DeviceTileMap& tm, int kt, int L, int tid) {
-  using TR = TileRegs<D, kKeysPerTile, NT>;
-  const int row0 = tid / (D / 8), ch = tid % (D / 8);
-  if (kt < tm.n_d0 && (kt + 1) * kKeysPerTile <= L) {
-    const size_t base = ((size_t)kt * kKeysPerTile * Hkv + kvh) * D;
-    const size_t stride = (size_t)Hkv * D;
-    const size_t toff = base + (size_t)row0 * stride + ch * 8;
-#pragma unroll
-    for (int p = 0; p < TR::kPasses; ++p) {
-      kr.v[p] = ld16(kbase + toff + (size_t)p * TR::kRowsPerPass * stride);
-      vr.v[p] = ld16(vbase + toff + (size_t)p * TR::kRowsPerPass * stride);
-    }
-  } else {
-#pragma unroll
-    for (int p = 0; p < TR::kPasses; ++p) {
-      int tok;
-      const bool ok = key_token(tm, kt, row0 + p * TR::kRowsPerPass, L, tok);
-      const size_t off = ((size_t)(ok ? tok : 0) * Hkv + kvh) * D + ch * 8;
-      const uint4 a = ld16(kbase + off), b = ld16(vbase + off);
-      kr.v[p] = ok ? a : make_uint4(0, 0, 0, 0);
-      vr.v[p] = ok ? b : make_uint4(0, 0, 0, 0);
-    }
-  }
-}
 
 // Key tile straight into its swizzled LDS image (K and V): wave w of NW fills the 1 KiB blocks
 // w, w + NW, ...; lane l of block b owns LDS bytes [1024 b + 16 l, +16), i.e. tile row
@@ -193,20 +138,6 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
        reinterpret_cast<char*>(lds_stat + half * 64));
 }
 
-template <int D, int NT>
-__device__ __forceinline__ void load_row_tile(TileRegs<D, kRowsPerTile, NT>& regs, const __bf16* base, int Hq, int h,
-                                              const DeviceTileMap& tm, int rt, int L, int tid) {
-  using TR = TileRegs<D, kRowsPerTile, NT>;
-  const int row0 = tid / (D / 8), ch = tid % (D / 8);
-#pragma unroll
-  for (int p = 0; p < TR::kPasses; ++p) {
-    int tok;
-    const bool ok = row_token(tm, rt, row0 + p * TR::kRowsPerPass, L, tok);
-    const uint4 a = ld16(base + ((size_t)(ok ? tok : 0) * Hq + h) * D + ch * 8);
-    regs.v[p] = ok ? a : make_uint4(0, 0, 0, 0);
-  }
-}
-
 // Bit `pos` of w selects x, otherwise -inf.
 __device__ __forceinline__ float mask_sel(float x, uint32_t w, int pos) {
   return ((w >> pos) & 1u) ? x : -__builtin_inff();
@@ -260,7 +191,7 @@ __device__ __forceinline__ void softmax_block(f32x16& s, uint32_t mw, float c, f
 // (row tile, NH query heads of one KV group); wave w owns rows [32w, 32w+32) of the tile.
 // K/V tiles are staged once in LDS per workgroup and serve all NH heads.
 // =====================================================================================
-template <int D, int NH, bool MASKED>
+template <int D, int NH, bool MASKED, bool SAFE>
 __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds, const NatOff<D>& no, const TrOff<D>& to,
                                          const bf16x8 (&qf)[NH][D / 16], f32x16 (&o)[NH][D / 32], float (&m)[NH],
                                          float (&lsum)[NH], const uint32_t (&mw)[2], float c) {
@@ -278,7 +209,20 @@ __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds,
     }
     bf16x8 pb[NH][2];
 #pragma unroll
-    for (int hh = 0; hh < NH; ++hh) softmax_block<D / 32, MASKED>(s[hh], mw[kb], c, m[hh], lsum[hh], o[hh], pb[hh]);
+    for (int hh = 0; hh < NH; ++hh) {
+      if (SAFE) {
+        softmax_block<D / 32, MASKED>(s[hh], mw[kb], c, m[hh], lsum[hh], o[hh], pb[hh]);
+      } else {  // reference max fixed at 0: p = 2^(c s); the caller checks the row sums' range
+        if (MASKED) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[hh][i] = mask_sel(s[hh][i], mw[kb], 8 * (i / 4) + (i % 4));
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[hh][i] = exp2_fast(s[hh][i] * c);
+        pb[hh][0] = pack8_sum(s[hh], 0, lsum[hh]);
+        pb[hh][1] = pack8_sum(s[hh], 1, lsum[hh]);
+      }
+    }
     // O^T += V^T P^T : A = V^T (lane <-> d, contraction over the block's 32 keys)
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
@@ -293,7 +237,6 @@ __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds,
 
 template <int D, int NH>
 __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p) {
-  constexpr int NT = 256;
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
 
@@ -321,42 +264,55 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p
                                   : make_uint4(0, 0, 0, 0));
 
   f32x16 o[NH][D / 32];
-  float m[NH], lsum[NH];
-#pragma unroll
-  for (int hh = 0; hh < NH; ++hh) {
-    m[hh] = kNegInit;
-    lsum[hh] = 0.f;
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) o[hh][db] = zero16();
-  }
-
+  float m[NH], lsum[NH], l_tot[NH];
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
-  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
-  __syncthreads();
 
-  for (int e = e0; e < e1; ++e) {
-    const int buf = (e - e0) & 1;
-    if (e + 1 < e1)
-      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
-                         wave, lane);
-    const int mask_id = tm.row_entries[e].mask_id;
-    if (mask_id < 0) {
-      const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
-      fwd_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
-    } else {
-      const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
-      const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
-      fwd_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+  // One pass over the row tile's key tiles.  The first pass keeps the softmax reference at 0
+  // (no running max: fewer vector instructions per score); it is exact as long as every row
+  // sum stays inside the fp32 / bf16 exponent range.  If any row of the workgroup leaves
+  // [2^-100, 2^100] (or is not finite) the tile is recomputed with the running-max form.
+  auto pass = [&](auto safe_tag) {
+    constexpr bool SAFE = decltype(safe_tag)::value;
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      m[hh] = SAFE ? kNegInit : 0.f;
+      lsum[hh] = 0.f;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) o[hh][db] = zero16();
     }
+    dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
     __syncthreads();
-  }
+    for (int e = e0; e < e1; ++e) {
+      const int buf = (e - e0) & 1;
+      if (e + 1 < e1)
+        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile,
+                           p.L, wave, lane);
+      const int mask_id = tm.row_entries[e].mask_id;
+      if (mask_id < 0) {
+        const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+        fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+      } else {
+        const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
+        const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
+        fwd_tile<D, NH, true, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+      }
+      __syncthreads();
+    }
+    bool bad = false;
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      l_tot[hh] = sum_halves(lsum[hh]);
+      bad |= !(l_tot[hh] > 0x1p-100f && l_tot[hh] < 0x1p100f);
+    }
+    return bad && row_ok;
+  };
+  if (__syncthreads_or(pass(std::false_type{}))) (void)pass(std::true_type{});
 
 #pragma unroll
   for (int hh = 0; hh < NH; ++hh) {
-    const float l_tot = sum_halves(lsum[hh]);
-    const float inv = 1.0f / l_tot;
+    const float inv = 1.0f / l_tot[hh];
     if (row_ok) {
       __bf16* orow = p.o + ((size_t)tq * p.Hq + h0 + hh) * D;
 #pragma unroll
@@ -368,7 +324,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p
           w[1] = pack_bf16(o[hh][db][4 * q4 + 2] * inv, o[hh][db][4 * q4 + 3] * inv);
           *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * g) = w;
         }
-      if (g == 0) p.lse[(size_t)(h0 + hh) * p.T + tq] = (m[hh] + __builtin_log2f(l_tot)) * kLn2;
+      if (g == 0) p.lse[(size_t)(h0 + hh) * p.T + tq] = (m[hh] + __builtin_log2f(l_tot[hh])) * kLn2;
     }
   }
 }
@@ -430,7 +386,6 @@ __device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, 
 
 template <int D, int NH>
 __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p) {
-  constexpr int NT = 256;
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
 
@@ -481,17 +436,15 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p)
 
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
-  const int soff = stage_off<D>(tid);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
-  TileRegs<D, kKeysPerTile, NT> kr, vr;
-  load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, tid);
-  store_tile<D, kKeysPerTile, NT>(lds[0][0], kr, soff);
-  store_tile<D, kKeysPerTile, NT>(lds[0][1], vr, soff);
+  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
   __syncthreads();
 
   for (int e = e0; e < e1; ++e) {
     const int buf = (e - e0) & 1;
-    if (e + 1 < e1) load_key_tile<D, NT>(kr, vr, p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L, tid);
+    if (e + 1 < e1)
+      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
+                         wave, lane);
     const int mask_id = tm.row_entries[e].mask_id;
     if (mask_id < 0) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
@@ -500,10 +453,6 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p)
       const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
       const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
       dq_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
-    }
-    if (e + 1 < e1) {
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][0], kr, soff);
-      store_tile<D, kKeysPerTile, NT>(lds[buf ^ 1][1], vr, soff);
     }
     __syncthreads();
   }
@@ -598,7 +547,6 @@ __device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds,
 
 template <int D, int RH>
 __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_kernel(BwdParams p) {
-  constexpr int NT = 256 * RH;
   constexpr int RB = 4 / RH;  // 32-row blocks per wave per row tile
   constexpr int kTileBytes = kRowsPerTile * D * 2;
   constexpr int kBufBytes = 2 * kTileBytes + 2 * kRowsPerTile * 4;  // Q | dO | lse2 | delta

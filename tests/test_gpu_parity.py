@@ -124,6 +124,31 @@ def test_small_cases_match_oracle(name, L, K, Hq, Hkv, D, seed, bounds, L_max):
             assert rel_l2(g4[n], got[n]) <= PART_REL, n
 
 
+@pytest.mark.parametrize("qscale", [12.0, 40.0])
+def test_large_logits_take_the_running_max_path(qscale):
+    """Scores far outside the exponent range that the forward's first pass (reference max fixed at
+    0) can hold: the kernel must detect it and redo the row tile with the running-max form."""
+    L, K, Hq, Hkv, D = 200, 4, 4, 2, 64
+    print(f"case large_logits qscale={qscale}", flush=True)
+    T = L * K
+    qb, kb, vb, dob = (rand_bits((T, Hq, D), 300, qscale), rand_bits((T, Hkv, D), 301), rand_bits((T, Hkv, D), 302),
+                       rand_bits((T, Hq, D), 303))
+    tm = pe.peagle_build_tilemap(L, K, None, device=0)
+    r = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+    r.fwd()
+    r.bwd()
+    got = r.results()
+    ref = _oracle(qb, kb, vb, dob, L, K, r.shape.scale)
+    lse_span = ref["LSE"].max() - ref["LSE"].min()
+    assert lse_span > 60 * (qscale / 12.0)       # the case really leaves the comfortable range
+    assert not any(np.isnan(got[n]).any() for n in got)
+    assert rel_l2(got["O"], ref["O"]) <= FWD_REL
+    # |LSE| is in the hundreds here: fp32 resolution of the stored value dominates the bf16-sum term
+    assert max_abs(got["LSE"], ref["LSE"]) <= LSE_ABS + 2e-6 * np.abs(ref["LSE"]).max()
+    for n in ("dQ", "dK", "dV"):
+        assert rel_l2(got[n], ref[n]) <= GRAD_REL, n
+
+
 def test_run_to_run_determinism():
     L, K, Hq, Hkv, D = 300, 8, 4, 2, 64
     print("case determinism", flush=True)
