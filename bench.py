@@ -73,6 +73,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3_median")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-anchors", type=int, default=2048)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one 256 MiB device-to-device copy (reference dispatch for HBM byte counters)")
     ap.add_argument("--seg-anchors", type=int, default=None,
                     help="override the anchors per query-row segment (diagnostic; the default is the workload's)")
     args = ap.parse_args()
@@ -142,6 +144,11 @@ def main() -> int:
                       "avg_launch_ms": a[0] / max(a[1], 1)} for name, a in acc.items()}
     mfma_ceiling = pe.peagle_measure_mfma_ceiling(stream)
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     flops = useful_flops(cfg.L, cfg.K, cfg.Hq, cfg.D)
     pairs = useful_pairs(cfg.L, cfg.K)

@@ -563,11 +563,15 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   int kt0, n_tiles, kvh, h_lo, h_hi;  // first key tile of the pair, tiles present (1 or 2)
   const bool chain = b >= p.n_d0_items;
   if (!chain) {
+    // Workgroups are dealt round-robin to the XCDs, so b % Hkv pins a KV head to an XCD's L2;
+    // within it the key-tile pairs of one query head are adjacent, so the workgroups that are
+    // resident together stream the same head's Q / dO rows and share them in L2.
+    const int n_pairs = (p.n_d0_tiles + 1) / 2;
     kvh = b % p.Hkv;
     b /= p.Hkv;
-    h_lo = kvh * group + b % group;
+    kt0 = 2 * (b % n_pairs);
+    h_lo = kvh * group + b / n_pairs;
     h_hi = h_lo + 1;
-    kt0 = 2 * (b / group);  // low key tiles are seen by the most rows: heaviest first
     n_tiles = kt0 + 1 < p.n_d0_tiles ? 2 : 1;
   } else {
     b -= p.n_d0_items;
