@@ -284,7 +284,19 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p
     }
     dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
     __syncthreads();
-    for (int e = e0; e < e1; ++e) {
+    // The leading full tiles run in a loop of their own (no mask branch, accumulators stay in
+    // place); the partial tiles that end a row tile's list take the general loop.
+    int e = e0;
+    for (; e < e1 && tm.row_entries[e].mask_id < 0; ++e) {
+      const int buf = (e - e0) & 1;
+      if (e + 1 < e1)
+        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile,
+                           p.L, wave, lane);
+      const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+      fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+      __syncthreads();
+    }
+    for (; e < e1; ++e) {
       const int buf = (e - e0) & 1;
       if (e + 1 < e1)
         dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile,
@@ -440,7 +452,17 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p)
   dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
   __syncthreads();
 
-  for (int e = e0; e < e1; ++e) {
+  int e = e0;
+  for (; e < e1 && tm.row_entries[e].mask_id < 0; ++e) {  // leading full tiles: no mask branch
+    const int buf = (e - e0) & 1;
+    if (e + 1 < e1)
+      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
+                         wave, lane);
+    const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+    dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
+    __syncthreads();
+  }
+  for (; e < e1; ++e) {
     const int buf = (e - e0) & 1;
     if (e + 1 < e1)
       dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
