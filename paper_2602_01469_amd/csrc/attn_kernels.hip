@@ -11,7 +11,6 @@
 #include "attn_kernels.h"
 #include "mfma_util.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace peagle {
@@ -837,12 +836,9 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters
 
 namespace {
 
-// Query heads of one KV group that share a workgroup's K/V tiles (register budget decides).
-inline int pick_nh(int group, int D, const char* env_name, int dflt64) {
-  int nh = D == 64 ? dflt64 : 1;
-  if (const char* e = getenv(env_name)) nh = atoi(e);
-  return (nh == 2 && group % 2 == 0) ? 2 : 1;
-}
+// Query heads of one KV group that share a workgroup's K/V tiles: two in the D = 64 forward
+// (the register budget of two waves per SIMD allows it), one everywhere else.
+inline int pick_nh(int group, int D, bool forward) { return (forward && D == 64 && group % 2 == 0) ? 2 : 1; }
 
 struct TimedSpan {
   KernelTimer* t;
@@ -902,15 +898,14 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
-  const int nh = pick_nh(group, D, "PEAGLE_NH_FWD", 2);
+  const int nh = pick_nh(group, D, true);
   const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
   TimedSpan span(timer, kKindFwd, stream);
   if (D == 64) {
     if (nh == 2) hipLaunchKernelGGL((fwd_kernel<64, 2>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((fwd_kernel<64, 1>), grid, block, 0, stream, p);
   } else {
-    if (nh == 2) hipLaunchKernelGGL((fwd_kernel<128, 2>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((fwd_kernel<128, 1>), grid, block, 0, stream, p);
+    hipLaunchKernelGGL((fwd_kernel<128, 1>), grid, block, 0, stream, p);
   }
   return span.finish();
 }
@@ -920,17 +915,12 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
-  const int nh = pick_nh(group, D, "PEAGLE_NH_DQ", 1);
+  const int nh = pick_nh(group, D, false);
   {
     const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
     TimedSpan span(timer, kKindDq, stream);
-    if (D == 64) {
-      if (nh == 2) hipLaunchKernelGGL((dq_kernel<64, 2>), grid, block, 0, stream, p);
-      else hipLaunchKernelGGL((dq_kernel<64, 1>), grid, block, 0, stream, p);
-    } else {
-      if (nh == 2) hipLaunchKernelGGL((dq_kernel<128, 2>), grid, block, 0, stream, p);
-      else hipLaunchKernelGGL((dq_kernel<128, 1>), grid, block, 0, stream, p);
-    }
+    if (D == 64) hipLaunchKernelGGL((dq_kernel<64, 1>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((dq_kernel<128, 1>), grid, block, 0, stream, p);
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
@@ -940,9 +930,7 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
   {
     const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
     TimedSpan span(timer, kKindDkDv, stream);
-    const int rh = getenv("PEAGLE_DKDV_RH") ? atoi(getenv("PEAGLE_DKDV_RH")) : 1;
-    if (D == 64 && rh == 2) hipLaunchKernelGGL((dkdv_kernel<64, 2>), grid, dim3(512), 0, stream, p);
-    else if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64, 1>), grid, dim3(256), 0, stream, p);
+    if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64, 1>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((dkdv_kernel<128, 1>), grid, dim3(256), 0, stream, p);
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
