@@ -65,6 +65,74 @@ def cpu_baseline(cfg, sample_anchors: int):
                       f"dense fp64 forward+backward, {dt:.1f} s"}
 
 
+def trace_lengths(quantiles):
+    """Sequence lengths at the given quantiles of the paper's training-length distribution (its Fig. 1
+    caption: median 3,891, P90 10,800, P99 20,000 tokens), log-linear between and beyond the three
+    published points, rounded up to 16 anchors and capped at 20480."""
+    import math
+    pts = [(0.5, 3891.0), (0.9, 10800.0), (0.99, 20000.0)]
+    out = []
+    for q in quantiles:
+        (q0, l0), (q1, l1) = (pts[0], pts[1]) if q <= pts[1][0] else (pts[1], pts[2])
+        t = (q - q0) / (q1 - q0)
+        L = math.exp(math.log(l0) + t * (math.log(l1) - math.log(l0)))
+        out.append(min(20480, max(16, int(math.ceil(L / 16.0)) * 16)))
+    return out
+
+
+def sweep(args) -> int:
+    """Throughput over sequence length with ONE tile map built for the maximum length: every shorter
+    sequence uses its prefix (the per-example crop of the amortized mask).  K=8, 64/8 heads, D=64,
+    segments of 2048 anchors; inputs are seeded N(0,1) bf16 drawn on the device (throughput only)."""
+    import torch
+
+    import paper_2602_01469_amd as pe
+    from peagle_inputs import useful_flops
+    pe.load_library()
+    torch.cuda.set_device(0)
+    K, Hq, Hkv, D, L_max = 8, 64, 8, 64, 20480
+    bounds = list(range(0, L_max, 2048)) + [L_max]
+    t0 = time.perf_counter()
+    tm = pe.peagle_build_tilemap(L_max, K, bounds, device=0)
+    build_ms = (time.perf_counter() - t0) * 1e3
+    stream = torch.cuda.current_stream()
+    qs = [0.1, 0.25, 0.5, 0.75, 0.9, 0.95, 0.99]
+    rows = []
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for q, L in zip(qs, trace_lengths(qs)):
+        T = L * K
+        mk = lambda h: torch.randn((T, h, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        qt, kt, vt, dot = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+        shape = pe.Shape(L, K, Hq, Hkv, D)
+        o, dq = torch.empty_like(qt), torch.empty_like(qt)
+        lse = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+        dk = torch.empty((T, Hkv, D), dtype=torch.float32, device="cuda")
+        dv = torch.empty_like(dk)
+        ws = torch.empty(pe.peagle_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+        S = len(bounds) - 1
+        step = lambda: pe.peagle_attn_step_partitioned(tm, shape, 0, S, qt, kt, vt, dot, o, lse, dq, dk, dv, None, None,
+                                                       ws, stream)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        n = 5
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / n
+        fl = useful_flops(L, K, Hq, D)
+        rows.append({"quantile": q, "L": L, "T": T, "ms_per_step": ms, "tflops": fl / (ms * 1e-3) / 1e12,
+                     "finite": bool(torch.isfinite(dk).all().item())})
+        del qt, kt, vt, dot, o, dq, lse, dk, dv, ws
+    print(json.dumps({"metric": "effective masked-attn TFLOP/s fwd+bwd over sequence length (one tile map, prefix views)",
+                      "unit": "TFLOP/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"length sweep at the trace quantiles, K={K} Hq={Hq} Hkv={Hkv} D={D}, "
+                                             f"tile map for L_max={L_max}, segments of 2048 anchors"},
+                      "tilemap_build_ms": build_ms, "sweep": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +141,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3_median")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-anchors", type=int, default=2048)
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline workload, time a sweep of sequence lengths on one tile map")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one 256 MiB device-to-device copy (reference dispatch for HBM byte counters)")
     ap.add_argument("--seg-anchors", type=int, default=None,
@@ -81,6 +151,9 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
+
+    if args.sweep:
+        return sweep(args)
 
     import torch
 
@@ -159,6 +232,7 @@ def main() -> int:
     dkdv_flops_per_launch = 8 * cfg.D * cfg.Hq * pairs / max(dkdv["launches_per_step"], 1)
     achieved = dkdv_flops_per_launch / (dkdv["avg_launch_ms"] * 1e-3) / 1e12
     props = torch.cuda.get_device_properties(0)
+    dinfo = pe.peagle_device_info()
     # tile pairs actually computed (128 rows x 64 keys each) vs useful pairs
     computed_pairs = (info["n_full"] + info["n_partial"]) * 128 * 64
     out = {
@@ -186,8 +260,8 @@ def main() -> int:
         "tilemap": {"device_bytes": info["device_bytes"], "n_masks": info["n_masks"], "n_full": info["n_full"],
                     "n_partial": info["n_partial"]},
         "kernels": kernels,
-        "device": {"name": props.name, "cus": props.multi_processor_count,
-                   "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
+        "device": {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "cus": dinfo["compute_units"],
+                   "clock_mhz": dinfo["clock_khz"] / 1e3},
         "roofline": {"bound": "mfma", "kernel": "dkdv_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": _read_traffic(cfg.name)},

@@ -205,6 +205,12 @@ int peagle_attn_step_profiled(const peagle_tilemap_t* tm, const peagle_shape_t* 
  */
 int peagle_measure_mfma_ceiling(void* stream, float* tflops);
 
+/*
+ * Measurement aid: compute-unit count and peak engine clock (kHz) of the current device, as the
+ * HIP runtime reports them (both host ints, out).
+ */
+int peagle_device_info(int32_t* compute_units, int32_t* clock_khz);
+
 /* Static, NUL-terminated description of a status code. */
 const char* peagle_strerror(int status);
 

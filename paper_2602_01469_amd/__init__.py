@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     peagle_attn_step_profiled,
     peagle_measure_mfma_ceiling,
     peagle_build_tilemap,
+    peagle_device_info,
     peagle_strerror,
     peagle_workspace_bytes,
 )

@@ -33,7 +33,7 @@ class _InfoC(C.Structure):
 EXPORTS = [
     "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
-    "peagle_attn_step_partitioned", "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_strerror",
+    "peagle_attn_step_partitioned", "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
 KERNEL_KINDS = ("fwd", "dq", "dkdv", "reduce")
@@ -82,6 +82,8 @@ def load_library():
     lib.peagle_attn_step_profiled.restype = C.c_int
     lib.peagle_measure_mfma_ceiling.argtypes = [vp, C.POINTER(C.c_float)]
     lib.peagle_measure_mfma_ceiling.restype = C.c_int
+    lib.peagle_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
+    lib.peagle_device_info.restype = C.c_int
     lib.peagle_strerror.argtypes = [C.c_int]
     lib.peagle_strerror.restype = C.c_char_p
     _lib = lib
@@ -271,3 +273,11 @@ def peagle_measure_mfma_ceiling(stream=None) -> float:
     if rc != 0:
         raise PeagleError(rc, "peagle_measure_mfma_ceiling")
     return float(out.value)
+
+
+def peagle_device_info() -> dict:
+    cus, khz = C.c_int32(0), C.c_int32(0)
+    rc = load_library().peagle_device_info(C.byref(cus), C.byref(khz))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_device_info")
+    return {"compute_units": int(cus.value), "clock_khz": int(khz.value)}

@@ -199,3 +199,14 @@ extern "C" int peagle_measure_mfma_ceiling(void* stream, float* tflops) {
   *tflops = 0.f;
   return peagle::measure_mfma_ceiling((hipStream_t)stream, tflops) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }
+
+extern "C" int peagle_device_info(int32_t* compute_units, int32_t* clock_khz) {
+  if (!compute_units || !clock_khz) return PEAGLE_ENULL;
+  int dev = 0, cus = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return PEAGLE_EHIP;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PEAGLE_EHIP;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess) return PEAGLE_EHIP;
+  *compute_units = cus;
+  *clock_khz = khz;
+  return PEAGLE_OK;
+}

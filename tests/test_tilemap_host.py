@@ -209,3 +209,11 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_NAME", "libdoes_not_exist.so")
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_trace_length_quantiles_hit_the_published_points():
+    """The benchmark's length sweep passes through the three quantiles the paper prints (Fig. 1 caption)."""
+    import bench
+    assert bench.trace_lengths([0.5, 0.9, 0.99]) == [3904, 10816, 20000]   # 3,891 / 10,800 / 20,000 rounded up to 16
+    ls = bench.trace_lengths([0.1, 0.25, 0.5, 0.75, 0.9, 0.95, 0.99])
+    assert ls == sorted(ls) and all(l % 16 == 0 for l in ls)
