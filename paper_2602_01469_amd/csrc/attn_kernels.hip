@@ -235,7 +235,7 @@ __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds,
 }
 
 template <int D, int NH>
-__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void fwd_kernel(FwdParams p) {
+__global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
 
@@ -396,7 +396,7 @@ __device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, 
 }
 
 template <int D, int NH>
-__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, 2) void dq_kernel(BwdParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
 
