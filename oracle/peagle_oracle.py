@@ -22,6 +22,13 @@ depth-major, ``t = d*L + i``; query head ``h`` uses KV head ``h // (Hq/Hkv)`` (t
 drafter is a LLaMA-3 style decoder, Sec. 2); the log-sum-exp is natural-log and
 includes the softmax scale.
 
+Conditional Drop-token sampling (the PARD paragraph of Sec. 3; position-count formula of
+Sec. 3.2) keeps only some positions at depths >= 1.  Because a kept position p at depth g needs
+p-1 at depth g-1 (Sec. 3.2, Challenge 2), the kept set is, per anchor, a prefix of its depths:
+anchor i keeps depths 0..n_i-1.  Every function below therefore also accepts an explicit token
+list ``tokens = (anchor[t], depth[t])`` in storage order; the mask is the same predicate
+evaluated on those coordinates.
+
 Everything is plain dense fp64: an explicit boolean mask evaluated element by element
 from the predicate, ``numpy`` matmuls, max-subtracted softmax.  The only blocking is
 over query rows, to bound memory; there is no tiling, fusion or reordering.
@@ -30,7 +37,11 @@ Pins (tests/test_oracle_pins.py): closed-form visible counts, causal reduction a
 depth 0 and at K=1 against an independent library routine, library autograd with an
 independently built mask, zero-query closed forms, finite differences, crop
 invariance, and the worked partition example of Sec. 3.2 / Fig. 4 for the segment
-assignment routine.  No function here is "parity unpinned".
+assignment routine.  The sampled-sequence path is pinned on that same worked example (its 38
+positions): token list against the printed position sets, mask against a brute-force rebuild
+from the dependency rules and against the dense mask restricted to kept positions, outputs
+against the dense problem's kept rows, gradients against library autograd, and Algorithm 1
+partitioning against the single pass.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -48,6 +59,8 @@ __all__ = [
     "segment_rows",
     "segment_keys",
     "attn_step_partitioned",
+    "attn_step_partitioned_sampled",
+    "cod_tokens",
     "partition_assign",
     "cod_position_count",
 ]
@@ -75,16 +88,37 @@ def token_coords(t, L: int):
     return t % L, t // L
 
 
-def element_mask(L: int, K: int, rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None) -> np.ndarray:
+def cod_tokens(depth_count: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Token list (anchor[t], depth[t]) of a drop-token sampled sequence in storage order:
+    depth-major, each depth holding the anchors that keep it, ascending (anchor i keeps depths
+    0 .. depth_count[i]-1)."""
+    n = np.asarray(depth_count)
+    assert (n >= 1).all()
+    anchors, depths = [], []
+    for g in range(int(n.max())):
+        keep = np.nonzero(n > g)[0]
+        anchors.append(keep)
+        depths.append(np.full(len(keep), g))
+    return np.concatenate(anchors), np.concatenate(depths)
+
+
+def element_mask(L: int, K: int, rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
+                 tokens: Optional[Tuple[np.ndarray, np.ndarray]] = None) -> np.ndarray:
     """Boolean mask M[r, c] over expanded positions, evaluated element by element.
 
-    ``rows`` / ``cols`` are token indices (default: all ``T = L*K``).
+    ``rows`` / ``cols`` are token indices (default: all).  ``tokens`` gives the (anchor, depth)
+    of every stored token for a sampled sequence; without it the sequence is dense, T = L*K.
     """
-    T = L * K
+    T = L * K if tokens is None else len(tokens[0])
     rows = np.arange(T) if rows is None else np.asarray(rows)
     cols = np.arange(T) if cols is None else np.asarray(cols)
-    i, d = token_coords(rows, L)
-    j, e = token_coords(cols, L)
+    if tokens is None:
+        i, d = token_coords(rows, L)
+        j, e = token_coords(cols, L)
+    else:
+        ta, td = np.asarray(tokens[0]), np.asarray(tokens[1])
+        i, d = ta[rows], td[rows]
+        j, e = ta[cols], td[cols]
     i = i[:, None]
     d = d[:, None]
     j = j[None, :]
@@ -109,7 +143,8 @@ def _kv_head(h: int, Hq: int, Hkv: int) -> int:
 
 def attn_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, L: int, K: int, scale: float,
                  rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
-                 row_block: int = 1024, return_probs: bool = False):
+                 row_block: int = 1024, return_probs: bool = False,
+                 tokens: Optional[Tuple[np.ndarray, np.ndarray]] = None):
     """O = softmax(scale * Q K^T + mask) V and LSE = ln sum exp(scale * q.k) over visible keys.
 
     q: [T, Hq, D]; k, v: [T, Hkv, D] (fp64).  ``rows``: token indices of the query rows
@@ -121,7 +156,8 @@ def attn_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, L: int, K: int, sc
     """
     T, Hq, D = q.shape
     Hkv = k.shape[1]
-    assert T == L * K and k.shape == v.shape and k.shape[0] == T and Hq % Hkv == 0
+    assert T == (L * K if tokens is None else len(tokens[0]))
+    assert k.shape == v.shape and k.shape[0] == T and Hq % Hkv == 0
     rows = np.arange(T) if rows is None else np.asarray(rows)
     cols = np.arange(T) if cols is None else np.asarray(cols)
     O = np.zeros((len(rows), Hq, D), dtype=np.float64)
@@ -129,7 +165,7 @@ def attn_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, L: int, K: int, sc
     P_all = np.zeros((Hq, len(rows), len(cols)), dtype=np.float64) if return_probs else None
     pos = 0
     for rb in _row_blocks(rows, row_block):
-        M = element_mask(L, K, rb, cols)
+        M = element_mask(L, K, rb, cols, tokens)
         for h in range(Hq):
             g = _kv_head(h, Hq, Hkv)
             S = scale * (q[rb, h, :] @ k[cols, g, :].T)
@@ -150,7 +186,7 @@ def attn_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray, L: int, K: int, sc
 
 def attn_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, do: np.ndarray, L: int, K: int, scale: float,
                   rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
-                  row_block: int = 1024) -> Dict[str, np.ndarray]:
+                  row_block: int = 1024, tokens: Optional[Tuple[np.ndarray, np.ndarray]] = None) -> Dict[str, np.ndarray]:
     """Gradients of sum(O * dO) for the rows in ``rows`` (default all).
 
     With P the softmax probabilities: dV = P^T dO, dP = dO V^T, Delta = rowsum(P * dP),
@@ -171,7 +207,7 @@ def attn_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, do: np.ndarray, L
     dV = np.zeros((T, Hkv, D))
     pos = 0
     for rb in _row_blocks(rows, row_block):
-        M = element_mask(L, K, rb, cols)
+        M = element_mask(L, K, rb, cols, tokens)
         sl = slice(pos, pos + len(rb))
         for h in range(Hq):
             g = _kv_head(h, Hq, Hkv)
@@ -241,6 +277,35 @@ def attn_step_partitioned(q, k, v, do, L: int, K: int, scale: float, seg_bounds:
         dK += r["dK"]
         dV += r["dV"]
     return {"O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
+
+
+def attn_step_partitioned_sampled(q, k, v, do, depth_count: Sequence[int], K: int, scale: float, S: int,
+                                  row_block: int = 1024) -> Dict[str, np.ndarray]:
+    """Within-sequence gradient accumulation for a drop-token sampled sequence, with the segment of
+    every position taken from Algorithm 1 (:func:`partition_assign`) and each segment holding its
+    own positions plus the cumulative depth-0 context N_s."""
+    ta, td = cod_tokens(depth_count)
+    L = len(depth_count)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    positions = [sorted((ta[td == g] + g).tolist()) for g in range(int(td.max()) + 1)]
+    A, N = partition_assign(positions, S, L)
+    seg_of_token = np.array([A[d][a + d] for a, d in zip(ta.tolist(), td.tolist())])
+    tok_of = {(a, d): t for t, (a, d) in enumerate(zip(ta.tolist(), td.tolist()))}
+    out = {"O": np.zeros((T, Hq, D)), "LSE": np.zeros((Hq, T)), "dQ": np.zeros((T, Hq, D)),
+           "dK": np.zeros((T, Hkv, D)), "dV": np.zeros((T, Hkv, D))}
+    for s in range(S):
+        rows = np.nonzero(seg_of_token == s)[0]
+        cols = np.array(sorted(set(rows.tolist()) | {tok_of[(p, 0)] for p in N[s]}))
+        if len(rows) == 0:
+            continue
+        r = attn_backward(q, k, v, do, L, K, scale, rows=rows, cols=cols, row_block=row_block, tokens=(ta, td))
+        out["O"][rows] = r["O"]
+        out["LSE"][:, rows] = r["LSE"]
+        out["dQ"][rows] = r["dQ"]
+        out["dK"] += r["dK"]
+        out["dV"] += r["dV"]
+    return out
 
 
 def partition_assign(positions: Sequence[Sequence[int]], S: int, L: int) -> Tuple[List[Dict[int, int]], List[List[int]]]:

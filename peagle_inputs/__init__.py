@@ -4,7 +4,8 @@ This module holds no attention arithmetic: it names the workload shapes, draws t
 random tensors and rounds them to bf16 bit patterns.  Both sides consume exactly
 these bytes.
 """
-from .gen import CONFIGS, WorkloadConfig, bf16_bits_to_f64, f32_to_bf16_bits, make_inputs, useful_pairs, useful_flops
+from .gen import (CONFIGS, WorkloadConfig, bf16_bits_to_f64, cod_depth_counts, f32_to_bf16_bits, make_inputs,
+                  make_inputs_tokens, useful_flops, useful_pairs)
 
 __all__ = [
     "CONFIGS",
@@ -12,6 +13,8 @@ __all__ = [
     "bf16_bits_to_f64",
     "f32_to_bf16_bits",
     "make_inputs",
+    "make_inputs_tokens",
+    "cod_depth_counts",
     "useful_pairs",
     "useful_flops",
 ]

@@ -96,3 +96,32 @@ def useful_pairs(L: int, K: int) -> int:
 def useful_flops(L: int, K: int, Hq: int, D: int) -> int:
     """Forward 4*D and backward 10*D flops per unmasked pair per query head."""
     return 14 * D * Hq * useful_pairs(L, K)
+
+
+def cod_depth_counts(L: int, K: int, retention: float, seed: int) -> np.ndarray:
+    """Depths kept per anchor under Conditional Drop-token sampling (PARD paragraph of the paper's
+    Sec. 3): depth 0 keeps all L positions, depth g keeps round(retention * |depth g-1|) of the
+    anchors kept at depth g-1, chosen uniformly at random (a position needs its predecessor at the
+    previous depth, so the kept sets are nested per anchor).  Returns int32[L] with values in 1..K."""
+    rng = np.random.default_rng(seed)
+    count = np.ones(L, dtype=np.int32)
+    alive = np.arange(L)
+    for g in range(1, K):
+        n_keep = int(round(retention * len(alive)))
+        if n_keep == 0:
+            break
+        alive = np.sort(rng.choice(alive, size=n_keep, replace=False))
+        count[alive] = g + 1
+    return count
+
+
+def make_inputs_tokens(cfg: WorkloadConfig, T: int, seed_offset: int = 1000):
+    """Q, K, V, dO bit patterns for a sequence of T stored tokens (sampled layouts), same recipe as make_inputs."""
+    rng = np.random.default_rng(cfg.seed + seed_offset)
+    out = []
+    for H in (cfg.Hq, cfg.Hkv, cfg.Hkv, cfg.Hq):
+        x = rng.standard_normal(size=(T, H, cfg.D), dtype=np.float32)
+        if cfg.value_scale != 1.0:
+            x *= np.float32(cfg.value_scale)
+        out.append(f32_to_bf16_bits(x))
+    return tuple(out)

@@ -337,3 +337,104 @@ def test_make_inputs_shapes_and_determinism():
     assert a[0].dtype == np.uint16
     x = bf16_bits_to_f64(a[0])
     assert abs(x.mean()) < 0.02 and abs(x.std() - 1.0) < 0.02
+
+
+# ----------------------------------------------------------------------------- drop-token sampled sequences
+
+def _paper_example_depth_counts():
+    """Per-anchor depth counts of the worked example of Sec. 3.2 (positions at depth g minus g = anchors)."""
+    d, _ = _read_partition_example()
+    count = np.ones(d["n"], dtype=int)
+    for g in range(1, d["K"]):
+        for p in d[f"depth{g}"]:
+            assert count[p - g] == g          # the predecessor (p-1, g-1) is kept: sets are nested per anchor
+            count[p - g] = g + 1
+    return count, d
+
+
+def test_sampled_tokens_of_paper_example():
+    count, d = _paper_example_depth_counts()
+    ta, td = orc.cod_tokens(count)
+    assert len(ta) == d["total"] == 38
+    for g in range(d["K"]):
+        assert sorted((ta[td == g] + g).tolist()) == d[f"depth{g}"]     # storage order: depth-major, positions ascending
+
+
+def _sampled_mask_brute_force(count, K):
+    """Mask over stored tokens rebuilt from the dependency rules in position coordinates."""
+    ta, td = orc.cod_tokens(count)
+    pos = {(int(a) + int(g), int(g)): t for t, (a, g) in enumerate(zip(ta, td))}   # (position, depth) -> token
+    T = len(ta)
+    M = np.zeros((T, T), dtype=bool)
+    for (p, g), r in pos.items():
+        for q0 in range(0, p - g + 1):
+            M[r, pos[(q0, 0)]] = True
+        pp, gg = p, g
+        while gg >= 1:
+            M[r, pos[(pp, gg)]] = True       # exists by nestedness
+            pp, gg = pp - 1, gg - 1
+    return M
+
+
+def test_sampled_mask_matches_dependency_rules_and_is_a_submask_of_the_dense_one():
+    count, d = _paper_example_depth_counts()
+    K, L = d["K"], d["n"]
+    ta, td = orc.cod_tokens(count)
+    M = orc.element_mask(L, K, tokens=(ta, td))
+    assert np.array_equal(M, _sampled_mask_brute_force(count, K))
+    dense = orc.element_mask(L, K)
+    idx = td * L + ta                                                   # same (anchor, depth) in the dense layout
+    assert np.array_equal(M, dense[np.ix_(idx, idx)])
+    assert np.array_equal(M.sum(axis=1), ta + 1 + td)                   # visible count is unchanged by sampling
+
+
+def test_sampled_attention_equals_dense_attention_on_kept_rows():
+    """Dropping positions removes rows and the keys only those rows could see, so a kept row's output
+    equals the dense problem's output for the same (anchor, depth)."""
+    count, d = _paper_example_depth_counts()
+    K, L, Hq, Hkv, D = d["K"], d["n"], 2, 1, 8
+    ta, td = orc.cod_tokens(count)
+    qd, kd, vd, dod = _rand(L, K, Hq, Hkv, D, 21)
+    idx = td * L + ta
+    O, LSE = orc.attn_forward(qd[idx], kd[idx], vd[idx], L, K, 0.4, tokens=(ta, td))
+    Od, LSEd = orc.attn_forward(qd, kd, vd, L, K, 0.4)
+    assert np.allclose(O, Od[idx], atol=1e-13) and np.allclose(LSE, LSEd[:, idx], atol=1e-13)
+    # gradients against torch autograd with the brute-force mask
+    r = orc.attn_backward(qd[idx], kd[idx], vd[idx], dod[idx], L, K, 0.4, tokens=(ta, td))
+    M = torch.from_numpy(_sampled_mask_brute_force(count, K))
+    tq = torch.from_numpy(qd[idx]).requires_grad_()
+    tk = torch.from_numpy(kd[idx]).requires_grad_()
+    tv = torch.from_numpy(vd[idx]).requires_grad_()
+    o = torch.nn.functional.scaled_dot_product_attention(
+        tq.permute(1, 0, 2)[None], tk.permute(1, 0, 2).repeat_interleave(2, 0)[None],
+        tv.permute(1, 0, 2).repeat_interleave(2, 0)[None], attn_mask=M, scale=0.4)[0].permute(1, 0, 2)
+    (o * torch.from_numpy(dod[idx])).sum().backward()
+    for name, t in (("dQ", tq), ("dK", tk), ("dV", tv)):
+        assert np.allclose(r[name], t.grad.numpy(), atol=1e-11), name
+
+
+def test_sampled_partition_by_algorithm_1_equals_single_pass():
+    count, d = _paper_example_depth_counts()
+    K, L, Hq, Hkv, D = d["K"], d["n"], 2, 1, 8
+    ta, td = orc.cod_tokens(count)
+    rng = np.random.default_rng(22)
+    T = len(ta)
+    q, k, v, do = (rng.standard_normal((T, Hq, D)), rng.standard_normal((T, Hkv, D)), rng.standard_normal((T, Hkv, D)),
+                   rng.standard_normal((T, Hq, D)))
+    full = orc.attn_backward(q, k, v, do, L, K, 0.3, tokens=(ta, td))
+    for S in (2, 4):
+        part = orc.attn_step_partitioned_sampled(q, k, v, do, count, K, 0.3, S)
+        for name in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.allclose(full[name], part[name], atol=1e-13), (S, name)
+
+
+def test_cod_depth_counts_follow_geometric_retention():
+    from peagle_inputs import cod_depth_counts
+    L, K, r = 8192, 8, 0.8
+    c = cod_depth_counts(L, K, r, seed=5)
+    assert c.min() >= 1 and c.max() <= K
+    sizes = [(c > g).sum() for g in range(K)]
+    assert sizes[0] == L
+    for g in range(1, K):
+        assert sizes[g] == round(r * sizes[g - 1])
+    assert abs(sum(sizes) - orc.cod_position_count(L, K, r)) < K          # the paper's n(1-r^K)/(1-r), up to rounding
