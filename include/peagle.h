@@ -175,6 +175,45 @@ int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_
                                  void* o, float* lse, void* dq, float* dk_acc, float* dv_acc, void* dk_bf16,
                                  void* dv_bf16, void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * Drop-token sampled sequences (Conditional Drop-token sampling, PARD paragraph of Sec. 3: depth g
+ * keeps a geometrically shrinking subset of positions, n(1-r^K)/(1-r) in total, Sec. 3.2).  A kept
+ * position p at depth g needs position p-1 at depth g-1 (Sec. 3.2, Challenge 2), so per anchor the
+ * kept depths are a prefix: anchor i keeps depths 0 .. depth_count[i]-1.
+ *
+ *   depth_count  host, int32[L], each in [1, K]
+ *   device       HIP device ordinal for the device copy of the token table, or -1 (host-only)
+ *
+ * Storage order of every [T, ...] tensor of such a sequence: depth-major, and within a depth the
+ * anchors that keep it in ascending order; T = sum(depth_count) (peagle_sampling_tokens).
+ */
+typedef struct peagle_sampling peagle_sampling_t;
+
+int peagle_build_sampling(const int32_t* depth_count, int32_t L, int32_t K, int32_t device,
+                          peagle_sampling_t** out);
+
+void peagle_sampling_destroy(peagle_sampling_t* sm);
+
+/* Stored tokens T of the sampled sequence (0 if sm is NULL). */
+int64_t peagle_sampling_tokens(const peagle_sampling_t* sm);
+
+/* Host copy of the token table: table_out (host) receives int32[K][L], the token of (depth, anchor)
+ * or -1 where the position was dropped. */
+int peagle_sampling_table(const peagle_sampling_t* sm, int32_t* table_out);
+
+/*
+ * peagle_attn_step_partitioned for a drop-token sampled sequence: same tile map (the mask of the
+ * sampled sequence is the dense mask restricted to kept positions), same segment passes and
+ * dK/dV accumulation (Sec. 3.2; a position is computed in the segment of its anchor, the depth-0
+ * context N_s is cumulative).  shape->L and shape->K must equal the sampling's; every [T, ...]
+ * tensor has T = peagle_sampling_tokens(sm) rows, lse is fp32 [Hq, T].  The workspace size is
+ * that of the dense shape, peagle_workspace_bytes().
+ */
+int peagle_attn_step_sampled(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const peagle_sampling_t* sm,
+                             int32_t seg_begin, int32_t seg_end, const void* q, const void* k, const void* v,
+                             const void* d_o, void* o, float* lse, void* dq, float* dk_acc, float* dv_acc,
+                             void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes, void* stream);
+
 /* Kernel kinds reported by peagle_attn_step_profiled. */
 #define PEAGLE_KERNEL_FWD 0      /* forward (O, LSE) */
 #define PEAGLE_KERNEL_DQ 1       /* Delta and dQ */

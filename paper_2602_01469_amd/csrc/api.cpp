@@ -2,6 +2,7 @@
 // paper: one forward+backward pass per segment, dK/dV accumulated across segments in fp32).
 #include <climits>
 #include <cmath>
+#include <cstdint>
 
 #include "attn_kernels.h"
 #include "peagle.h"
@@ -44,8 +45,11 @@ int check_shape(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
   return PEAGLE_OK;
 }
 
-FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
-                   const void* k, const void* v, void* o, float* lse) {
+// Token count and token table of the call: a dense sequence stores all L*K positions in order.
+int tokens_of(const peagle_shape_t* s, const peagle_sampling_t* sm) { return sm ? (int)sm->T : s->L * s->K; }
+
+FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const peagle_sampling_t* sm,
+                   const SegRange& sr, const void* q, const void* k, const void* v, void* o, float* lse) {
   FwdParams p{};
   p.q = (const __bf16*)q;
   p.k = (const __bf16*)k;
@@ -53,8 +57,9 @@ FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   p.o = (__bf16*)o;
   p.lse = lse;
   p.tm = tm->dview;
+  p.tm.tok_table = sm ? sm->dev_table : nullptr;
   p.L = s->L;
-  p.T = s->L * s->K;
+  p.T = tokens_of(s, sm);
   p.Hq = s->Hq;
   p.Hkv = s->Hkv;
   p.rt_lo = sr.rt_lo;
@@ -63,9 +68,10 @@ FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   return p;
 }
 
-BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
-                   const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
-                   float* dk_acc, float* dv_acc, void* workspace, int chain_accumulate) {
+BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const peagle_sampling_t* sm,
+                   const SegRange& sr, const void* q, const void* k, const void* v, const void* o,
+                   const void* d_o, const float* lse, void* dq, float* dk_acc, float* dv_acc, void* workspace,
+                   int chain_accumulate) {
   const WsLayout w = ws_layout(s);
   BwdParams p{};
   p.q = (const __bf16*)q;
@@ -82,8 +88,9 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   p.dk_part = (float*)((char*)workspace + w.dk_off);
   p.dv_part = (float*)((char*)workspace + w.dv_off);
   p.tm = tm->dview;
+  p.tm.tok_table = sm ? sm->dev_table : nullptr;
   p.L = s->L;
-  p.T = s->L * s->K;
+  p.T = tokens_of(s, sm);
   p.Hq = s->Hq;
   p.Hkv = s->Hkv;
   p.L64 = w.L64;
@@ -114,7 +121,7 @@ extern "C" int peagle_attn_fwd(const peagle_tilemap_t* tm, const peagle_shape_t*
   rc = peagle::resolve_segment(tm, shape->L, seg, &sr);
   if (rc != PEAGLE_OK) return rc;
   if (tm->device < 0) return PEAGLE_ENODEVICE;
-  const FwdParams p = make_fwd(tm, shape, sr, q, k, v, o, lse);
+  const FwdParams p = make_fwd(tm, shape, nullptr, sr, q, k, v, o, lse);
   return peagle::launch_fwd(p, shape->D, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }
 
@@ -131,37 +138,39 @@ extern "C" int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t*
   if (rc != PEAGLE_OK) return rc;
   if (!workspace || ws_bytes < ws_layout(shape).total) return PEAGLE_EWORKSPACE;
   if (tm->device < 0) return PEAGLE_ENODEVICE;
-  const BwdParams p = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, accumulate);
+  const BwdParams p =
+      make_bwd(tm, shape, nullptr, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, accumulate);
   const int acc_below = accumulate ? INT_MAX : 0;
   return peagle::launch_bwd(p, shape->D, sr.a_hi, acc_below, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK
                                                                                                    : PEAGLE_EHIP;
 }
 
-static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin, int32_t seg_end,
-                     const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
+static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const peagle_sampling_t* sm,
+                     int32_t seg_begin, int32_t seg_end, const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
                      float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes,
                      void* stream, peagle::KernelTimer* timer) {
   int rc = check_shape(tm, shape);
   if (rc != PEAGLE_OK) return rc;
   if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
   if (seg_begin < 0 || seg_end > tm->S || seg_begin > seg_end) return PEAGLE_EINVAL;
+  if (sm && (sm->L != shape->L || sm->K != shape->K)) return PEAGLE_ESHAPE;
   if (!workspace || ws_bytes < ws_layout(shape).total) return PEAGLE_EWORKSPACE;
-  if (tm->device < 0) return PEAGLE_ENODEVICE;
+  if (tm->device < 0 || (sm && sm->device != tm->device)) return PEAGLE_ENODEVICE;
   hipStream_t st = (hipStream_t)stream;
   for (int32_t s = seg_begin; s < seg_end; ++s) {
     SegRange sr;
     rc = peagle::resolve_segment(tm, shape->L, s, &sr);
     if (rc != PEAGLE_OK) return rc;
     if (sr.a_lo >= sr.a_hi) continue;  // segment lies beyond the cropped length
-    const FwdParams fp = make_fwd(tm, shape, sr, q, k, v, o, lse);
+    const FwdParams fp = make_fwd(tm, shape, sm, sr, q, k, v, o, lse);
     if (peagle::launch_fwd(fp, shape->D, st, timer) != hipSuccess) return PEAGLE_EHIP;
     // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
     // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
-    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
+    const BwdParams bp = make_bwd(tm, shape, sm, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
     if (peagle::launch_bwd(bp, shape->D, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
   }
   if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
-    const size_t n = (size_t)shape->L * shape->K * shape->Hkv * shape->D;
+    const size_t n = (size_t)tokens_of(shape, sm) * shape->Hkv * shape->D;
     if (dk_bf16 && peagle::launch_cast_bf16(dk_acc, dk_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
     if (dv_bf16 && peagle::launch_cast_bf16(dv_acc, dv_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
   }
@@ -173,7 +182,17 @@ extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const pe
                                             const void* v, const void* d_o, void* o, float* lse, void* dq,
                                             float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
                                             void* workspace, size_t ws_bytes, void* stream) {
-  return step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
+  return step_impl(tm, shape, nullptr, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16,
+                   dv_bf16, workspace, ws_bytes, stream, nullptr);
+}
+
+extern "C" int peagle_attn_step_sampled(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
+                                        const peagle_sampling_t* sm, int32_t seg_begin, int32_t seg_end,
+                                        const void* q, const void* k, const void* v, const void* d_o, void* o,
+                                        float* lse, void* dq, float* dk_acc, float* dv_acc, void* dk_bf16,
+                                        void* dv_bf16, void* workspace, size_t ws_bytes, void* stream) {
+  if (!sm) return PEAGLE_ENULL;
+  return step_impl(tm, shape, sm, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
                    workspace, ws_bytes, stream, nullptr);
 }
 
@@ -188,8 +207,8 @@ extern "C" int peagle_attn_step_profiled(const peagle_tilemap_t* tm, const peagl
     profile->launches[i] = 0;
   }
   peagle::KernelTimer timer;
-  int rc = step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr,
-                     workspace, ws_bytes, stream, &timer);
+  int rc = step_impl(tm, shape, nullptr, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr,
+                     nullptr, workspace, ws_bytes, stream, &timer);
   if (rc != PEAGLE_OK) return rc;
   return timer.collect(profile->ms, profile->launches) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }

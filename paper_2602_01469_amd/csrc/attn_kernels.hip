@@ -35,7 +35,12 @@ __device__ __forceinline__ bool key_token(const DeviceTileMap& tm, int kt, int r
   const int e = ck / tm.A;
   const int j = R * tm.A + (ck - e * tm.A);
   tok = (1 + e) * L + j;
-  return ck < tm.A * (tm.K - 1) && j < L;
+  bool ok = ck < tm.A * (tm.K - 1) && j < L;
+  if (tm.tok_table) {  // sampled sequence: the position may have been dropped
+    tok = ok ? tm.tok_table[tok] : -1;
+    ok = tok >= 0;
+  }
+  return ok;
 }
 
 // Token of row `r` of row tile `rt`; false if the row is padding or beyond the sequence.
@@ -43,7 +48,12 @@ __device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r
   const int d = r / tm.A;
   const int i = rt * tm.A + (r - d * tm.A);
   tok = d * L + i;
-  return d < tm.K && i < L;
+  bool ok = d < tm.K && i < L;
+  if (tm.tok_table) {
+    tok = ok ? tm.tok_table[tok] : -1;
+    ok = tok >= 0;
+  }
+  return ok;
 }
 
 __device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
@@ -91,7 +101,7 @@ struct RowDmaLane {
   static constexpr int kBlocks = kRowsPerTile * D * 2 / 1024;
   static constexpr int kPer = kBlocks / NW;
   static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
-  int tok0[kPer];    // d*L + a : token of the row in row tile 0
+  int tok0[kPer];    // d*L + a : token of the row in row tile 0 (index into the token table if sampled)
   int a[kPer];       // anchor offset inside the row tile; >= A*K... marks a padding row via a huge value
   int chunk[kPer];   // element offset of the logical 16-byte chunk this lane fetches
   int stat_tok0, stat_a;  // same for the row whose per-row statistic this lane copies (waves 0..3)
@@ -120,8 +130,13 @@ __device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base,
   const int i0 = rt * tm.A;
 #pragma unroll
   for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
-    const bool ok = i0 + rl.a[i] < L;  // padding rows carry a huge anchor offset
-    const size_t off = ((size_t)(ok ? rl.tok0[i] + i0 : 0) * Hq + h) * D + rl.chunk[i];
+    bool ok = i0 + rl.a[i] < L;  // padding rows carry a huge anchor offset
+    int tok = rl.tok0[i] + i0;
+    if (tm.tok_table) {
+      tok = ok ? tm.tok_table[tok] : -1;
+      ok = tok >= 0;
+    }
+    const size_t off = ((size_t)(ok ? tok : 0) * Hq + h) * D + rl.chunk[i];
     dma16(ok ? (const void*)(base + off) : tm.zeros, lds_tile + (i * NW + wave) * 1024);
   }
 }
@@ -132,8 +147,13 @@ template <int D, int NW>
 __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base, int T, int h, const DeviceTileMap& tm,
                                              const RowDmaLane<D, NW>& rl, int rt, int L, int half) {
   const int i0 = rt * tm.A;
-  const bool ok = i0 + rl.stat_a < L;
-  dma4(ok ? (const void*)(base + (size_t)h * T + rl.stat_tok0 + i0) : tm.zeros,
+  bool ok = i0 + rl.stat_a < L;
+  int tok = rl.stat_tok0 + i0;
+  if (tm.tok_table) {
+    tok = ok ? tm.tok_table[tok] : -1;
+    ok = tok >= 0;
+  }
+  dma4(ok ? (const void*)(base + (size_t)h * T + tok) : tm.zeros,
        reinterpret_cast<char*>(lds_stat + half * 64));
 }
 
@@ -396,7 +416,7 @@ __device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, 
 }
 
 template <int D, int NH>
-__global__ __launch_bounds__(256, 2) void dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
 

@@ -227,6 +227,67 @@ extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
   delete tm;
 }
 
+extern "C" int peagle_build_sampling(const int32_t* depth_count, int32_t L, int32_t K, int32_t device,
+                                     peagle_sampling_t** out) {
+  if (!out) return PEAGLE_ENULL;
+  *out = nullptr;
+  if (!depth_count) return PEAGLE_ENULL;
+  if (L < 1 || K < 1 || device < -1) return PEAGLE_EINVAL;
+  if (K > peagle::kRowsPerTile) return PEAGLE_EUNSUPPORTED;
+  if ((int64_t)L * K > INT32_MAX) return PEAGLE_EINVAL;
+  for (int32_t i = 0; i < L; ++i)
+    if (depth_count[i] < 1 || depth_count[i] > K) return PEAGLE_EINVAL;
+  peagle_sampling* sm = new (std::nothrow) peagle_sampling();
+  if (!sm) return PEAGLE_EHIP;
+  sm->L = L;
+  sm->K = K;
+  sm->table.assign((size_t)L * K, -1);
+  int32_t next = 0;
+  for (int32_t g = 0; g < K; ++g)
+    for (int32_t i = 0; i < L; ++i)
+      if (depth_count[i] > g) sm->table[(size_t)g * L + i] = next++;
+  sm->T = next;
+  if (device >= 0) {
+    int prev = 0;
+    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) {
+      delete sm;
+      return PEAGLE_EHIP;
+    }
+    const size_t bytes = sm->table.size() * sizeof(int32_t);
+    hipError_t err = hipMalloc((void**)&sm->dev_table, bytes);
+    if (err == hipSuccess) err = hipMemcpy(sm->dev_table, sm->table.data(), bytes, hipMemcpyHostToDevice);
+    (void)hipSetDevice(prev);
+    if (err != hipSuccess) {
+      if (sm->dev_table) (void)hipFree(sm->dev_table);
+      delete sm;
+      return PEAGLE_EHIP;
+    }
+    sm->device = device;
+  }
+  *out = sm;
+  return PEAGLE_OK;
+}
+
+extern "C" void peagle_sampling_destroy(peagle_sampling_t* sm) {
+  if (!sm) return;
+  if (sm->dev_table) {
+    int prev = 0;
+    if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(sm->device) == hipSuccess) {
+      (void)hipFree(sm->dev_table);
+      (void)hipSetDevice(prev);
+    }
+  }
+  delete sm;
+}
+
+extern "C" int64_t peagle_sampling_tokens(const peagle_sampling_t* sm) { return sm ? sm->T : 0; }
+
+extern "C" int peagle_sampling_table(const peagle_sampling_t* sm, int32_t* table_out) {
+  if (!sm || !table_out) return PEAGLE_ENULL;
+  std::memcpy(table_out, sm->table.data(), sm->table.size() * sizeof(int32_t));
+  return PEAGLE_OK;
+}
+
 extern "C" int peagle_tilemap_info(const peagle_tilemap_t* tm, peagle_tilemap_info_t* info) {
   if (!tm || !info) return PEAGLE_ENULL;
   info->L_max = tm->L_max;

@@ -31,6 +31,8 @@ struct DeviceTileMap {
   const int32_t* key_seg_ptr; // [n_key_tiles][S + 1]  offsets into key_entries: where each segment's row tiles start
   const uint32_t* masks;      // [n_masks][128][2]
   const void* zeros;          // 256 zero bytes: source of rows that do not exist, for direct-to-LDS loads
+  const int32_t* tok_table;   // per call, not part of the map: [K][L] token of (depth, anchor) of a drop-token
+                              // sampled sequence, -1 where the position was dropped; null for a dense sequence
   int32_t A, K, S, n_row_tiles, n_d0, n_csub, n_key_tiles;
 };
 
@@ -52,6 +54,16 @@ struct peagle_tilemap {
   void* dev_blob = nullptr;                      // one allocation holding all device arrays
   int64_t dev_bytes = 0;
   peagle::DeviceTileMap dview{};
+};
+
+// Drop-token sampled sequence (Conditional Drop-token sampling, PARD paragraph of Sec. 3): anchor i
+// keeps depths 0 .. depth_count[i]-1; tokens are stored depth-major, kept anchors ascending.
+struct peagle_sampling {
+  int32_t L = 0, K = 0;
+  int64_t T = 0;                                 // stored tokens
+  std::vector<int32_t> table;                    // [K][L], -1 = dropped
+  int32_t device = -1;
+  int32_t* dev_table = nullptr;
 };
 
 namespace peagle {

@@ -326,3 +326,83 @@ def test_c5_p99_stress_prefix_and_samples():
         L, K, Hq, Hkv, D, scale = cfg.L, cfg.K, grp, 1, cfg.D, cfg.scale
 
     _sampled_check(_Cfg, got_g, qb[:, hs], kb[:, g:g + 1], vb[:, g:g + 1], dob[:, hs], g=0, n_anchor_samples=4)
+
+
+# ----------------------------------------------------------------------------- drop-token sampled sequences
+
+def _paper_example_counts():
+    """Per-anchor depth counts of the n=16, K=4 worked example of Sec. 3.2 (38 positions)."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "partition_example.txt")
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            tok = line.split("#")[0].split()
+            if tok and tok[0] != "assign":
+                vals[tok[0]] = [int(x) for x in tok[1:]]
+    n, K = vals["n"][0], vals["K"][0]
+    count = np.ones(n, dtype=np.int32)
+    for g in range(1, K):
+        for p in vals[f"depth{g}"]:
+            count[p - g] = g + 1
+    assert count.sum() == vals["total"][0]
+    return count, K
+
+
+SAMPLED = [
+    # name, L, K, Hq, Hkv, D, retention, seed, bounds, L_max
+    ("paper_example", None, 4, 2, 1, 64, None, 300, None, None),
+    ("paper_example_two_segments", None, 4, 2, 1, 64, None, 305, [0, 32, 64], 64),
+    ("r08_k8", 200, 8, 4, 2, 64, 0.8, 310, None, None),
+    ("r08_k8_segments_cropped", 219, 8, 4, 2, 64, 0.8, 320, [0, 64, 128, 256], 256),
+    ("r05_k4_several_tiles", 700, 4, 4, 2, 64, 0.5, 330, [0, 256, 512, 700], None),
+    ("r08_d128", 150, 8, 2, 1, 128, 0.8, 340, [0, 64, 150], None),
+    ("nothing_dropped", 100, 4, 2, 2, 64, 1.0, 350, None, None),
+    ("only_depth0_kept", 100, 4, 2, 2, 64, 0.0, 360, None, None),
+    ("k3_padding_rows", 90, 3, 2, 1, 64, 0.7, 370, None, None),
+]
+
+
+@pytest.mark.parametrize("name,L,K,Hq,Hkv,D,ret,seed,bounds,L_max", SAMPLED, ids=[c[0] for c in SAMPLED])
+def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bounds, L_max):
+    """Conditional Drop-token sampled sequences: every output of the sampled step against the oracle
+    evaluated on the explicit token list (single pass), and - where segments are given - against
+    the oracle's Algorithm 1 partitioned run."""
+    from gpu_harness import SampledRun
+    from peagle_inputs import cod_depth_counts
+    if ret is None:
+        count, K = _paper_example_counts()
+        L = len(count)
+    else:
+        count = cod_depth_counts(L, K, ret, seed)
+    print(f"case {name}: L={L} K={K} Hq={Hq} Hkv={Hkv} D={D} retention={ret} seed={seed} bounds={bounds} "
+          f"L_max={L_max} tokens={int(count.sum())}", flush=True)
+    ta, td = orc.cod_tokens(count)
+    T = len(ta)
+    qb, kb, vb, dob = (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1), rand_bits((T, Hkv, D), seed + 2),
+                       rand_bits((T, Hq, D), seed + 3))
+    tm = pe.peagle_build_tilemap(L_max or L, K, bounds, device=0)
+    S = 1 if bounds is None else len(bounds) - 1
+    r = SampledRun(tm, count, K, Hq, Hkv, D, qb, kb, vb, dob)
+    assert r.sm.T == T
+    tab = r.sm.table()
+    assert np.array_equal(tab[td, ta], np.arange(T)) and (tab >= 0).sum() == T      # storage order of the oracle
+    dkb = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    dvb = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    r.step(0, S, dkb, dvb)
+    got = r.results()
+    q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    ref = orc.attn_backward(q, k, v, do, L, K, r.shape.scale, tokens=(ta, td))
+    _check_against_oracle(got, ref, name)
+    assert np.array_equal(bf16_to_f64(dkb), bf16_to_f64(r.dk.to(torch.bfloat16)))
+    assert np.array_equal(bf16_to_f64(dvb), bf16_to_f64(r.dv.to(torch.bfloat16)))
+    if S > 1:
+        part = orc.attn_step_partitioned_sampled(q, k, v, do, count, K, r.shape.scale, S)
+        _check_against_oracle(got, part, name + " vs Algorithm 1 partition")
+    if ret == 1.0:
+        # nothing dropped: same storage order as the dense layout, and the dense entry point agrees bit for bit
+        d = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        d.step(0, S)
+        gd = d.results()
+        for n in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.array_equal(gd[n], got[n]), n

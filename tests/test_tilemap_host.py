@@ -217,3 +217,52 @@ def test_trace_length_quantiles_hit_the_published_points():
     assert bench.trace_lengths([0.5, 0.9, 0.99]) == [3904, 10816, 20000]   # 3,891 / 10,800 / 20,000 rounded up to 16
     ls = bench.trace_lengths([0.1, 0.25, 0.5, 0.75, 0.9, 0.95, 0.99])
     assert ls == sorted(ls) and all(l % 16 == 0 for l in ls)
+
+
+# ----------------------------------------------------------------------------- drop-token sampling handle (host)
+
+def test_sampling_table_matches_the_oracle_token_order():
+    from oracle import peagle_oracle as orc
+    from peagle_inputs import cod_depth_counts
+    for L, K, r, seed in [(16, 4, 0.6, 1), (300, 8, 0.8, 2), (50, 3, 0.0, 3), (64, 5, 1.0, 4)]:
+        count = cod_depth_counts(L, K, r, seed)
+        sm = pe.peagle_build_sampling(count, K, device=-1)
+        ta, td = orc.cod_tokens(count)
+        tab = sm.table()
+        assert sm.T == len(ta) == int(count.sum())
+        assert np.array_equal(tab[td, ta], np.arange(len(ta)))
+        assert (tab >= 0).sum() == len(ta)
+        sm.destroy()
+
+
+def test_sampling_build_rejects_bad_arguments():
+    lib = pe.load_library()
+    import ctypes as C
+    out = C.c_void_p()
+    good = (C.c_int32 * 4)(1, 2, 3, 1)
+    assert lib.peagle_build_sampling(None, 4, 3, -1, C.byref(out)) == -2
+    assert lib.peagle_build_sampling(good, 4, 3, -1, None) == -2
+    assert lib.peagle_build_sampling(good, 0, 3, -1, C.byref(out)) == -1
+    assert lib.peagle_build_sampling(good, 4, 2, -1, C.byref(out)) == -1          # a count above K
+    assert lib.peagle_build_sampling((C.c_int32 * 4)(1, 0, 1, 1), 4, 3, -1, C.byref(out)) == -1   # depth 0 is always kept
+    assert lib.peagle_build_sampling(good, 4, 129, -1, C.byref(out)) == -5
+    assert out.value is None
+    assert lib.peagle_sampling_tokens(None) == 0
+
+
+def test_sampled_step_validates_before_launching():
+    """The sampled step entry point rejects mismatched shapes / missing pointers on the host (no GPU)."""
+    import ctypes as C
+    lib = pe.load_library()
+    tm = pe.peagle_build_tilemap(64, 4, None, device=-1)
+    sm = pe.peagle_build_sampling([1, 2, 3, 4] * 16, 4, device=-1)
+    one = C.c_void_p(16)   # never dereferenced: validation fails first
+
+    def call(shape, sm_h, ws=one, ws_bytes=1 << 40, q=one):
+        return lib.peagle_attn_step_sampled(tm.handle, shape.c(), sm_h, 0, 1, q, one, one, one, one, one, one, one, one,
+                                            None, None, ws, ws_bytes, None)
+    assert call(pe.Shape(64, 4, 2, 1, 64), None) == -2
+    assert call(pe.Shape(64, 4, 2, 1, 64), sm.handle, q=None) == -2
+    assert call(pe.Shape(32, 4, 2, 1, 64), sm.handle) == -3                         # sampling built for another length
+    assert call(pe.Shape(64, 4, 2, 1, 64), sm.handle, ws=None) == -6
+    assert call(pe.Shape(64, 4, 2, 1, 64), sm.handle) == -8                         # host-only handles cannot launch
