@@ -57,6 +57,18 @@ __device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r
 }
 
 __device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// Entry `e` of a tile list, made wave-uniform (the index is uniform; this lets branches on the
+// entry be scalar).  Lists are read two iterations ahead of their use so that the latency of
+// the load never sits on the loop's critical path.
+__device__ __forceinline__ TileEntry load_entry(const TileEntry* list, int e) {
+  const u32x2 w = *reinterpret_cast<const u32x2*>(list + e);
+  const uint32_t w0 = w[0], w1 = w[1];
+  TileEntry en;
+  en.tile = __builtin_amdgcn_readfirstlane((int)w0);
+  en.mask_id = __builtin_amdgcn_readfirstlane((int)w1);
+  return en;
+}
 __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 
 // Key tile straight into its swizzled LDS image (K and V): wave w of NW fills the 1 KiB blocks
@@ -287,6 +299,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
+  const int e_lead = e0 + tm.row_lead[rt];  // end of the leading run of full tiles
 
   // One pass over the row tile's key tiles.  The first pass keeps the softmax reference at 0
   // (no running max: fewer vector instructions per score); it is exact as long as every row
@@ -301,35 +314,40 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) o[hh][db] = zero16();
     }
-    dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
+    TileEntry cur = load_entry(tm.row_entries, e0);
+    TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
+    dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
     __syncthreads();
-    // The leading full tiles run in a loop of their own (no mask branch, accumulators stay in
-    // place); the partial tiles that end a row tile's list take the general loop.
+    // The leading full tiles run in a counted loop of their own (no mask branch, accumulators
+    // stay in place); the partial tiles that end a row tile's list take the general loop.
     int e = e0;
-    for (; e < e1 && tm.row_entries[e].mask_id < 0; ++e) {
+    for (; e < e_lead; ++e) {
       const int buf = (e - e0) & 1;
+      const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
-        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile,
-                           p.L, wave, lane);
+        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
       __syncthreads();
+      cur = nxt;
+      nxt = ahead;
     }
     for (; e < e1; ++e) {
       const int buf = (e - e0) & 1;
+      const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
-        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile,
-                           p.L, wave, lane);
-      const int mask_id = tm.row_entries[e].mask_id;
-      if (mask_id < 0) {
+        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
+      if (cur.mask_id < 0) {
         const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
         fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
       } else {
-        const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
+        const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)cur.mask_id * kRowsPerTile + r) * 2);
         const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
         fwd_tile<D, NH, true, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
       }
       __syncthreads();
+      cur = nxt;
+      nxt = ahead;
     }
     bool bad = false;
 #pragma unroll
@@ -468,34 +486,40 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
   const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
-  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e0].tile, p.L, wave, lane);
+  const int e_lead = e0 + tm.row_lead[rt];  // end of the leading run of full tiles
+  TileEntry cur = load_entry(tm.row_entries, e0);
+  TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
+  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
   __syncthreads();
 
   int e = e0;
-  for (; e < e1 && tm.row_entries[e].mask_id < 0; ++e) {  // leading full tiles: no mask branch
+  for (; e < e_lead; ++e) {  // leading full tiles: counted loop, no mask branch
     const int buf = (e - e0) & 1;
+    const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
-                         wave, lane);
+      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
     const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
     dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     __syncthreads();
+    cur = nxt;
+    nxt = ahead;
   }
   for (; e < e1; ++e) {
     const int buf = (e - e0) & 1;
+    const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, tm.row_entries[e + 1].tile, p.L,
-                         wave, lane);
-    const int mask_id = tm.row_entries[e].mask_id;
-    if (mask_id < 0) {
+      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
+    if (cur.mask_id < 0) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     } else {
-      const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)mask_id * kRowsPerTile + r) * 2);
+      const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)cur.mask_id * kRowsPerTile + r) * 2);
       const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
       dq_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     }
     __syncthreads();
+    cur = nxt;
+    nxt = ahead;
   }
 
   if (row_ok) {
@@ -680,9 +704,7 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   // Q / dO row tiles and their per-row terms (-lse/scale, -Delta, prepared by the dQ kernel) go
   // straight from global memory into the LDS buffer that the next iteration reads.
   const RowDmaLane<D, 4 * RH> rl = row_dma_lane<D, 4 * RH>(tm, p.L, wave, lane);
-  auto issue = [&](int it, int buf) {
-    const int hh = h_lo + it / n_row_tiles;
-    const int rt = tm.key_entries[e_lo + it % n_row_tiles].tile;
+  auto issue = [&](int hh, int rt, int buf) {
     char* base = lds + buf * kBufBytes;
     dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rl, rt, p.L, wave);
     dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rl, rt, p.L, wave);
@@ -690,31 +712,66 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     if (wave < 2) dma_row_stat<D, 4 * RH>(stat, p.nlse, p.T, hh, tm, rl, rt, p.L, wave & 1);
     else if (wave < 4) dma_row_stat<D, 4 * RH>(stat + kRowsPerTile, p.delta, p.T, hh, tm, rl, rt, p.L, wave & 1);
   };
+  // Iteration `it` handles row tile ei = it % n_row_tiles of head h_lo + it / n_row_tiles.  The
+  // list entries are read two iterations ahead (row tile for the copy issued one iteration
+  // ahead, mask for the compute), as wave-uniform values; entry -2 marks a row tile that does
+  // not see this wave's key tile.
+  auto row_tile_at = [&](int ei) { return load_entry(tm.key_entries, e_lo + ei).tile; };
+  auto mask_at = [&](int ei) {
+    return ei >= my_skip ? load_entry(tm.key_entries, my_lo + ei - my_skip).mask_id : -2;
+  };
+  auto step = [&](int& ei, int& hh) {  // advance (ei, hh) by one iteration
+    if (++ei == n_row_tiles) {
+      ei = 0;
+      ++hh;
+    }
+  };
 
-  if (n_iter > 0) issue(0, 0);
+  int ei_n = 0, hh_n = h_lo;        // next iteration (its copy is issued now)
+  int ei_a = 0, hh_a = h_lo;        // two ahead (its entries are loaded now)
+  int rt_n = 0, mask_c = -2, mask_n = -2;
+  if (n_iter > 0) {
+    issue(h_lo, row_tile_at(0), 0);
+    mask_c = mask_at(0);
+    step(ei_n, hh_n);
+    step(ei_a, hh_a);
+    if (n_iter > 1) {
+      rt_n = row_tile_at(ei_n);
+      mask_n = mask_at(ei_n);
+    }
+    step(ei_a, hh_a);
+  }
   __syncthreads();
 
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
-    if (it + 1 < n_iter) issue(it + 1, buf ^ 1);
-    const int ei = it % n_row_tiles;
-    if (ei >= my_skip) {
-      const int mask_id = tm.key_entries[my_lo + ei - my_skip].mask_id;
+    int rt_a = 0, mask_a = -2;
+    if (it + 2 < n_iter) {
+      rt_a = row_tile_at(ei_a);
+      mask_a = mask_at(ei_a);
+    }
+    if (it + 1 < n_iter) issue(hh_n, rt_n, buf ^ 1);
+    if (mask_c != -2) {
       const char* q_lds = lds + buf * kBufBytes;
       const char* do_lds = q_lds + kTileBytes;
       const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * kTileBytes);
       const float* delta_lds = lse_lds + kRowsPerTile;
       const int row_base = part * (kRowsPerTile / RH);
-      if (mask_id < 0) {
+      if (mask_c < 0) {
         dkdv_tile<D, RB, false>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
                                 p.c_log2);
       } else {
-        const uint32_t* mrow = tm.masks + (size_t)mask_id * kRowsPerTile * 2 + (kblk & 1);
+        const uint32_t* mrow = tm.masks + (size_t)mask_c * kRowsPerTile * 2 + (kblk & 1);
         dkdv_tile<D, RB, true>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, mrow,
                                p.c_log2);
       }
     }
     __syncthreads();
+    step(ei_n, hh_n);
+    step(ei_a, hh_a);
+    rt_n = rt_a;
+    mask_c = mask_n;
+    mask_n = mask_a;
   }
 
   // sum the row parts through LDS (part 0 owns the result), then store from registers:

@@ -139,6 +139,9 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
       ++key_count[kt];
     }
     tm->row_ptr[R + 1] = (int32_t)tm->row_entries.size();
+    int32_t lead = 0;
+    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1] && tm->row_entries[e].mask_id < 0; ++e) ++lead;
+    tm->row_lead.push_back(lead);
   }
   tm->n_masks = (int32_t)pool.index.size();
 
@@ -171,14 +174,15 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
       delete tm;
       return PEAGLE_EHIP;
     }
-    constexpr int kArrays = 7;
+    constexpr int kArrays = 8;
     static const char kZeros[256] = {0};
     const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
                                 tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
                                 tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
-                                sizeof(kZeros)};
+                                sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t)};
     const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
-                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros};
+                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
+                                tm->row_lead.data()};
     size_t off[kArrays], total = 0;
     for (int i = 0; i < kArrays; ++i) {
       off[i] = total;
@@ -203,6 +207,7 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
     tm->dview.masks = (const uint32_t*)(base + off[4]);
     tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
     tm->dview.zeros = base + off[6];
+    tm->dview.row_lead = (const int32_t*)(base + off[7]);
     tm->dview.A = A;
     tm->dview.K = K;
     tm->dview.S = S;

@@ -26,6 +26,7 @@ struct TileEntry {
 struct DeviceTileMap {
   const int32_t* row_ptr;     // [n_row_tiles + 1]  offsets into row_entries
   const TileEntry* row_entries;
+  const int32_t* row_lead;    // [n_row_tiles]  length of the leading run of full entries in each row tile's list
   const int32_t* key_ptr;     // [n_key_tiles + 1]  offsets into key_entries (row tiles ascending)
   const TileEntry* key_entries;
   const int32_t* key_seg_ptr; // [n_key_tiles][S + 1]  offsets into key_entries: where each segment's row tiles start
@@ -43,6 +44,7 @@ struct peagle_tilemap {
   int32_t n_row_tiles = 0, n_d0 = 0, n_csub = 0, n_key_tiles = 0;
   std::vector<int32_t> seg_bounds;               // [S+1] anchors
   std::vector<int32_t> row_ptr;
+  std::vector<int32_t> row_lead;                 // leading full entries per row tile
   std::vector<peagle::TileEntry> row_entries;
   std::vector<int32_t> key_ptr;
   std::vector<peagle::TileEntry> key_entries;
