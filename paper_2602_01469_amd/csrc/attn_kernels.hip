@@ -57,19 +57,25 @@ __device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r
 }
 
 __device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 
 // Entry `e` of a tile list, made wave-uniform (the index is uniform; this lets branches on the
-// entry be scalar).  Lists are read two iterations ahead of their use so that the latency of
-// the load never sits on the loop's critical path.
-__device__ __forceinline__ TileEntry load_entry(const TileEntry* list, int e) {
-  const u32x2 w = *reinterpret_cast<const u32x2*>(list + e);
-  const uint32_t w0 = w[0], w1 = w[1];
+// entry be scalar).  Lists are read two iterations ahead of their use: fetch_entry() starts the
+// load early in an iteration, take_entry() - called after the iteration's barrier - moves the
+// value to scalar registers.  The empty assembly statement pins that move below the barrier;
+// without it the compiler places it, and the wait for the load, right behind the load.
+__device__ __forceinline__ u32x2 fetch_entry(const TileEntry* list, int e) {
+  return *reinterpret_cast<const u32x2*>(list + e);
+}
+__device__ __forceinline__ TileEntry take_entry(u32x2 w) {
+  uint32_t w0 = w[0], w1 = w[1];
+  asm volatile("" : "+v"(w0), "+v"(w1) : : "memory");
   TileEntry en;
   en.tile = __builtin_amdgcn_readfirstlane((int)w0);
   en.mask_id = __builtin_amdgcn_readfirstlane((int)w1);
   return en;
 }
-__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ TileEntry load_entry(const TileEntry* list, int e) { return take_entry(fetch_entry(list, e)); }
 
 // Key tile straight into its swizzled LDS image (K and V): wave w of NW fills the 1 KiB blocks
 // w, w + NW, ...; lane l of block b owns LDS bytes [1024 b + 16 l, +16), i.e. tile row
@@ -317,24 +323,24 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
     TileEntry cur = load_entry(tm.row_entries, e0);
     TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
     dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
-    __syncthreads();
+    dma_publish();
     // The leading full tiles run in a counted loop of their own (no mask branch, accumulators
     // stay in place); the partial tiles that end a row tile's list take the general loop.
     int e = e0;
     for (; e < e_lead; ++e) {
       const int buf = (e - e0) & 1;
-      const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
+      const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
         dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
-      __syncthreads();
+      dma_publish();
       cur = nxt;
-      nxt = ahead;
+      nxt = take_entry(ahead);
     }
     for (; e < e1; ++e) {
       const int buf = (e - e0) & 1;
-      const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
+      const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
         dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
       if (cur.mask_id < 0) {
@@ -345,9 +351,9 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
         const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
         fwd_tile<D, NH, true, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
       }
-      __syncthreads();
+      dma_publish();
       cur = nxt;
-      nxt = ahead;
+      nxt = take_entry(ahead);
     }
     bool bad = false;
 #pragma unroll
@@ -490,23 +496,23 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   TileEntry cur = load_entry(tm.row_entries, e0);
   TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
   dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
-  __syncthreads();
+  dma_publish();
 
   int e = e0;
   for (; e < e_lead; ++e) {  // leading full tiles: counted loop, no mask branch
     const int buf = (e - e0) & 1;
-    const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
+    const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
       dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
     const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
     dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
-    __syncthreads();
+    dma_publish();
     cur = nxt;
-    nxt = ahead;
+    nxt = take_entry(ahead);
   }
   for (; e < e1; ++e) {
     const int buf = (e - e0) & 1;
-    const TileEntry ahead = load_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
+    const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
       dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
     if (cur.mask_id < 0) {
@@ -517,9 +523,9 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
       const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
       dq_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     }
-    __syncthreads();
+    dma_publish();
     cur = nxt;
-    nxt = ahead;
+    nxt = take_entry(ahead);
   }
 
   if (row_ok) {
@@ -716,10 +722,9 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   // list entries are read two iterations ahead (row tile for the copy issued one iteration
   // ahead, mask for the compute), as wave-uniform values; entry -2 marks a row tile that does
   // not see this wave's key tile.
-  auto row_tile_at = [&](int ei) { return load_entry(tm.key_entries, e_lo + ei).tile; };
-  auto mask_at = [&](int ei) {
-    return ei >= my_skip ? load_entry(tm.key_entries, my_lo + ei - my_skip).mask_id : -2;
-  };
+  auto fetch_row_tile = [&](int ei) { return fetch_entry(tm.key_entries, e_lo + ei); };
+  auto fetch_mask = [&](int ei) { return fetch_entry(tm.key_entries, ei >= my_skip ? my_lo + ei - my_skip : e_lo + ei); };
+  auto mask_of = [&](int ei, const TileEntry& en) { return ei >= my_skip ? en.mask_id : -2; };
   auto step = [&](int& ei, int& hh) {  // advance (ei, hh) by one iteration
     if (++ei == n_row_tiles) {
       ei = 0;
@@ -731,25 +736,23 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   int ei_a = 0, hh_a = h_lo;        // two ahead (its entries are loaded now)
   int rt_n = 0, mask_c = -2, mask_n = -2;
   if (n_iter > 0) {
-    issue(h_lo, row_tile_at(0), 0);
-    mask_c = mask_at(0);
+    issue(h_lo, take_entry(fetch_row_tile(0)).tile, 0);
+    mask_c = mask_of(0, take_entry(fetch_mask(0)));
     step(ei_n, hh_n);
     step(ei_a, hh_a);
     if (n_iter > 1) {
-      rt_n = row_tile_at(ei_n);
-      mask_n = mask_at(ei_n);
+      rt_n = take_entry(fetch_row_tile(ei_n)).tile;
+      mask_n = mask_of(ei_n, take_entry(fetch_mask(ei_n)));
     }
     step(ei_a, hh_a);
   }
-  __syncthreads();
+  dma_publish();
 
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
-    int rt_a = 0, mask_a = -2;
-    if (it + 2 < n_iter) {
-      rt_a = row_tile_at(ei_a);
-      mask_a = mask_at(ei_a);
-    }
+    const bool have_ahead = it + 2 < n_iter;
+    const u32x2 rt_raw = fetch_row_tile(have_ahead ? ei_a : 0);
+    const u32x2 mask_raw = fetch_mask(have_ahead ? ei_a : 0);
     if (it + 1 < n_iter) issue(hh_n, rt_n, buf ^ 1);
     if (mask_c != -2) {
       const char* q_lds = lds + buf * kBufBytes;
@@ -766,12 +769,12 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
                                p.c_log2);
       }
     }
-    __syncthreads();
+    dma_publish();
+    rt_n = take_entry(rt_raw).tile;
+    mask_c = mask_n;
+    mask_n = have_ahead ? mask_of(ei_a, take_entry(mask_raw)) : -2;
     step(ei_n, hh_n);
     step(ei_a, hh_a);
-    rt_n = rt_a;
-    mask_c = mask_n;
-    mask_n = mask_a;
   }
 
   // sum the row parts through LDS (part 0 owns the result), then store from registers:

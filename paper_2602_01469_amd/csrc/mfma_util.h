@@ -113,7 +113,8 @@ __device__ __forceinline__ bf16x8 frag_tr(const char* tile, const TrOff<D>& t, i
 
 // Asynchronous global -> LDS copy, 16 bytes per lane (global_load_lds_dwordx4): lane l's bytes
 // land at lds_wave_base + 16*l, so one call fills 1 KiB of LDS per wave; lds_wave_base must be
-// wave-uniform.  Completion is tracked by vmcnt (a __syncthreads() waits for it).
+// wave-uniform.  Completion is tracked by vmcnt of the issuing wave only: use dma_publish() to
+// make the data visible to the other waves.
 __device__ __forceinline__ void dma16(const void* gsrc, char* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
                                    PEAGLE_LDS_PTR(void, lds_wave_base), 16, 0, 0);
@@ -123,6 +124,16 @@ __device__ __forceinline__ void dma16(const void* gsrc, char* lds_wave_base) {
 __device__ __forceinline__ void dma4(const void* gsrc, char* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
                                    PEAGLE_LDS_PTR(void, lds_wave_base), 4, 0, 0);
+}
+
+// Wait until every global -> LDS copy this wave has issued has landed (vmcnt(0)), then
+// synchronise the workgroup: after it, all waves may read what any wave copied, and the buffers
+// read before it may be overwritten.  The wait is explicit because a workgroup barrier by itself
+// only orders ordinary LDS traffic; it is an assembly statement with a memory clobber so that it
+// stays behind every earlier LDS read.
+__device__ __forceinline__ void dma_publish() {
+  asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+  __syncthreads();
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
