@@ -133,6 +133,56 @@ def sweep(args) -> int:
     return 0
 
 
+def sampled(args) -> int:
+    """The named workload under Conditional Drop-token sampling with the given retention rate
+    (peagle_attn_step_sampled): same tile map and segments, T = kept positions only.  Useful FLOPs count
+    the pairs of kept positions."""
+    import numpy as np
+    import torch
+
+    import paper_2602_01469_amd as pe
+    from peagle_inputs import CONFIGS, cod_depth_counts, make_inputs_tokens, useful_pairs, useful_pairs_sampled
+    pe.load_library()
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.workload]
+    bounds = cfg.seg_bounds()
+    S = len(bounds) - 1
+    tm = pe.peagle_build_tilemap(cfg.L, cfg.K, bounds, device=0)
+    count = cod_depth_counts(cfg.L, cfg.K, args.cod_retention, cfg.seed)
+    sm = pe.peagle_build_sampling(count, cfg.K, device=0)
+    T = sm.T
+    dev = lambda x: torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v, do = (dev(x) for x in make_inputs_tokens(cfg, T))
+    shape = pe.Shape(cfg.L, cfg.K, cfg.Hq, cfg.Hkv, cfg.D, cfg.scale)
+    o, dq = torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty((cfg.Hq, T), dtype=torch.float32, device="cuda")
+    dk = torch.empty((T, cfg.Hkv, cfg.D), dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    ws = torch.empty(pe.peagle_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    step = lambda: pe.peagle_attn_step_sampled(tm, shape, sm, 0, S, q, k, v, do, o, lse, dq, dk, dv, None, None, ws,
+                                               stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+    pairs = useful_pairs_sampled(count)
+    flops = 14 * cfg.D * cfg.Hq * pairs
+    print(json.dumps({
+        "metric": "effective masked-attn TFLOP/s fwd+bwd (useful FLOPs of kept positions), drop-token sampled sequence",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} with retention {args.cod_retention}: L={cfg.L} K={cfg.K} kept positions "
+                               f"T={T} of {cfg.T}, Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D}, {S} segments, seed {cfg.seed}"},
+        "kept_positions": T, "useful_pairs": pairs, "useful_pairs_dense": useful_pairs(cfg.L, cfg.K),
+        "finite": bool(torch.isfinite(dk).all().item() and torch.isfinite(dv).all().item())}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +195,9 @@ def main() -> int:
                     help="instead of the headline workload, time a sweep of sequence lengths on one tile map")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one 256 MiB device-to-device copy (reference dispatch for HBM byte counters)")
+    ap.add_argument("--cod-retention", type=float, default=None,
+                    help="instead of the headline (dense) workload, time the same shape under drop-token sampling "
+                         "with this retention rate")
     ap.add_argument("--seg-anchors", type=int, default=None,
                     help="override the anchors per query-row segment (diagnostic; the default is the workload's)")
     args = ap.parse_args()
@@ -154,6 +207,8 @@ def main() -> int:
 
     if args.sweep:
         return sweep(args)
+    if args.cod_retention is not None:
+        return sampled(args)
 
     import torch
 

@@ -5,7 +5,7 @@ random tensors and rounds them to bf16 bit patterns.  Both sides consume exactly
 these bytes.
 """
 from .gen import (CONFIGS, WorkloadConfig, bf16_bits_to_f64, cod_depth_counts, f32_to_bf16_bits, make_inputs,
-                  make_inputs_tokens, useful_flops, useful_pairs)
+                  make_inputs_tokens, useful_flops, useful_pairs, useful_pairs_sampled)
 
 __all__ = [
     "CONFIGS",
@@ -15,6 +15,7 @@ __all__ = [
     "make_inputs",
     "make_inputs_tokens",
     "cod_depth_counts",
+    "useful_pairs_sampled",
     "useful_pairs",
     "useful_flops",
 ]

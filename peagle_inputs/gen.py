@@ -125,3 +125,11 @@ def make_inputs_tokens(cfg: WorkloadConfig, T: int, seed_offset: int = 1000):
             x *= np.float32(cfg.value_scale)
         out.append(f32_to_bf16_bits(x))
     return tuple(out)
+
+
+def useful_pairs_sampled(depth_count) -> int:
+    """Unmasked (query, key) pairs of a sampled sequence: the row of anchor i at depth d sees i+1 depth-0
+    keys and d chain keys, and anchor i keeps depths 0..depth_count[i]-1."""
+    n = np.asarray(depth_count, dtype=np.int64)
+    i = np.arange(len(n), dtype=np.int64)
+    return int((n * (i + 1) + n * (n - 1) // 2).sum())

@@ -386,6 +386,9 @@ def test_sampled_mask_matches_dependency_rules_and_is_a_submask_of_the_dense_one
     idx = td * L + ta                                                   # same (anchor, depth) in the dense layout
     assert np.array_equal(M, dense[np.ix_(idx, idx)])
     assert np.array_equal(M.sum(axis=1), ta + 1 + td)                   # visible count is unchanged by sampling
+    from peagle_inputs import useful_pairs_sampled
+    assert M.sum() == useful_pairs_sampled(count)
+    assert useful_pairs_sampled(np.full(L, K)) == useful_pairs(L, K)
 
 
 def test_sampled_attention_equals_dense_attention_on_kept_rows():
