@@ -135,8 +135,8 @@ def sweep(args) -> int:
 
 def sampled(args) -> int:
     """The named workload under Conditional Drop-token sampling with the given retention rate
-    (peagle_attn_step_sampled): same tile map and segments, T = kept positions only.  Useful FLOPs count
-    the pairs of kept positions."""
+    (a sampled tile map, built per sequence and timed separately): same segments, T = kept positions
+    only.  Useful FLOPs count the pairs of kept positions."""
     import numpy as np
     import torch
 
@@ -147,10 +147,12 @@ def sampled(args) -> int:
     cfg = CONFIGS[args.workload]
     bounds = cfg.seg_bounds()
     S = len(bounds) - 1
-    tm = pe.peagle_build_tilemap(cfg.L, cfg.K, bounds, device=0)
     count = cod_depth_counts(cfg.L, cfg.K, args.cod_retention, cfg.seed)
-    sm = pe.peagle_build_sampling(count, cfg.K, device=0)
-    T = sm.T
+    t0 = time.perf_counter()
+    tm = pe.peagle_build_tilemap_sampled(count, cfg.K, bounds, device=0)
+    build_ms = (time.perf_counter() - t0) * 1e3
+    info = tm.info()
+    T = tm.tokens(cfg.L)
     dev = lambda x: torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
     q, k, v, do = (dev(x) for x in make_inputs_tokens(cfg, T))
     shape = pe.Shape(cfg.L, cfg.K, cfg.Hq, cfg.Hkv, cfg.D, cfg.scale)
@@ -160,8 +162,8 @@ def sampled(args) -> int:
     dv = torch.empty_like(dk)
     ws = torch.empty(pe.peagle_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
-    step = lambda: pe.peagle_attn_step_sampled(tm, shape, sm, 0, S, q, k, v, do, o, lse, dq, dk, dv, None, None, ws,
-                                               stream)
+    step = lambda: pe.peagle_attn_step_partitioned(tm, shape, 0, S, q, k, v, do, o, lse, dq, dk, dv, None, None, ws,
+                                                   stream)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -179,6 +181,10 @@ def sampled(args) -> int:
         "config": {"workload": f"{cfg.name} with retention {args.cod_retention}: L={cfg.L} K={cfg.K} kept positions "
                                f"T={T} of {cfg.T}, Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D}, {S} segments, seed {cfg.seed}"},
         "kept_positions": T, "useful_pairs": pairs, "useful_pairs_dense": useful_pairs(cfg.L, cfg.K),
+        "useful_over_computed_pairs": pairs / ((info["n_full"] + info["n_partial"]) * 128 * 64),
+        "tilemap_build_ms": build_ms,
+        "tilemap": {"device_bytes": info["device_bytes"], "n_masks": info["n_masks"], "n_row_tiles": info["n_row_tiles"],
+                    "n_full": info["n_full"], "n_partial": info["n_partial"]},
         "finite": bool(torch.isfinite(dk).all().item() and torch.isfinite(dv).all().item())}))
     return 0
 

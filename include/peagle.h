@@ -81,6 +81,8 @@ typedef struct peagle_tilemap_info {
   int64_t n_partial;             /* tile pairs that need a bitmask */
   int32_t n_masks;               /* distinct bitmasks in the pool (128 rows x 64 bits each) */
   int64_t device_bytes;          /* bytes of the device copy (0 if host-only) */
+  int64_t tokens;                /* stored tokens of a length-L_max sequence */
+  int32_t sampled;               /* 1 if built by peagle_build_tilemap_sampled */
 } peagle_tilemap_info_t;
 
 /*
@@ -112,8 +114,9 @@ int peagle_tilemap_info(const peagle_tilemap_t* tm, peagle_tilemap_info_t* info 
 /*
  * Host-side expansion of the tile map back to the element mask, for bit-exact checks.
  * For the query rows t in [row_begin, row_end) (token indices of a length-L problem, L <= L_max)
- * writes (row_end-row_begin) * ceil(L*K/8) bytes to bits_out (host): bit (c % 8) of byte c/8 of a
- * row is 1 iff key token c is visible.  With seg >= 0, rows outside segment `seg` come out all zero.
+ * writes (row_end-row_begin) * ceil(T/8) bytes to bits_out (host), T = peagle_tilemap_tokens(tm, L):
+ * bit (c % 8) of byte c/8 of a row is 1 iff key token c is visible.  With seg >= 0, rows outside
+ * segment `seg` come out all zero.
  */
 int peagle_tilemap_expand_rows(const peagle_tilemap_t* tm, int32_t L, int32_t seg, int64_t row_begin,
                                int64_t row_end, uint8_t* bits_out);
@@ -176,43 +179,30 @@ int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_
                                  void* dv_bf16, void* workspace, size_t ws_bytes, void* stream);
 
 /*
- * Drop-token sampled sequences (Conditional Drop-token sampling, PARD paragraph of Sec. 3: depth g
- * keeps a geometrically shrinking subset of positions, n(1-r^K)/(1-r) in total, Sec. 3.2).  A kept
- * position p at depth g needs position p-1 at depth g-1 (Sec. 3.2, Challenge 2), so per anchor the
- * kept depths are a prefix: anchor i keeps depths 0 .. depth_count[i]-1.
+ * Tile map of a drop-token sampled sequence (Conditional Drop-token sampling, PARD paragraph of
+ * Sec. 3: depth g keeps a geometrically shrinking subset of positions, n(1-r^K)/(1-r) in total,
+ * Sec. 3.2).  A kept position p at depth g needs position p-1 at depth g-1 (Sec. 3.2,
+ * Challenge 2), so per anchor the kept depths are a prefix: anchor i keeps depths
+ * 0 .. depth_count[i]-1.
  *
  *   depth_count  host, int32[L], each in [1, K]
- *   device       HIP device ordinal for the device copy of the token table, or -1 (host-only)
+ *   seg_bounds   host, int32[S+1], 0 = b_0 < ... < b_S = L, any anchor indices (NULL with S = 1)
  *
  * Storage order of every [T, ...] tensor of such a sequence: depth-major, and within a depth the
- * anchors that keep it in ascending order; T = sum(depth_count) (peagle_sampling_tokens).
+ * anchors that keep it in ascending order; T = sum(depth_count) = peagle_tilemap_tokens(tm, L).
+ * The map is built for this one sequence (the sample differs per example) and is used with
+ * shape->L == L in every entry point that takes a tile map; all of them then index tensors of T
+ * rows (lse is [Hq, T]).  Its row tiles are runs of consecutive anchors packed until their kept
+ * positions fill 128 rows, so no matrix-core work is spent on dropped positions; the mask is the
+ * dense parallel-prediction mask restricted to kept positions.  Segment s computes the kept
+ * positions of anchors [b_s, b_{s+1}) against the cumulative depth-0 context (Sec. 3.2).
  */
-typedef struct peagle_sampling peagle_sampling_t;
+int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t L, int32_t K, const int32_t* seg_bounds,
+                                 int32_t S, int32_t device, peagle_tilemap_t** out);
 
-int peagle_build_sampling(const int32_t* depth_count, int32_t L, int32_t K, int32_t device,
-                          peagle_sampling_t** out);
-
-void peagle_sampling_destroy(peagle_sampling_t* sm);
-
-/* Stored tokens T of the sampled sequence (0 if sm is NULL). */
-int64_t peagle_sampling_tokens(const peagle_sampling_t* sm);
-
-/* Host copy of the token table: table_out (host) receives int32[K][L], the token of (depth, anchor)
- * or -1 where the position was dropped. */
-int peagle_sampling_table(const peagle_sampling_t* sm, int32_t* table_out);
-
-/*
- * peagle_attn_step_partitioned for a drop-token sampled sequence: same tile map (the mask of the
- * sampled sequence is the dense mask restricted to kept positions), same segment passes and
- * dK/dV accumulation (Sec. 3.2; a position is computed in the segment of its anchor, the depth-0
- * context N_s is cumulative).  shape->L and shape->K must equal the sampling's; every [T, ...]
- * tensor has T = peagle_sampling_tokens(sm) rows, lse is fp32 [Hq, T].  The workspace size is
- * that of the dense shape, peagle_workspace_bytes().
- */
-int peagle_attn_step_sampled(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const peagle_sampling_t* sm,
-                             int32_t seg_begin, int32_t seg_end, const void* q, const void* k, const void* v,
-                             const void* d_o, void* o, float* lse, void* dq, float* dk_acc, float* dv_acc,
-                             void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes, void* stream);
+/* Stored tokens T of a length-L sequence under this map: L*K for a dense map, the kept positions
+ * for a sampled one (which accepts only its own L).  -1 on a bad argument. */
+int64_t peagle_tilemap_tokens(const peagle_tilemap_t* tm, int32_t L);
 
 /* Kernel kinds reported by peagle_attn_step_profiled. */
 #define PEAGLE_KERNEL_FWD 0      /* forward (O, LSE) */

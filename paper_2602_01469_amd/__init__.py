@@ -5,7 +5,6 @@ used only for device buffers and streams; every step of the path runs in the HIP
 """
 from .binding import (  # noqa: F401
     PeagleError,
-    Sampling,
     Shape,
     TileMap,
     lib_path,
@@ -14,8 +13,7 @@ from .binding import (  # noqa: F401
     peagle_attn_fwd,
     peagle_attn_step_partitioned,
     peagle_attn_step_profiled,
-    peagle_attn_step_sampled,
-    peagle_build_sampling,
+    peagle_build_tilemap_sampled,
     peagle_measure_mfma_ceiling,
     peagle_build_tilemap,
     peagle_device_info,

@@ -27,15 +27,15 @@ class _InfoC(C.Structure):
     _fields_ = [("L_max", C.c_int32), ("K", C.c_int32), ("S", C.c_int32), ("anchors_per_row_tile", C.c_int32),
                 ("rows_per_tile", C.c_int32), ("keys_per_tile", C.c_int32), ("n_row_tiles", C.c_int32),
                 ("n_depth0_key_tiles", C.c_int32), ("n_chain_sub_tiles", C.c_int32), ("n_key_tiles", C.c_int32),
-                ("n_full", C.c_int64), ("n_partial", C.c_int64), ("n_masks", C.c_int32), ("device_bytes", C.c_int64)]
+                ("n_full", C.c_int64), ("n_partial", C.c_int64), ("n_masks", C.c_int32), ("device_bytes", C.c_int64),
+                ("tokens", C.c_int64), ("sampled", C.c_int32)]
 
 
 EXPORTS = [
     "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
-    "peagle_attn_step_partitioned", "peagle_build_sampling", "peagle_sampling_destroy", "peagle_sampling_tokens",
-    "peagle_sampling_table", "peagle_attn_step_sampled", "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling",
-    "peagle_device_info", "peagle_strerror",
+    "peagle_attn_step_partitioned", "peagle_build_tilemap_sampled", "peagle_tilemap_tokens",
+    "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
 KERNEL_KINDS = ("fwd", "dq", "dkdv", "reduce")
@@ -79,17 +79,10 @@ def load_library():
     lib.peagle_attn_step_partitioned.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                  vp, vp, vp, sz, vp]
     lib.peagle_attn_step_partitioned.restype = C.c_int
-    lib.peagle_build_sampling.argtypes = [C.POINTER(i32), i32, i32, i32, C.POINTER(vp)]
-    lib.peagle_build_sampling.restype = C.c_int
-    lib.peagle_sampling_destroy.argtypes = [vp]
-    lib.peagle_sampling_destroy.restype = None
-    lib.peagle_sampling_tokens.argtypes = [vp]
-    lib.peagle_sampling_tokens.restype = i64
-    lib.peagle_sampling_table.argtypes = [vp, vp]
-    lib.peagle_sampling_table.restype = C.c_int
-    lib.peagle_attn_step_sampled.argtypes = [vp, C.POINTER(_ShapeC), vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
-                                             vp, vp, vp, sz, vp]
-    lib.peagle_attn_step_sampled.restype = C.c_int
+    lib.peagle_build_tilemap_sampled.argtypes = [C.POINTER(i32), i32, i32, C.POINTER(i32), i32, i32, C.POINTER(vp)]
+    lib.peagle_build_tilemap_sampled.restype = C.c_int
+    lib.peagle_tilemap_tokens.argtypes = [vp, i32]
+    lib.peagle_tilemap_tokens.restype = i64
     lib.peagle_attn_step_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                               sz, vp, C.POINTER(_ProfileC)]
     lib.peagle_attn_step_profiled.restype = C.c_int
@@ -153,10 +146,16 @@ class TileMap:
             raise PeagleError(rc, "peagle_tilemap_info")
         return {name: getattr(inf, name) for name, _ in _InfoC._fields_}
 
+    def tokens(self, L: int) -> int:
+        """Stored tokens T of a length-L sequence under this map (L*K, or the kept positions of a sampled map)."""
+        T = int(load_library().peagle_tilemap_tokens(self.handle, int(L)))
+        if T < 0:
+            raise PeagleError(-3, "peagle_tilemap_tokens")
+        return T
+
     def expand_rows(self, L: int, seg: int, row_begin: int, row_end: int) -> np.ndarray:
-        """Packed element-mask bits [row_end-row_begin, ceil(L*K/8)] (uint8, little bit order)."""
-        K = self.info()["K"]
-        row_bytes = (L * K + 7) // 8
+        """Packed element-mask bits [row_end-row_begin, ceil(T/8)] (uint8, little bit order)."""
+        row_bytes = (self.tokens(L) + 7) // 8
         out = np.zeros((max(row_end - row_begin, 0), row_bytes), dtype=np.uint8)
         rc = load_library().peagle_tilemap_expand_rows(self.handle, L, seg, row_begin, row_end,
                                                        out.ctypes.data_as(C.c_void_p))
@@ -184,6 +183,23 @@ def peagle_build_tilemap(L_max: int, K: int, seg_bounds: Optional[Sequence[int]]
                                       C.byref(out))
     if rc != 0:
         raise PeagleError(rc, "peagle_build_tilemap")
+    return TileMap(out.value)
+
+
+def peagle_build_tilemap_sampled(depth_count: Sequence[int], K: int, seg_bounds: Optional[Sequence[int]] = None,
+                                 device: int = 0) -> TileMap:
+    lib = load_library()
+    n = np.ascontiguousarray(depth_count, dtype=np.int32)
+    out = C.c_void_p()
+    if seg_bounds is None:
+        rc = lib.peagle_build_tilemap_sampled(n.ctypes.data_as(C.POINTER(C.c_int32)), len(n), K, None, 1, device,
+                                              C.byref(out))
+    else:
+        b = np.ascontiguousarray(seg_bounds, dtype=np.int32)
+        rc = lib.peagle_build_tilemap_sampled(n.ctypes.data_as(C.POINTER(C.c_int32)), len(n), K,
+                                              b.ctypes.data_as(C.POINTER(C.c_int32)), len(b) - 1, device, C.byref(out))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_build_tilemap_sampled")
     return TileMap(out.value)
 
 
@@ -217,7 +233,7 @@ def _stream_ptr(stream):
 def peagle_attn_fwd(tm: TileMap, shape: Shape, seg: int, q, k, v, o, lse, stream=None) -> None:
     import torch
     bf, f32 = torch.bfloat16, torch.float32
-    T = shape.T
+    T = tm.tokens(shape.L)
     rc = load_library().peagle_attn_fwd(
         tm.handle, shape.c(), seg,
         _ptr(q, "q", bf, (T, shape.Hq, shape.D)), _ptr(k, "k", bf, (T, shape.Hkv, shape.D)),
@@ -231,7 +247,7 @@ def peagle_attn_bwd(tm: TileMap, shape: Shape, seg: int, q, k, v, o, d_o, lse, d
                     workspace, stream=None) -> None:
     import torch
     bf, f32 = torch.bfloat16, torch.float32
-    T = shape.T
+    T = tm.tokens(shape.L)
     qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
     if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
         raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
@@ -248,7 +264,7 @@ def peagle_attn_step_partitioned(tm: TileMap, shape: Shape, seg_begin: int, seg_
                                  dk_acc, dv_acc, dk_bf16, dv_bf16, workspace, stream=None) -> None:
     import torch
     bf, f32 = torch.bfloat16, torch.float32
-    T = shape.T
+    T = tm.tokens(shape.L)
     qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
     if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
         raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
@@ -262,75 +278,12 @@ def peagle_attn_step_partitioned(tm: TileMap, shape: Shape, seg_begin: int, seg_
         raise PeagleError(rc, "peagle_attn_step_partitioned")
 
 
-class Sampling:
-    """Owner of a peagle_sampling_t handle (drop-token sampled sequence)."""
-
-    def __init__(self, handle: int, L: int, K: int):
-        self._h = C.c_void_p(handle)
-        self.L, self.K = int(L), int(K)
-
-    @property
-    def handle(self):
-        if not self._h:
-            raise ValueError("sampling already destroyed")
-        return self._h
-
-    @property
-    def T(self) -> int:
-        return int(load_library().peagle_sampling_tokens(self.handle))
-
-    def table(self) -> np.ndarray:
-        out = np.empty((self.K, self.L), dtype=np.int32)
-        rc = load_library().peagle_sampling_table(self.handle, out.ctypes.data_as(C.c_void_p))
-        if rc != 0:
-            raise PeagleError(rc, "peagle_sampling_table")
-        return out
-
-    def destroy(self):
-        if self._h:
-            load_library().peagle_sampling_destroy(self._h)
-            self._h = C.c_void_p(None)
-
-    def __del__(self):
-        try:
-            self.destroy()
-        except Exception:
-            pass
-
-
-def peagle_build_sampling(depth_count: Sequence[int], K: int, device: int = 0) -> Sampling:
-    n = np.ascontiguousarray(depth_count, dtype=np.int32)
-    out = C.c_void_p()
-    rc = load_library().peagle_build_sampling(n.ctypes.data_as(C.POINTER(C.c_int32)), len(n), K, device, C.byref(out))
-    if rc != 0:
-        raise PeagleError(rc, "peagle_build_sampling")
-    return Sampling(out.value, len(n), K)
-
-
-def peagle_attn_step_sampled(tm: TileMap, shape: Shape, sm: Sampling, seg_begin: int, seg_end: int, q, k, v, d_o, o,
-                             lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16, workspace, stream=None) -> None:
-    import torch
-    bf, f32 = torch.bfloat16, torch.float32
-    T = sm.T
-    qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
-    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
-        raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
-    rc = load_library().peagle_attn_step_sampled(
-        tm.handle, shape.c(), sm.handle, seg_begin, seg_end, _ptr(q, "q", bf, qs), _ptr(k, "k", bf, ks),
-        _ptr(v, "v", bf, ks), _ptr(d_o, "d_o", bf, qs), _ptr(o, "o", bf, qs), _ptr(lse, "lse", f32, (shape.Hq, T)),
-        _ptr(dq, "dq", bf, qs), _ptr(dk_acc, "dk_acc", f32, ks), _ptr(dv_acc, "dv_acc", f32, ks),
-        _ptr(dk_bf16, "dk_bf16", bf, ks), _ptr(dv_bf16, "dv_bf16", bf, ks),
-        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
-    if rc != 0:
-        raise PeagleError(rc, "peagle_attn_step_sampled")
-
-
 def peagle_attn_step_profiled(tm: TileMap, shape: Shape, seg_begin: int, seg_end: int, q, k, v, d_o, o, lse, dq,
                               dk_acc, dv_acc, workspace, stream=None) -> dict:
     """Same work as peagle_attn_step_partitioned; returns {kind: (ms, launches)} from HIP events."""
     import torch
     bf, f32 = torch.bfloat16, torch.float32
-    T = shape.T
+    T = tm.tokens(shape.L)
     qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
     prof = _ProfileC()
     rc = load_library().peagle_attn_step_profiled(

@@ -2,7 +2,6 @@
 // paper: one forward+backward pass per segment, dK/dV accumulated across segments in fp32).
 #include <climits>
 #include <cmath>
-#include <cstdint>
 
 #include "attn_kernels.h"
 #include "peagle.h"
@@ -21,10 +20,15 @@ struct WsLayout {
   int L64;
 };
 
-WsLayout ws_layout(const peagle_shape_t* s) {
+// Stored tokens of the call: L*K for a dense map, the kept positions for a sampled one.
+size_t tokens_of(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
+  return tm->sampled ? (size_t)tm->T_tokens : (size_t)s->L * s->K;
+}
+
+WsLayout ws_layout(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
   WsLayout w;
   w.L64 = (s->L + 63) / 64 * 64;
-  const size_t T = (size_t)s->L * s->K;
+  const size_t T = tokens_of(tm, s);
   const size_t part = (size_t)s->Hq * w.L64 * s->D * sizeof(float);
   w.delta_off = 0;
   w.nlse_off = align256(T * s->Hq * sizeof(float));
@@ -42,14 +46,12 @@ int check_shape(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
   if (s->layout != PEAGLE_LAYOUT_DEPTH_MAJOR) return PEAGLE_EUNSUPPORTED;
   if (s->D != 64 && s->D != 128) return PEAGLE_EUNSUPPORTED;
   if (s->K != tm->K || s->L > tm->L_max) return PEAGLE_ESHAPE;
+  if (tm->sampled && s->L != tm->L_max) return PEAGLE_ESHAPE;  // a sampled map serves its own sequence only
   return PEAGLE_OK;
 }
 
-// Token count and token table of the call: a dense sequence stores all L*K positions in order.
-int tokens_of(const peagle_shape_t* s, const peagle_sampling_t* sm) { return sm ? (int)sm->T : s->L * s->K; }
-
-FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const peagle_sampling_t* sm,
-                   const SegRange& sr, const void* q, const void* k, const void* v, void* o, float* lse) {
+FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
+                   const void* k, const void* v, void* o, float* lse) {
   FwdParams p{};
   p.q = (const __bf16*)q;
   p.k = (const __bf16*)k;
@@ -57,9 +59,8 @@ FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const pe
   p.o = (__bf16*)o;
   p.lse = lse;
   p.tm = tm->dview;
-  p.tm.tok_table = sm ? sm->dev_table : nullptr;
   p.L = s->L;
-  p.T = tokens_of(s, sm);
+  p.T = (int)tokens_of(tm, s);
   p.Hq = s->Hq;
   p.Hkv = s->Hkv;
   p.rt_lo = sr.rt_lo;
@@ -68,11 +69,10 @@ FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const pe
   return p;
 }
 
-BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const peagle_sampling_t* sm,
-                   const SegRange& sr, const void* q, const void* k, const void* v, const void* o,
-                   const void* d_o, const float* lse, void* dq, float* dk_acc, float* dv_acc, void* workspace,
-                   int chain_accumulate) {
-  const WsLayout w = ws_layout(s);
+BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
+                   const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
+                   float* dk_acc, float* dv_acc, void* workspace, int chain_accumulate) {
+  const WsLayout w = ws_layout(tm, s);
   BwdParams p{};
   p.q = (const __bf16*)q;
   p.k = (const __bf16*)k;
@@ -88,9 +88,8 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const pe
   p.dk_part = (float*)((char*)workspace + w.dk_off);
   p.dv_part = (float*)((char*)workspace + w.dv_off);
   p.tm = tm->dview;
-  p.tm.tok_table = sm ? sm->dev_table : nullptr;
   p.L = s->L;
-  p.T = tokens_of(s, sm);
+  p.T = (int)tokens_of(tm, s);
   p.Hq = s->Hq;
   p.Hkv = s->Hkv;
   p.L64 = w.L64;
@@ -109,7 +108,7 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const pe
 
 extern "C" size_t peagle_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape) {
   if (check_shape(tm, shape) != PEAGLE_OK) return 0;
-  return ws_layout(shape).total;
+  return ws_layout(tm, shape).total;
 }
 
 extern "C" int peagle_attn_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg, const void* q,
@@ -121,7 +120,7 @@ extern "C" int peagle_attn_fwd(const peagle_tilemap_t* tm, const peagle_shape_t*
   rc = peagle::resolve_segment(tm, shape->L, seg, &sr);
   if (rc != PEAGLE_OK) return rc;
   if (tm->device < 0) return PEAGLE_ENODEVICE;
-  const FwdParams p = make_fwd(tm, shape, nullptr, sr, q, k, v, o, lse);
+  const FwdParams p = make_fwd(tm, shape, sr, q, k, v, o, lse);
   return peagle::launch_fwd(p, shape->D, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }
 
@@ -136,41 +135,39 @@ extern "C" int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t*
   SegRange sr;
   rc = peagle::resolve_segment(tm, shape->L, seg, &sr);
   if (rc != PEAGLE_OK) return rc;
-  if (!workspace || ws_bytes < ws_layout(shape).total) return PEAGLE_EWORKSPACE;
+  if (!workspace || ws_bytes < ws_layout(tm, shape).total) return PEAGLE_EWORKSPACE;
   if (tm->device < 0) return PEAGLE_ENODEVICE;
-  const BwdParams p =
-      make_bwd(tm, shape, nullptr, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, accumulate);
+  const BwdParams p = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, accumulate);
   const int acc_below = accumulate ? INT_MAX : 0;
   return peagle::launch_bwd(p, shape->D, sr.a_hi, acc_below, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK
                                                                                                    : PEAGLE_EHIP;
 }
 
-static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const peagle_sampling_t* sm,
-                     int32_t seg_begin, int32_t seg_end, const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
+static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin, int32_t seg_end,
+                     const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
                      float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes,
                      void* stream, peagle::KernelTimer* timer) {
   int rc = check_shape(tm, shape);
   if (rc != PEAGLE_OK) return rc;
   if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
   if (seg_begin < 0 || seg_end > tm->S || seg_begin > seg_end) return PEAGLE_EINVAL;
-  if (sm && (sm->L != shape->L || sm->K != shape->K)) return PEAGLE_ESHAPE;
-  if (!workspace || ws_bytes < ws_layout(shape).total) return PEAGLE_EWORKSPACE;
-  if (tm->device < 0 || (sm && sm->device != tm->device)) return PEAGLE_ENODEVICE;
+  if (!workspace || ws_bytes < ws_layout(tm, shape).total) return PEAGLE_EWORKSPACE;
+  if (tm->device < 0) return PEAGLE_ENODEVICE;
   hipStream_t st = (hipStream_t)stream;
   for (int32_t s = seg_begin; s < seg_end; ++s) {
     SegRange sr;
     rc = peagle::resolve_segment(tm, shape->L, s, &sr);
     if (rc != PEAGLE_OK) return rc;
     if (sr.a_lo >= sr.a_hi) continue;  // segment lies beyond the cropped length
-    const FwdParams fp = make_fwd(tm, shape, sm, sr, q, k, v, o, lse);
+    const FwdParams fp = make_fwd(tm, shape, sr, q, k, v, o, lse);
     if (peagle::launch_fwd(fp, shape->D, st, timer) != hipSuccess) return PEAGLE_EHIP;
     // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
     // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
-    const BwdParams bp = make_bwd(tm, shape, sm, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
+    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
     if (peagle::launch_bwd(bp, shape->D, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
   }
   if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
-    const size_t n = (size_t)tokens_of(shape, sm) * shape->Hkv * shape->D;
+    const size_t n = tokens_of(tm, shape) * shape->Hkv * shape->D;
     if (dk_bf16 && peagle::launch_cast_bf16(dk_acc, dk_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
     if (dv_bf16 && peagle::launch_cast_bf16(dv_acc, dv_bf16, n, st) != hipSuccess) return PEAGLE_EHIP;
   }
@@ -182,17 +179,7 @@ extern "C" int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const pe
                                             const void* v, const void* d_o, void* o, float* lse, void* dq,
                                             float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
                                             void* workspace, size_t ws_bytes, void* stream) {
-  return step_impl(tm, shape, nullptr, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16,
-                   dv_bf16, workspace, ws_bytes, stream, nullptr);
-}
-
-extern "C" int peagle_attn_step_sampled(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
-                                        const peagle_sampling_t* sm, int32_t seg_begin, int32_t seg_end,
-                                        const void* q, const void* k, const void* v, const void* d_o, void* o,
-                                        float* lse, void* dq, float* dk_acc, float* dv_acc, void* dk_bf16,
-                                        void* dv_bf16, void* workspace, size_t ws_bytes, void* stream) {
-  if (!sm) return PEAGLE_ENULL;
-  return step_impl(tm, shape, sm, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
+  return step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
                    workspace, ws_bytes, stream, nullptr);
 }
 
@@ -207,8 +194,8 @@ extern "C" int peagle_attn_step_profiled(const peagle_tilemap_t* tm, const peagl
     profile->launches[i] = 0;
   }
   peagle::KernelTimer timer;
-  int rc = step_impl(tm, shape, nullptr, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr,
-                     nullptr, workspace, ws_bytes, stream, &timer);
+  int rc = step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr,
+                     workspace, ws_bytes, stream, &timer);
   if (rc != PEAGLE_OK) return rc;
   return timer.collect(profile->ms, profile->launches) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }

@@ -30,30 +30,28 @@ __device__ __forceinline__ bool key_token(const DeviceTileMap& tm, int kt, int r
     return tok < L;
   }
   const int cid = kt - tm.n_d0;
+  if (tm.row_tok) {  // sampled map: explicit list of the tile's chain keys
+    tok = tm.chain_tok[(size_t)cid * kKeysPerTile + row];
+    return tok >= 0;
+  }
   const int R = cid / tm.n_csub;
   const int ck = (cid - R * tm.n_csub) * kKeysPerTile + row;
   const int e = ck / tm.A;
   const int j = R * tm.A + (ck - e * tm.A);
   tok = (1 + e) * L + j;
-  bool ok = ck < tm.A * (tm.K - 1) && j < L;
-  if (tm.tok_table) {  // sampled sequence: the position may have been dropped
-    tok = ok ? tm.tok_table[tok] : -1;
-    ok = tok >= 0;
-  }
-  return ok;
+  return ck < tm.A * (tm.K - 1) && j < L;
 }
 
 // Token of row `r` of row tile `rt`; false if the row is padding or beyond the sequence.
 __device__ __forceinline__ bool row_token(const DeviceTileMap& tm, int rt, int r, int L, int& tok) {
+  if (tm.row_tok) {  // sampled map: explicit list of the tile's rows
+    tok = tm.row_tok[(size_t)rt * kRowsPerTile + r];
+    return tok >= 0;
+  }
   const int d = r / tm.A;
   const int i = rt * tm.A + (r - d * tm.A);
   tok = d * L + i;
-  bool ok = d < tm.K && i < L;
-  if (tm.tok_table) {
-    tok = ok ? tm.tok_table[tok] : -1;
-    ok = tok >= 0;
-  }
-  return ok;
+  return d < tm.K && i < L;
 }
 
 __device__ __forceinline__ uint4 ld16(const __bf16* p) { return *reinterpret_cast<const uint4*>(p); }
@@ -119,10 +117,11 @@ struct RowDmaLane {
   static constexpr int kBlocks = kRowsPerTile * D * 2 / 1024;
   static constexpr int kPer = kBlocks / NW;
   static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
-  int tok0[kPer];    // d*L + a : token of the row in row tile 0 (index into the token table if sampled)
+  int tok0[kPer];    // d*L + a : token of the row in row tile 0 (dense map)
   int a[kPer];       // anchor offset inside the row tile; >= A*K... marks a padding row via a huge value
+  int row[kPer];     // row of the tile (index into a sampled map's row list)
   int chunk[kPer];   // element offset of the logical 16-byte chunk this lane fetches
-  int stat_tok0, stat_a;  // same for the row whose per-row statistic this lane copies (waves 0..3)
+  int stat_tok0, stat_a, stat_row;  // same for the row whose per-row statistic this lane copies (waves 0..3)
 };
 template <int D, int NW>
 __device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& tm, int L, int wave, int lane) {
@@ -131,15 +130,19 @@ __device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& t
 #pragma unroll
   for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
     const int row = (i * NW + wave) * (512 / D) + row_in_blk;
-    const int d = row / tm.A, a = row - d * tm.A;
+    const int A = tm.row_tok ? 1 : tm.A;  // a sampled map has no fixed geometry; rows come from its list
+    const int d = row / A, a = row - d * A;
     r.tok0[i] = d * L + a;
     r.a[i] = d < tm.K ? a : (1 << 30);
+    r.row[i] = row;
     r.chunk[i] = (phys ^ swz<D>(row)) << 3;
   }
   const int srow = (wave & 1) * 64 + lane;
-  const int sd = srow / tm.A, sa = srow - sd * tm.A;
+  const int A = tm.row_tok ? 1 : tm.A;
+  const int sd = srow / A, sa = srow - sd * A;
   r.stat_tok0 = sd * L + sa;
   r.stat_a = sd < tm.K ? sa : (1 << 30);
+  r.stat_row = srow;
   return r;
 }
 template <int D, int NW>
@@ -150,8 +153,8 @@ __device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base,
   for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
     bool ok = i0 + rl.a[i] < L;  // padding rows carry a huge anchor offset
     int tok = rl.tok0[i] + i0;
-    if (tm.tok_table) {
-      tok = ok ? tm.tok_table[tok] : -1;
+    if (tm.row_tok) {
+      tok = tm.row_tok[(size_t)rt * kRowsPerTile + rl.row[i]];
       ok = tok >= 0;
     }
     const size_t off = ((size_t)(ok ? tok : 0) * Hq + h) * D + rl.chunk[i];
@@ -167,8 +170,8 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
   const int i0 = rt * tm.A;
   bool ok = i0 + rl.stat_a < L;
   int tok = rl.stat_tok0 + i0;
-  if (tm.tok_table) {
-    tok = ok ? tm.tok_table[tok] : -1;
+  if (tm.row_tok) {
+    tok = tm.row_tok[(size_t)rt * kRowsPerTile + rl.stat_row];
     ok = tok >= 0;
   }
   dma4(ok ? (const void*)(base + (size_t)h * T + tok) : tm.zeros,

@@ -44,6 +44,91 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }  // namespace
 
+namespace {
+
+// Second half of both builders: key tile -> row tile lists, per-segment offsets, device copy.
+// `key_count[t]` = entries that name key tile t.  Takes ownership of tm (deleted on failure).
+int finish_map(peagle_tilemap* tm, const std::vector<int32_t>& key_count, int32_t device, peagle_tilemap_t** out) {
+  // key tile -> row tiles (ascending), same mask ids
+  tm->key_ptr.assign(tm->n_key_tiles + 1, 0);
+  for (int32_t t = 0; t < tm->n_key_tiles; ++t) tm->key_ptr[t + 1] = tm->key_ptr[t] + key_count[t];
+  tm->key_entries.resize(tm->row_entries.size());
+  std::vector<int32_t> fill(tm->key_ptr.begin(), tm->key_ptr.end() - 1);
+  for (int32_t R = 0; R < tm->n_row_tiles; ++R)
+    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
+      const TileEntry& en = tm->row_entries[e];
+      tm->key_entries[fill[en.tile]++] = TileEntry{R, en.mask_id};
+    }
+
+  // per key tile: where the row tiles of each segment start inside its list
+  tm->key_seg_ptr.resize((size_t)tm->n_key_tiles * (tm->S + 1));
+  for (int32_t t = 0; t < tm->n_key_tiles; ++t) {
+    int32_t e = tm->key_ptr[t];
+    for (int32_t sg = 0; sg <= tm->S; ++sg) {
+      const int32_t first_rt = tm->seg_rt[sg];
+      while (e < tm->key_ptr[t + 1] && tm->key_entries[e].tile < first_rt) ++e;
+      tm->key_seg_ptr[(size_t)t * (tm->S + 1) + sg] = e;
+    }
+  }
+
+  tm->device = device;
+  if (device >= 0) {
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) {
+      delete tm;
+      return PEAGLE_EHIP;
+    }
+    constexpr int kArrays = 10;
+    static const char kZeros[256] = {0};
+    const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
+                                tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
+                                tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
+                                sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t),
+                                tm->row_tok.size() * sizeof(int32_t), tm->chain_tok.size() * sizeof(int32_t)};
+    const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
+                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
+                                tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data()};
+    size_t off[kArrays], total = 0;
+    for (int i = 0; i < kArrays; ++i) {
+      off[i] = total;
+      total += align256(sz[i] ? sz[i] : 4);
+    }
+    hipError_t err = hipMalloc(&tm->dev_blob, total);
+    for (int i = 0; i < kArrays && err == hipSuccess; ++i)
+      if (sz[i]) err = hipMemcpy((char*)tm->dev_blob + off[i], src[i], sz[i], hipMemcpyHostToDevice);
+    if (err == hipSuccess) err = hipDeviceSynchronize();
+    (void)hipSetDevice(prev);
+    if (err != hipSuccess) {
+      if (tm->dev_blob) (void)hipFree(tm->dev_blob);
+      delete tm;
+      return PEAGLE_EHIP;
+    }
+    tm->dev_bytes = (int64_t)total;
+    char* base = (char*)tm->dev_blob;
+    tm->dview.row_ptr = (const int32_t*)(base + off[0]);
+    tm->dview.row_entries = (const TileEntry*)(base + off[1]);
+    tm->dview.key_ptr = (const int32_t*)(base + off[2]);
+    tm->dview.key_entries = (const TileEntry*)(base + off[3]);
+    tm->dview.masks = (const uint32_t*)(base + off[4]);
+    tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
+    tm->dview.zeros = base + off[6];
+    tm->dview.row_lead = (const int32_t*)(base + off[7]);
+    tm->dview.row_tok = tm->row_tok.empty() ? nullptr : (const int32_t*)(base + off[8]);
+    tm->dview.chain_tok = tm->chain_tok.empty() ? nullptr : (const int32_t*)(base + off[9]);
+    tm->dview.A = tm->A;
+    tm->dview.K = tm->K;
+    tm->dview.S = tm->S;
+    tm->dview.n_row_tiles = tm->n_row_tiles;
+    tm->dview.n_d0 = tm->n_d0;
+    tm->dview.n_csub = tm->n_csub;
+    tm->dview.n_key_tiles = tm->n_key_tiles;
+  }
+  *out = tm;
+  return PEAGLE_OK;
+}
+
+}  // namespace
+
 extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg_bounds, int32_t S, int32_t device,
                                     peagle_tilemap_t** out) {
   if (!out) return PEAGLE_ENULL;
@@ -144,80 +229,10 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
     tm->row_lead.push_back(lead);
   }
   tm->n_masks = (int32_t)pool.index.size();
-
-  // key tile -> row tiles (ascending), same mask ids
-  tm->key_ptr.assign(tm->n_key_tiles + 1, 0);
-  for (int32_t t = 0; t < tm->n_key_tiles; ++t) tm->key_ptr[t + 1] = tm->key_ptr[t] + key_count[t];
-  tm->key_entries.resize(tm->row_entries.size());
-  std::vector<int32_t> fill(tm->key_ptr.begin(), tm->key_ptr.end() - 1);
-  for (int32_t R = 0; R < tm->n_row_tiles; ++R)
-    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
-      const TileEntry& en = tm->row_entries[e];
-      tm->key_entries[fill[en.tile]++] = TileEntry{R, en.mask_id};
-    }
-
-  // per key tile: where the row tiles of each segment start inside its list
-  tm->key_seg_ptr.resize((size_t)tm->n_key_tiles * (S + 1));
-  for (int32_t t = 0; t < tm->n_key_tiles; ++t) {
-    int32_t e = tm->key_ptr[t];
-    for (int32_t sg = 0; sg <= S; ++sg) {
-      const int32_t first_rt = sg == S ? tm->n_row_tiles : b[sg] / A;
-      while (e < tm->key_ptr[t + 1] && tm->key_entries[e].tile < first_rt) ++e;
-      tm->key_seg_ptr[(size_t)t * (S + 1) + sg] = e;
-    }
-  }
-
-  tm->device = device;
-  if (device >= 0) {
-    int prev = -1;
-    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) {
-      delete tm;
-      return PEAGLE_EHIP;
-    }
-    constexpr int kArrays = 8;
-    static const char kZeros[256] = {0};
-    const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
-                                tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
-                                tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
-                                sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t)};
-    const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
-                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
-                                tm->row_lead.data()};
-    size_t off[kArrays], total = 0;
-    for (int i = 0; i < kArrays; ++i) {
-      off[i] = total;
-      total += align256(sz[i] ? sz[i] : 4);
-    }
-    hipError_t err = hipMalloc(&tm->dev_blob, total);
-    for (int i = 0; i < kArrays && err == hipSuccess; ++i)
-      if (sz[i]) err = hipMemcpy((char*)tm->dev_blob + off[i], src[i], sz[i], hipMemcpyHostToDevice);
-    if (err == hipSuccess) err = hipDeviceSynchronize();
-    (void)hipSetDevice(prev);
-    if (err != hipSuccess) {
-      if (tm->dev_blob) (void)hipFree(tm->dev_blob);
-      delete tm;
-      return PEAGLE_EHIP;
-    }
-    tm->dev_bytes = (int64_t)total;
-    char* base = (char*)tm->dev_blob;
-    tm->dview.row_ptr = (const int32_t*)(base + off[0]);
-    tm->dview.row_entries = (const TileEntry*)(base + off[1]);
-    tm->dview.key_ptr = (const int32_t*)(base + off[2]);
-    tm->dview.key_entries = (const TileEntry*)(base + off[3]);
-    tm->dview.masks = (const uint32_t*)(base + off[4]);
-    tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
-    tm->dview.zeros = base + off[6];
-    tm->dview.row_lead = (const int32_t*)(base + off[7]);
-    tm->dview.A = A;
-    tm->dview.K = K;
-    tm->dview.S = S;
-    tm->dview.n_row_tiles = tm->n_row_tiles;
-    tm->dview.n_d0 = tm->n_d0;
-    tm->dview.n_csub = tm->n_csub;
-    tm->dview.n_key_tiles = tm->n_key_tiles;
-  }
-  *out = tm;
-  return PEAGLE_OK;
+  tm->seg_rt.resize(S + 1);
+  for (int32_t sg = 0; sg <= S; ++sg) tm->seg_rt[sg] = sg == S ? tm->n_row_tiles : b[sg] / A;
+  tm->T_tokens = (int64_t)L_max * K;
+  return finish_map(tm, key_count, device, out);
 }
 
 extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
@@ -232,65 +247,145 @@ extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
   delete tm;
 }
 
-extern "C" int peagle_build_sampling(const int32_t* depth_count, int32_t L, int32_t K, int32_t device,
-                                     peagle_sampling_t** out) {
+// Tile map of a drop-token sampled sequence (Conditional Drop-token sampling, PARD paragraph of
+// Sec. 3; kept positions are nested per anchor, Sec. 3.2 Challenge 2).  Same structure as the
+// dense map, with three differences: a row tile is a run of consecutive anchors packed greedily
+// until its kept positions would exceed 128 rows (never across a segment boundary), so every
+// tile is full of rows that exist; rows and chain keys are named by explicit token lists; the
+// partial masks depend on the sample and are built per tile from the same visibility rule.
+extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t L, int32_t K,
+                                            const int32_t* seg_bounds, int32_t S, int32_t device,
+                                            peagle_tilemap_t** out) {
   if (!out) return PEAGLE_ENULL;
   *out = nullptr;
   if (!depth_count) return PEAGLE_ENULL;
-  if (L < 1 || K < 1 || device < -1) return PEAGLE_EINVAL;
-  if (K > peagle::kRowsPerTile) return PEAGLE_EUNSUPPORTED;
-  if ((int64_t)L * K > INT32_MAX) return PEAGLE_EINVAL;
+  if (L < 1 || S < 1 || K < 1 || device < -1) return PEAGLE_EINVAL;
+  if (K > kRowsPerTile) return PEAGLE_EUNSUPPORTED;
+  if ((int64_t)L * K > (int64_t)1 << 30) return PEAGLE_EUNSUPPORTED;
+  if (!seg_bounds && S != 1) return PEAGLE_ENULL;
   for (int32_t i = 0; i < L; ++i)
     if (depth_count[i] < 1 || depth_count[i] > K) return PEAGLE_EINVAL;
-  peagle_sampling* sm = new (std::nothrow) peagle_sampling();
-  if (!sm) return PEAGLE_EHIP;
-  sm->L = L;
-  sm->K = K;
-  sm->table.assign((size_t)L * K, -1);
+
+  peagle_tilemap* tm = new (std::nothrow) peagle_tilemap();
+  if (!tm) return PEAGLE_EINVAL;
+  tm->L_max = L;
+  tm->K = K;
+  tm->S = S;
+  tm->A = 0;  // anchors per row tile vary
+  tm->sampled = 1;
+  if (seg_bounds) tm->seg_bounds.assign(seg_bounds, seg_bounds + S + 1);
+  else tm->seg_bounds = {0, L};
+  const std::vector<int32_t>& b = tm->seg_bounds;
+  bool ok = b[0] == 0 && b[S] == L;
+  for (int s = 0; s < S && ok; ++s) ok = b[s] < b[s + 1];
+  if (!ok) {
+    delete tm;
+    return PEAGLE_EBOUNDS;
+  }
+
+  // token of (depth, anchor): depth-major storage, kept anchors ascending
+  std::vector<int32_t> tok_of((size_t)L * K, -1);
   int32_t next = 0;
   for (int32_t g = 0; g < K; ++g)
     for (int32_t i = 0; i < L; ++i)
-      if (depth_count[i] > g) sm->table[(size_t)g * L + i] = next++;
-  sm->T = next;
-  if (device >= 0) {
-    int prev = 0;
-    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) {
-      delete sm;
-      return PEAGLE_EHIP;
-    }
-    const size_t bytes = sm->table.size() * sizeof(int32_t);
-    hipError_t err = hipMalloc((void**)&sm->dev_table, bytes);
-    if (err == hipSuccess) err = hipMemcpy(sm->dev_table, sm->table.data(), bytes, hipMemcpyHostToDevice);
-    (void)hipSetDevice(prev);
-    if (err != hipSuccess) {
-      if (sm->dev_table) (void)hipFree(sm->dev_table);
-      delete sm;
-      return PEAGLE_EHIP;
-    }
-    sm->device = device;
-  }
-  *out = sm;
-  return PEAGLE_OK;
-}
+      if (depth_count[i] > g) tok_of[(size_t)g * L + i] = next++;
+  tm->T_tokens = next;
+  tm->tok_pos.assign(next, -1);
 
-extern "C" void peagle_sampling_destroy(peagle_sampling_t* sm) {
-  if (!sm) return;
-  if (sm->dev_table) {
-    int prev = 0;
-    if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(sm->device) == hipSuccess) {
-      (void)hipFree(sm->dev_table);
-      (void)hipSetDevice(prev);
+  // greedy packing of anchors into row tiles, one segment at a time
+  std::vector<int32_t> tile_a0, tile_a1;  // anchors [a0, a1) of each row tile
+  tm->seg_rt.assign(S + 1, 0);
+  for (int32_t sg = 0; sg < S; ++sg) {
+    tm->seg_rt[sg] = (int32_t)tile_a0.size();
+    int32_t a = b[sg];
+    while (a < b[sg + 1]) {
+      int32_t rows = 0, e = a;
+      while (e < b[sg + 1] && rows + depth_count[e] <= kRowsPerTile) rows += depth_count[e++];
+      tile_a0.push_back(a);
+      tile_a1.push_back(e);
+      a = e;
     }
   }
-  delete sm;
+  tm->n_row_tiles = (int32_t)tile_a0.size();
+  tm->seg_rt[S] = tm->n_row_tiles;
+  tm->n_d0 = (L + kKeysPerTile - 1) / kKeysPerTile;
+  tm->n_csub = K > 1 ? kRowsPerTile / kKeysPerTile : 0;  // a tile's chain keys are rows minus anchors: < 128
+  tm->n_key_tiles = tm->n_d0 + tm->n_row_tiles * tm->n_csub;
+
+  MaskPool pool;
+  pool.storage = &tm->masks;
+  std::vector<uint32_t> bits(kMaskWords);
+  tm->row_ptr.assign(tm->n_row_tiles + 1, 0);
+  tm->row_tok.assign((size_t)tm->n_row_tiles * kRowsPerTile, -1);
+  tm->chain_tok.assign((size_t)tm->n_row_tiles * tm->n_csub * kKeysPerTile, -1);
+  std::vector<int32_t> key_count(tm->n_key_tiles, 0);
+  std::vector<int32_t> row_a(kRowsPerTile), row_d(kRowsPerTile), key_a, key_e;
+  for (int32_t R = 0; R < tm->n_row_tiles; ++R) {
+    const int32_t a0 = tile_a0[R], a1 = tile_a1[R];
+    // rows of the tile, depth-major like the dense tile; chain keys = its rows of depth >= 1
+    int rows_used = 0;
+    key_a.clear();
+    key_e.clear();
+    for (int32_t g = 0; g < K; ++g)
+      for (int32_t i = a0; i < a1; ++i)
+        if (depth_count[i] > g) {
+          row_a[rows_used] = i;
+          row_d[rows_used] = g;
+          tm->row_tok[(size_t)R * kRowsPerTile + rows_used] = tok_of[(size_t)g * L + i];
+          tm->tok_pos[tok_of[(size_t)g * L + i]] = (int64_t)R * kRowsPerTile + rows_used;
+          ++rows_used;
+          if (g >= 1) {
+            key_a.push_back(i);
+            key_e.push_back(g);
+          }
+        }
+    // depth-0 stream
+    for (int32_t c = 0; c < tm->n_d0; ++c) {
+      const int64_t j0 = (int64_t)c * kKeysPerTile, j1 = j0 + kKeysPerTile - 1;
+      if (j0 > a1 - 1) break;
+      TileEntry en{c, -1};
+      if (j1 <= a0) {
+        ++tm->n_full;
+      } else {
+        std::fill(bits.begin(), bits.end(), 0u);
+        for (int r = 0; r < rows_used; ++r)
+          for (int kk = 0; kk < kKeysPerTile; ++kk)
+            if (j0 + kk < L && sees(row_a[r], row_d[r], j0 + kk, 0)) bits[r * kMaskWordsPerRow + kk / 32] |= 1u << (kk % 32);
+        en.mask_id = pool.intern(bits);
+        ++tm->n_partial;
+      }
+      tm->row_entries.push_back(en);
+      ++key_count[c];
+    }
+    // chain stream
+    for (int32_t sub = 0; sub < tm->n_csub; ++sub) {
+      const size_t k0 = (size_t)sub * kKeysPerTile;
+      if (k0 >= key_a.size()) break;
+      std::fill(bits.begin(), bits.end(), 0u);
+      const int32_t kt = tm->n_d0 + R * tm->n_csub + sub;
+      for (int kk = 0; kk < kKeysPerTile && k0 + kk < key_a.size(); ++kk) {
+        const int32_t ja = key_a[k0 + kk], je = key_e[k0 + kk];
+        tm->chain_tok[((size_t)R * tm->n_csub + sub) * kKeysPerTile + kk] = tok_of[(size_t)je * L + ja];
+        for (int r = 0; r < rows_used; ++r)
+          if (sees(row_a[r], row_d[r], ja, je)) bits[r * kMaskWordsPerRow + kk / 32] |= 1u << (kk % 32);
+      }
+      tm->row_entries.push_back(TileEntry{kt, pool.intern(bits)});
+      ++tm->n_partial;
+      ++key_count[kt];
+    }
+    tm->row_ptr[R + 1] = (int32_t)tm->row_entries.size();
+    int32_t lead = 0;
+    for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1] && tm->row_entries[e].mask_id < 0; ++e) ++lead;
+    tm->row_lead.push_back(lead);
+  }
+  tm->n_masks = (int32_t)pool.index.size();
+  return finish_map(tm, key_count, device, out);
 }
 
-extern "C" int64_t peagle_sampling_tokens(const peagle_sampling_t* sm) { return sm ? sm->T : 0; }
-
-extern "C" int peagle_sampling_table(const peagle_sampling_t* sm, int32_t* table_out) {
-  if (!sm || !table_out) return PEAGLE_ENULL;
-  std::memcpy(table_out, sm->table.data(), sm->table.size() * sizeof(int32_t));
-  return PEAGLE_OK;
+extern "C" int64_t peagle_tilemap_tokens(const peagle_tilemap_t* tm, int32_t L) {
+  if (!tm || L < 1 || L > tm->L_max) return -1;
+  if (tm->sampled) return L == tm->L_max ? tm->T_tokens : -1;
+  return (int64_t)L * tm->K;
 }
 
 extern "C" int peagle_tilemap_info(const peagle_tilemap_t* tm, peagle_tilemap_info_t* info) {
@@ -309,6 +404,8 @@ extern "C" int peagle_tilemap_info(const peagle_tilemap_t* tm, peagle_tilemap_in
   info->n_partial = tm->n_partial;
   info->n_masks = tm->n_masks;
   info->device_bytes = tm->dev_bytes;
+  info->tokens = tm->T_tokens;
+  info->sampled = tm->sampled;
   return PEAGLE_OK;
 }
 
@@ -328,6 +425,12 @@ int peagle::resolve_segment(const peagle_tilemap* tm, int32_t L, int32_t seg, Se
   out->cropped = hi < tm->seg_bounds[out->s_hi];
   out->a_lo = lo;
   out->a_hi = hi;
+  if (tm->sampled) {  // built for exactly this sequence: no crop, row tiles from the packing
+    if (L != tm->L_max) return PEAGLE_ESHAPE;
+    out->rt_lo = tm->seg_rt[out->s_lo];
+    out->rt_hi = tm->seg_rt[out->s_hi];
+    return PEAGLE_OK;
+  }
   out->rt_lo = lo / tm->A;
   out->rt_hi = (hi + tm->A - 1) / tm->A;
   if (lo == hi) out->rt_hi = out->rt_lo;
@@ -340,19 +443,27 @@ extern "C" int peagle_tilemap_expand_rows(const peagle_tilemap_t* tm, int32_t L,
   peagle::SegRange sr;
   int rc = peagle::resolve_segment(tm, L, seg, &sr);
   if (rc != PEAGLE_OK) return rc;
-  const int64_t T = (int64_t)L * tm->K;
+  const int64_t T = tm->sampled ? tm->T_tokens : (int64_t)L * tm->K;
   if (row_begin < 0 || row_end < row_begin || row_end > T) return PEAGLE_EINVAL;
   const int64_t row_bytes = (T + 7) / 8;
   const int A = tm->A;
   const int chain_keys = A * (tm->K - 1);
   std::memset(bits_out, 0, (size_t)((row_end - row_begin) * row_bytes));
   for (int64_t t = row_begin; t < row_end; ++t) {
-    const int64_t i = t % L;
-    const int d = (int)(t / L);
-    if (i < sr.a_lo || i >= sr.a_hi) continue;
+    int32_t R;
+    int r;
+    if (tm->sampled) {
+      R = (int32_t)(tm->tok_pos[t] / kRowsPerTile);
+      r = (int)(tm->tok_pos[t] % kRowsPerTile);
+      if (R < sr.rt_lo || R >= sr.rt_hi) continue;
+    } else {
+      const int64_t i = t % L;
+      const int d = (int)(t / L);
+      if (i < sr.a_lo || i >= sr.a_hi) continue;
+      R = (int32_t)(i / A);
+      r = d * A + (int)(i % A);  // row inside the tile
+    }
     uint8_t* dst = bits_out + (t - row_begin) * row_bytes;
-    const int32_t R = (int32_t)(i / A);
-    const int r = d * A + (int)(i % A);  // row inside the tile
     for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
       const TileEntry& en = tm->row_entries[e];
       const uint32_t* mw = en.mask_id < 0 ? nullptr : &tm->masks[(size_t)en.mask_id * kMaskWords + r * kMaskWordsPerRow];
@@ -363,6 +474,9 @@ extern "C" int peagle_tilemap_expand_rows(const peagle_tilemap_t* tm, int32_t L,
           const int64_t j = (int64_t)en.tile * kKeysPerTile + kk;
           if (j >= L) continue;
           tok = j;
+        } else if (tm->sampled) {
+          tok = tm->chain_tok[(size_t)(en.tile - tm->n_d0) * kKeysPerTile + kk];
+          if (tok < 0) continue;
         } else {
           const int32_t cid = en.tile - tm->n_d0;
           const int ck = (cid % tm->n_csub) * kKeysPerTile + kk;

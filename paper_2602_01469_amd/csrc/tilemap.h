@@ -32,15 +32,20 @@ struct DeviceTileMap {
   const int32_t* key_seg_ptr; // [n_key_tiles][S + 1]  offsets into key_entries: where each segment's row tiles start
   const uint32_t* masks;      // [n_masks][128][2]
   const void* zeros;          // 256 zero bytes: source of rows that do not exist, for direct-to-LDS loads
-  const int32_t* tok_table;   // per call, not part of the map: [K][L] token of (depth, anchor) of a drop-token
-                              // sampled sequence, -1 where the position was dropped; null for a dense sequence
+  const int32_t* row_tok;     // sampled maps only (else null): [n_row_tiles][128] token of each row, -1 = no row
+  const int32_t* chain_tok;   // sampled maps only: [n_row_tiles * n_csub][64] token of each chain key, -1 = none
   int32_t A, K, S, n_row_tiles, n_d0, n_csub, n_key_tiles;
 };
 
 }  // namespace peagle
 
 struct peagle_tilemap {
-  int32_t L_max = 0, K = 0, S = 0, A = 0;
+  int32_t L_max = 0, K = 0, S = 0, A = 0;       // A = 0 for a sampled map (anchors per row tile vary)
+  int32_t sampled = 0;                           // built from a drop-token sampled position set
+  int64_t T_tokens = 0;                          // stored tokens of a length-L_max sequence
+  std::vector<int32_t> seg_rt;                   // [S+1] first row tile of each segment
+  std::vector<int32_t> row_tok, chain_tok;       // explicit token lists of a sampled map (empty for a dense one)
+  std::vector<int64_t> tok_pos;                  // sampled map, host only: token -> row tile * 128 + row
   int32_t n_row_tiles = 0, n_d0 = 0, n_csub = 0, n_key_tiles = 0;
   std::vector<int32_t> seg_bounds;               // [S+1] anchors
   std::vector<int32_t> row_ptr;
@@ -56,16 +61,6 @@ struct peagle_tilemap {
   void* dev_blob = nullptr;                      // one allocation holding all device arrays
   int64_t dev_bytes = 0;
   peagle::DeviceTileMap dview{};
-};
-
-// Drop-token sampled sequence (Conditional Drop-token sampling, PARD paragraph of Sec. 3): anchor i
-// keeps depths 0 .. depth_count[i]-1; tokens are stored depth-major, kept anchors ascending.
-struct peagle_sampling {
-  int32_t L = 0, K = 0;
-  int64_t T = 0;                                 // stored tokens
-  std::vector<int32_t> table;                    // [K][L], -1 = dropped
-  int32_t device = -1;
-  int32_t* dev_table = nullptr;
 };
 
 namespace peagle {

@@ -55,14 +55,12 @@ class Run:
 
 
 class SampledRun(Run):
-    """Same for a drop-token sampled sequence: T = stored tokens of the sampling."""
+    """Same for a drop-token sampled sequence: `tm` is a sampled tile map, T = its kept positions."""
 
-    def __init__(self, tm, depth_count, K, Hq, Hkv, D, qb, kb, vb, dob, scale=None):
-        L = len(depth_count)
+    def __init__(self, tm, L, K, Hq, Hkv, D, qb, kb, vb, dob, scale=None):
         self.tm = tm
-        self.sm = pe.peagle_build_sampling(depth_count, K, device=0)
         self.shape = pe.Shape(L, K, Hq, Hkv, D, scale)
-        T = self.sm.T
+        T = tm.tokens(L)
         assert qb.shape[0] == T
         self.q, self.k, self.v, self.do = (to_dev_bf16(x) for x in (qb, kb, vb, dob))
         self.o = torch.full((T, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
@@ -71,10 +69,6 @@ class SampledRun(Run):
         self.dk = torch.full((T, Hkv, D), float("nan"), dtype=torch.float32, device="cuda")
         self.dv = torch.full((T, Hkv, D), float("nan"), dtype=torch.float32, device="cuda")
         self.ws = torch.empty(pe.peagle_workspace_bytes(tm, self.shape), dtype=torch.uint8, device="cuda")
-
-    def step(self, seg_begin, seg_end, dk_bf16=None, dv_bf16=None):
-        pe.peagle_attn_step_sampled(self.tm, self.shape, self.sm, seg_begin, seg_end, self.q, self.k, self.v, self.do,
-                                    self.o, self.lse, self.dq, self.dk, self.dv, dk_bf16, dv_bf16, self.ws)
 
 
 def rel_l2(a, b):

@@ -350,23 +350,25 @@ def _paper_example_counts():
 
 
 SAMPLED = [
-    # name, L, K, Hq, Hkv, D, retention, seed, bounds, L_max
-    ("paper_example", None, 4, 2, 1, 64, None, 300, None, None),
-    ("paper_example_two_segments", None, 4, 2, 1, 64, None, 305, [0, 32, 64], 64),
-    ("r08_k8", 200, 8, 4, 2, 64, 0.8, 310, None, None),
-    ("r08_k8_segments_cropped", 219, 8, 4, 2, 64, 0.8, 320, [0, 64, 128, 256], 256),
-    ("r05_k4_several_tiles", 700, 4, 4, 2, 64, 0.5, 330, [0, 256, 512, 700], None),
-    ("r08_d128", 150, 8, 2, 1, 128, 0.8, 340, [0, 64, 150], None),
-    ("nothing_dropped", 100, 4, 2, 2, 64, 1.0, 350, None, None),
-    ("only_depth0_kept", 100, 4, 2, 2, 64, 0.0, 360, None, None),
-    ("k3_padding_rows", 90, 3, 2, 1, 64, 0.7, 370, None, None),
+    # name, L, K, Hq, Hkv, D, retention, seed, bounds
+    ("paper_example", None, 4, 2, 1, 64, None, 300, None),
+    ("paper_example_two_segments", None, 4, 2, 1, 64, None, 305, [0, 8, 16]),
+    ("r08_k8", 200, 8, 4, 2, 64, 0.8, 310, None),
+    ("r08_k8_unaligned_segments", 219, 8, 4, 2, 64, 0.8, 320, [0, 61, 130, 219]),
+    ("r05_k4_several_tiles", 700, 4, 4, 2, 64, 0.5, 330, [0, 256, 512, 700]),
+    ("r08_d128", 150, 8, 2, 1, 128, 0.8, 340, [0, 64, 150]),
+    ("nothing_dropped", 100, 4, 2, 2, 64, 1.0, 350, None),
+    ("only_depth0_kept", 100, 4, 2, 2, 64, 0.0, 360, None),
+    ("k3", 90, 3, 2, 1, 64, 0.7, 370, None),
+    ("k16_r09", 120, 16, 2, 2, 64, 0.9, 380, [0, 50, 120]),
+    ("k1", 300, 1, 2, 1, 64, 0.5, 390, None),
 ]
 
 
-@pytest.mark.parametrize("name,L,K,Hq,Hkv,D,ret,seed,bounds,L_max", SAMPLED, ids=[c[0] for c in SAMPLED])
-def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bounds, L_max):
-    """Conditional Drop-token sampled sequences: every output of the sampled step against the oracle
-    evaluated on the explicit token list (single pass), and - where segments are given - against
+@pytest.mark.parametrize("name,L,K,Hq,Hkv,D,ret,seed,bounds", SAMPLED, ids=[c[0] for c in SAMPLED])
+def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bounds):
+    """Conditional Drop-token sampled sequences: every output of the step on a sampled tile map against the
+    oracle evaluated on the explicit token list (single pass), and - where segments are given - against
     the oracle's Algorithm 1 partitioned run."""
     from gpu_harness import SampledRun
     from peagle_inputs import cod_depth_counts
@@ -376,17 +378,15 @@ def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bound
     else:
         count = cod_depth_counts(L, K, ret, seed)
     print(f"case {name}: L={L} K={K} Hq={Hq} Hkv={Hkv} D={D} retention={ret} seed={seed} bounds={bounds} "
-          f"L_max={L_max} tokens={int(count.sum())}", flush=True)
+          f"tokens={int(count.sum())}", flush=True)
     ta, td = orc.cod_tokens(count)
     T = len(ta)
     qb, kb, vb, dob = (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1), rand_bits((T, Hkv, D), seed + 2),
                        rand_bits((T, Hq, D), seed + 3))
-    tm = pe.peagle_build_tilemap(L_max or L, K, bounds, device=0)
+    tm = pe.peagle_build_tilemap_sampled(count, K, bounds, device=0)
+    assert tm.tokens(L) == T
     S = 1 if bounds is None else len(bounds) - 1
-    r = SampledRun(tm, count, K, Hq, Hkv, D, qb, kb, vb, dob)
-    assert r.sm.T == T
-    tab = r.sm.table()
-    assert np.array_equal(tab[td, ta], np.arange(T)) and (tab >= 0).sum() == T      # storage order of the oracle
+    r = SampledRun(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
     dkb = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device="cuda")
     dvb = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device="cuda")
     r.step(0, S, dkb, dvb)
@@ -399,10 +399,23 @@ def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bound
     if S > 1:
         part = orc.attn_step_partitioned_sampled(q, k, v, do, count, K, r.shape.scale, S)
         _check_against_oracle(got, part, name + " vs Algorithm 1 partition")
+        # unpartitioned pass through the single-segment entry points on the same map
+        r1 = SampledRun(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        r1.fwd()
+        r1.bwd()
+        g1 = r1.results()
+        for n in ("O", "LSE", "dQ"):
+            assert np.array_equal(g1[n], got[n]), n
+        for n in ("dK", "dV"):
+            assert rel_l2(g1[n], got[n]) <= PART_REL, n
     if ret == 1.0:
-        # nothing dropped: same storage order as the dense layout, and the dense entry point agrees bit for bit
-        d = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        # nothing dropped: same storage order as the dense layout; the dense map must agree to rounding order
+        dm = pe.peagle_build_tilemap(L, K, bounds, device=0)
+        d = Run(dm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
         d.step(0, S)
         gd = d.results()
-        for n in ("O", "LSE", "dQ", "dK", "dV"):
-            assert np.array_equal(gd[n], got[n]), n
+        for n in ("O", "dQ"):
+            assert rel_l2(gd[n], got[n]) <= 2e-3, n          # bf16 outputs, different summation order
+        assert max_abs(gd["LSE"], got["LSE"]) <= 1e-5
+        for n in ("dK", "dV"):
+            assert rel_l2(gd[n], got[n]) <= PART_REL, n

@@ -219,50 +219,104 @@ def test_trace_length_quantiles_hit_the_published_points():
     assert ls == sorted(ls) and all(l % 16 == 0 for l in ls)
 
 
-# ----------------------------------------------------------------------------- drop-token sampling handle (host)
+# ----------------------------------------------------------------------------- sampled tile maps (host)
 
-def test_sampling_table_matches_the_oracle_token_order():
+def _expand_all(tm, L):
+    T = tm.tokens(L)
+    bits = tm.expand_rows(L, -1, 0, T)
+    return np.unpackbits(bits, axis=1, bitorder="little")[:, :T].astype(bool)
+
+
+def _paper_example_counts():
+    vals = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "partition_example.txt")) as f:
+        for line in f:
+            tok = line.split("#")[0].split()
+            if tok and tok[0] != "assign":
+                vals[tok[0]] = [int(x) for x in tok[1:]]
+    count = np.ones(vals["n"][0], dtype=np.int32)
+    for g in range(1, vals["K"][0]):
+        for p in vals[f"depth{g}"]:
+            count[p - g] = g + 1
+    return count, vals["K"][0]
+
+
+@pytest.mark.parametrize("L,K,r,seed,bounds", [
+    (16, 4, None, 0, None), (16, 4, None, 0, [0, 8, 16]), (300, 8, 0.8, 2, None), (300, 8, 0.8, 2, [0, 77, 150, 300]),
+    (50, 3, 0.0, 3, None), (64, 5, 1.0, 4, None), (200, 16, 0.9, 5, [0, 100, 200]), (130, 1, 0.5, 6, None),
+    (40, 128, 0.97, 7, None), (700, 4, 0.5, 8, [0, 1, 699, 700])])
+def test_sampled_tilemap_expands_to_the_oracle_mask_bit_exactly(L, K, r, seed, bounds):
     from oracle import peagle_oracle as orc
     from peagle_inputs import cod_depth_counts
-    for L, K, r, seed in [(16, 4, 0.6, 1), (300, 8, 0.8, 2), (50, 3, 0.0, 3), (64, 5, 1.0, 4)]:
+    if r is None:
+        count, K = _paper_example_counts()
+    else:
         count = cod_depth_counts(L, K, r, seed)
-        sm = pe.peagle_build_sampling(count, K, device=-1)
-        ta, td = orc.cod_tokens(count)
-        tab = sm.table()
-        assert sm.T == len(ta) == int(count.sum())
-        assert np.array_equal(tab[td, ta], np.arange(len(ta)))
-        assert (tab >= 0).sum() == len(ta)
-        sm.destroy()
+    tm = pe.peagle_build_tilemap_sampled(count, K, bounds, device=-1)
+    ta, td = orc.cod_tokens(count)
+    T = len(ta)
+    inf = tm.info()
+    assert inf["sampled"] == 1 and inf["tokens"] == T == tm.tokens(L)
+    ref = orc.element_mask(L, K, tokens=(ta, td))
+    assert np.array_equal(_expand_all(tm, L), ref)
+    if bounds is not None:
+        # per segment: exactly the rows of the segment's anchors, each with its full key set
+        seen = np.zeros(T, dtype=int)
+        for s in range(len(bounds) - 1):
+            bits = np.unpackbits(tm.expand_rows(L, s, 0, T), axis=1, bitorder="little")[:, :T].astype(bool)
+            rows = (ta >= bounds[s]) & (ta < bounds[s + 1])
+            assert np.array_equal(bits[rows], ref[rows]) and not bits[~rows].any()
+            seen += rows
+        assert (seen == 1).all()
+    # every row tile is packed: no tile could take the next anchor, and none crosses a segment boundary
+    assert inf["n_row_tiles"] >= -(-T // 128)
+    with pytest.raises(pe.PeagleError):
+        tm.tokens(L - 1) if L > 1 else tm.tokens(L + 1)
 
 
-def test_sampling_build_rejects_bad_arguments():
+def test_sampled_tilemap_packs_rows_densely():
+    from peagle_inputs import cod_depth_counts
+    L, K = 4096, 8
+    count = cod_depth_counts(L, K, 0.8, 2)
+    tm = pe.peagle_build_tilemap_sampled(count, K, [0, 1024, 2048, 3072, 4096], device=-1)
+    inf = tm.info()
+    T = int(count.sum())
+    assert inf["tokens"] == T
+    # greedy packing leaves at most K-1 free rows per tile (plus one short tile per segment)
+    assert inf["n_row_tiles"] <= -(-T // (128 - (K - 1))) + 4
+    dense = pe.peagle_build_tilemap(L, K, [0, 1024, 2048, 3072, 4096], device=-1).info()
+    assert inf["n_row_tiles"] < 0.6 * dense["n_row_tiles"]
+
+
+def test_sampled_tilemap_build_rejects_bad_arguments():
     lib = pe.load_library()
     import ctypes as C
     out = C.c_void_p()
     good = (C.c_int32 * 4)(1, 2, 3, 1)
-    assert lib.peagle_build_sampling(None, 4, 3, -1, C.byref(out)) == -2
-    assert lib.peagle_build_sampling(good, 4, 3, -1, None) == -2
-    assert lib.peagle_build_sampling(good, 0, 3, -1, C.byref(out)) == -1
-    assert lib.peagle_build_sampling(good, 4, 2, -1, C.byref(out)) == -1          # a count above K
-    assert lib.peagle_build_sampling((C.c_int32 * 4)(1, 0, 1, 1), 4, 3, -1, C.byref(out)) == -1   # depth 0 is always kept
-    assert lib.peagle_build_sampling(good, 4, 129, -1, C.byref(out)) == -5
+    assert lib.peagle_build_tilemap_sampled(None, 4, 3, None, 1, -1, C.byref(out)) == -2
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 1, -1, None) == -2
+    assert lib.peagle_build_tilemap_sampled(good, 0, 3, None, 1, -1, C.byref(out)) == -1
+    assert lib.peagle_build_tilemap_sampled(good, 4, 2, None, 1, -1, C.byref(out)) == -1          # a count above K
+    assert lib.peagle_build_tilemap_sampled((C.c_int32 * 4)(1, 0, 1, 1), 4, 3, None, 1, -1, C.byref(out)) == -1
+    assert lib.peagle_build_tilemap_sampled(good, 4, 129, None, 1, -1, C.byref(out)) == -5
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, (C.c_int32 * 3)(0, 3, 5), 2, -1, C.byref(out)) == -4
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 2, -1, C.byref(out)) == -2
     assert out.value is None
-    assert lib.peagle_sampling_tokens(None) == 0
+    assert lib.peagle_tilemap_tokens(None, 4) == -1
 
 
-def test_sampled_step_validates_before_launching():
-    """The sampled step entry point rejects mismatched shapes / missing pointers on the host (no GPU)."""
+def test_sampled_map_serves_only_its_own_length():
+    """Compute entry points reject another L for a sampled map on the host (no GPU involved)."""
     import ctypes as C
     lib = pe.load_library()
-    tm = pe.peagle_build_tilemap(64, 4, None, device=-1)
-    sm = pe.peagle_build_sampling([1, 2, 3, 4] * 16, 4, device=-1)
+    tm = pe.peagle_build_tilemap_sampled([1, 2, 3, 4] * 16, 4, None, device=-1)
     one = C.c_void_p(16)   # never dereferenced: validation fails first
 
-    def call(shape, sm_h, ws=one, ws_bytes=1 << 40, q=one):
-        return lib.peagle_attn_step_sampled(tm.handle, shape.c(), sm_h, 0, 1, q, one, one, one, one, one, one, one, one,
-                                            None, None, ws, ws_bytes, None)
-    assert call(pe.Shape(64, 4, 2, 1, 64), None) == -2
-    assert call(pe.Shape(64, 4, 2, 1, 64), sm.handle, q=None) == -2
-    assert call(pe.Shape(32, 4, 2, 1, 64), sm.handle) == -3                         # sampling built for another length
-    assert call(pe.Shape(64, 4, 2, 1, 64), sm.handle, ws=None) == -6
-    assert call(pe.Shape(64, 4, 2, 1, 64), sm.handle) == -8                         # host-only handles cannot launch
+    def call(shape, ws=one, ws_bytes=1 << 40):
+        return lib.peagle_attn_step_partitioned(tm.handle, shape.c(), 0, 1, one, one, one, one, one, one, one, one, one,
+                                                None, None, ws, ws_bytes, None)
+    assert call(pe.Shape(32, 4, 2, 1, 64)) == -3
+    assert call(pe.Shape(64, 4, 2, 1, 64), ws=None) == -6
+    assert call(pe.Shape(64, 4, 2, 1, 64)) == -8                                    # host-only map cannot launch
+    assert pe.peagle_workspace_bytes(tm, pe.Shape(64, 4, 2, 1, 64)) > 0
+    assert pe.peagle_workspace_bytes(tm, pe.Shape(32, 4, 2, 1, 64)) == 0
