@@ -8,6 +8,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <map>
 #include <new>
@@ -312,9 +313,13 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
   tm->n_csub = K > 1 ? kRowsPerTile / kKeysPerTile : 0;  // a tile's chain keys are rows minus anchors: < 128
   tm->n_key_tiles = tm->n_d0 + tm->n_row_tiles * tm->n_csub;
 
-  MaskPool pool;
-  pool.storage = &tm->masks;
+  // the masks of a sampled map depend on the sample: stored one per partial pair, not interned
   std::vector<uint32_t> bits(kMaskWords);
+  auto append_mask = [&](const std::vector<uint32_t>& m) {
+    tm->masks.insert(tm->masks.end(), m.begin(), m.end());
+    return tm->n_masks++;
+  };
+  std::vector<int32_t> chain_index((size_t)K * kRowsPerTile);  // [depth][anchor - a0] -> index in the tile's chain list
   tm->row_ptr.assign(tm->n_row_tiles + 1, 0);
   tm->row_tok.assign((size_t)tm->n_row_tiles * kRowsPerTile, -1);
   tm->chain_tok.assign((size_t)tm->n_row_tiles * tm->n_csub * kKeysPerTile, -1);
@@ -335,6 +340,7 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
           tm->tok_pos[tok_of[(size_t)g * L + i]] = (int64_t)R * kRowsPerTile + rows_used;
           ++rows_used;
           if (g >= 1) {
+            chain_index[(size_t)g * kRowsPerTile + (i - a0)] = (int32_t)key_a.size();
             key_a.push_back(i);
             key_e.push_back(g);
           }
@@ -347,11 +353,17 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
       if (j1 <= a0) {
         ++tm->n_full;
       } else {
+        // depth-0 keys are causal in the anchor (sees(i, d, j, 0) == j <= i): row r sees the first
+        // row_a[r] - j0 + 1 keys of the tile, a prefix mask
         std::fill(bits.begin(), bits.end(), 0u);
-        for (int r = 0; r < rows_used; ++r)
-          for (int kk = 0; kk < kKeysPerTile; ++kk)
-            if (j0 + kk < L && sees(row_a[r], row_d[r], j0 + kk, 0)) bits[r * kMaskWordsPerRow + kk / 32] |= 1u << (kk % 32);
-        en.mask_id = pool.intern(bits);
+        for (int r = 0; r < rows_used; ++r) {
+          const int64_t n_vis = std::min<int64_t>(kKeysPerTile, (int64_t)row_a[r] - j0 + 1);
+          if (n_vis <= 0) continue;
+          const uint64_t m = n_vis >= 64 ? ~0ull : ((1ull << n_vis) - 1);
+          bits[r * kMaskWordsPerRow] = (uint32_t)m;
+          bits[r * kMaskWordsPerRow + 1] = (uint32_t)(m >> 32);
+        }
+        en.mask_id = append_mask(bits);
         ++tm->n_partial;
       }
       tm->row_entries.push_back(en);
@@ -366,10 +378,15 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
       for (int kk = 0; kk < kKeysPerTile && k0 + kk < key_a.size(); ++kk) {
         const int32_t ja = key_a[k0 + kk], je = key_e[k0 + kk];
         tm->chain_tok[((size_t)R * tm->n_csub + sub) * kKeysPerTile + kk] = tok_of[(size_t)je * L + ja];
-        for (int r = 0; r < rows_used; ++r)
-          if (sees(row_a[r], row_d[r], ja, je)) bits[r * kMaskWordsPerRow + kk / 32] |= 1u << (kk % 32);
       }
-      tm->row_entries.push_back(TileEntry{kt, pool.intern(bits)});
+      // a chain key (j, e) is seen by the rows of its own anchor at depths >= e (sees(i, d, j, e) ==
+      // (j == i && e <= d)): walk each row's own chain instead of testing all pairs
+      for (int r = 0; r < rows_used; ++r)
+        for (int e = 1; e <= row_d[r]; ++e) {
+          const int64_t ck = (int64_t)chain_index[(size_t)e * kRowsPerTile + (row_a[r] - a0)] - (int64_t)k0;
+          if (ck >= 0 && ck < kKeysPerTile) bits[r * kMaskWordsPerRow + ck / 32] |= 1u << (ck % 32);
+        }
+      tm->row_entries.push_back(TileEntry{kt, append_mask(bits)});
       ++tm->n_partial;
       ++key_count[kt];
     }
@@ -378,7 +395,6 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
     for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1] && tm->row_entries[e].mask_id < 0; ++e) ++lead;
     tm->row_lead.push_back(lead);
   }
-  tm->n_masks = (int32_t)pool.index.size();
   return finish_map(tm, key_count, device, out);
 }
 

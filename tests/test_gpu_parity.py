@@ -419,3 +419,50 @@ def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bound
         assert max_abs(gd["LSE"], got["LSE"]) <= 1e-5
         for n in ("dK", "dV"):
             assert rel_l2(gd[n], got[n]) <= PART_REL, n
+
+
+def test_full_size_sampled_c3_retention_08():
+    """c3 shape under drop-token sampling with retention 0.8, in the launch configuration the benchmark's
+    --cod-retention mode times: oracle on every kept depth of sampled anchors (O, LSE, dQ), on the keys of
+    the last anchors (dK, dV), identities that hold at any size, and the unpartitioned run."""
+    from gpu_harness import SampledRun
+    from peagle_inputs import cod_depth_counts, make_inputs_tokens
+    cfg = CONFIGS["c3_median"]
+    L, K = cfg.L, cfg.K
+    count = cod_depth_counts(L, K, 0.8, cfg.seed)
+    ta, td = orc.cod_tokens(count)
+    T = len(ta)
+    print(f"case sampled c3: L={L} K={K} kept positions {T}", flush=True)
+    qb, kb, vb, dob = make_inputs_tokens(cfg, T)
+    b = cfg.seg_bounds()
+    tm = pe.peagle_build_tilemap_sampled(count, K, b, device=0)
+    r = SampledRun(tm, L, K, cfg.Hq, cfg.Hkv, cfg.D, qb, kb, vb, dob, cfg.scale)
+    r.step(0, len(b) - 1)
+    got = r.results()
+    assert not any(np.isnan(got[n]).any() for n in got)
+    g = 2
+    grp = cfg.Hq // cfg.Hkv
+    hs = slice(g * grp, (g + 1) * grp)
+    q, k, v, do = (bf16_bits_to_f64(x) for x in (qb[:, hs], kb[:, g:g + 1], vb[:, g:g + 1], dob[:, hs]))
+    rng = np.random.default_rng(1)
+    anchors = np.unique(np.concatenate([[0, 1, 63, 64, L // 2, L - 1], rng.integers(0, L, size=6),
+                                        np.nonzero(count == K)[0][:3]]))
+    rows = np.nonzero(np.isin(ta, anchors))[0]
+    print(f"case sampled c3: oracle on {len(rows)} rows", flush=True)
+    ref = orc.attn_backward(q, k, v, do, L, K, cfg.scale, rows=rows, row_block=256, tokens=(ta, td))
+    assert rel_l2(got["O"][rows][:, hs], ref["O"]) <= FWD_REL
+    _check_o_abs(got["O"][rows][:, hs], ref["O"], "sampled c3")
+    assert max_abs(got["LSE"][hs][:, rows], ref["LSE"]) <= LSE_ABS
+    assert rel_l2(got["dQ"][rows][:, hs], ref["dQ"]) <= GRAD_REL
+    rows2 = np.nonzero(ta >= L - 40)[0]                     # keys of the last anchors: seen by those anchors' rows only
+    ref2 = orc.attn_backward(q, k, v, do, L, K, cfg.scale, rows=rows2, row_block=256, tokens=(ta, td))
+    for n in ("dK", "dV"):
+        assert rel_l2(got[n][rows2][:, g:g + 1], ref2[n][rows2]) <= GRAD_REL, n
+    _check_global_identities(got, qb, kb, dob, cfg)
+    r.fwd()
+    r.bwd()
+    whole = r.results()
+    for n in ("O", "LSE", "dQ"):
+        assert np.array_equal(whole[n], got[n]), n
+    for n in ("dK", "dV"):
+        assert rel_l2(got[n], whole[n]) <= PART_REL, n
