@@ -187,6 +187,12 @@ int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_
  *
  *   depth_count  host, int32[L], each in [1, K]
  *   seg_bounds   host, int32[S+1], 0 = b_0 < ... < b_S = L, any anchor indices (NULL with S = 1)
+ *   assignment   which segment computes the rows of depth >= 1 (depth 0 always goes by position):
+ *                PEAGLE_ASSIGN_BY_ANCHOR  - with their anchor, as in the dense map;
+ *                PEAGLE_ASSIGN_ALGORITHM1 - as Algorithm 1 assigns them: depth 1 by its own position
+ *                p = i+1, deeper depths inherit from (p-1, g-1), so the chain of anchor i is computed
+ *                in the segment holding position i+1 (the last segment if i+1 is past the sequence).
+ *                Outputs do not depend on the choice (every row is computed once, dK/dV are sums).
  *
  * Storage order of every [T, ...] tensor of such a sequence: depth-major, and within a depth the
  * anchors that keep it in ascending order; T = sum(depth_count) = peagle_tilemap_tokens(tm, L).
@@ -194,11 +200,13 @@ int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_
  * shape->L == L in every entry point that takes a tile map; all of them then index tensors of T
  * rows (lse is [Hq, T]).  Its row tiles are runs of consecutive anchors packed until their kept
  * positions fill 128 rows, so no matrix-core work is spent on dropped positions; the mask is the
- * dense parallel-prediction mask restricted to kept positions.  Segment s computes the kept
- * positions of anchors [b_s, b_{s+1}) against the cumulative depth-0 context (Sec. 3.2).
+ * dense parallel-prediction mask restricted to kept positions.  Segment s computes its rows
+ * against the cumulative depth-0 context N_s = [0, b_{s+1}) and their own chains (Sec. 3.2).
  */
+#define PEAGLE_ASSIGN_BY_ANCHOR 0
+#define PEAGLE_ASSIGN_ALGORITHM1 1
 int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t L, int32_t K, const int32_t* seg_bounds,
-                                 int32_t S, int32_t device, peagle_tilemap_t** out);
+                                 int32_t S, int32_t assignment, int32_t device, peagle_tilemap_t** out);
 
 /* Stored tokens T of a length-L sequence under this map: L*K for a dense map, the kept positions
  * for a sampled one (which accepts only its own L).  -1 on a bad argument. */

@@ -4,6 +4,8 @@ Thin ctypes binding over ``libpeagle_attn.so`` (C ABI in ``include/peagle.h``). 
 used only for device buffers and streams; every step of the path runs in the HIP kernels.
 """
 from .binding import (  # noqa: F401
+    ASSIGN_ALGORITHM1,
+    ASSIGN_BY_ANCHOR,
     PeagleError,
     Shape,
     TileMap,

@@ -79,7 +79,8 @@ def load_library():
     lib.peagle_attn_step_partitioned.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                  vp, vp, vp, sz, vp]
     lib.peagle_attn_step_partitioned.restype = C.c_int
-    lib.peagle_build_tilemap_sampled.argtypes = [C.POINTER(i32), i32, i32, C.POINTER(i32), i32, i32, C.POINTER(vp)]
+    lib.peagle_build_tilemap_sampled.argtypes = [C.POINTER(i32), i32, i32, C.POINTER(i32), i32, i32, i32,
+                                                 C.POINTER(vp)]
     lib.peagle_build_tilemap_sampled.restype = C.c_int
     lib.peagle_tilemap_tokens.argtypes = [vp, i32]
     lib.peagle_tilemap_tokens.restype = i64
@@ -186,18 +187,22 @@ def peagle_build_tilemap(L_max: int, K: int, seg_bounds: Optional[Sequence[int]]
     return TileMap(out.value)
 
 
+ASSIGN_BY_ANCHOR, ASSIGN_ALGORITHM1 = 0, 1
+
+
 def peagle_build_tilemap_sampled(depth_count: Sequence[int], K: int, seg_bounds: Optional[Sequence[int]] = None,
-                                 device: int = 0) -> TileMap:
+                                 device: int = 0, assignment: int = ASSIGN_BY_ANCHOR) -> TileMap:
     lib = load_library()
     n = np.ascontiguousarray(depth_count, dtype=np.int32)
     out = C.c_void_p()
     if seg_bounds is None:
-        rc = lib.peagle_build_tilemap_sampled(n.ctypes.data_as(C.POINTER(C.c_int32)), len(n), K, None, 1, device,
-                                              C.byref(out))
+        rc = lib.peagle_build_tilemap_sampled(n.ctypes.data_as(C.POINTER(C.c_int32)), len(n), K, None, 1, assignment,
+                                              device, C.byref(out))
     else:
         b = np.ascontiguousarray(seg_bounds, dtype=np.int32)
         rc = lib.peagle_build_tilemap_sampled(n.ctypes.data_as(C.POINTER(C.c_int32)), len(n), K,
-                                              b.ctypes.data_as(C.POINTER(C.c_int32)), len(b) - 1, device, C.byref(out))
+                                              b.ctypes.data_as(C.POINTER(C.c_int32)), len(b) - 1, assignment, device,
+                                              C.byref(out))
     if rc != 0:
         raise PeagleError(rc, "peagle_build_tilemap_sampled")
     return TileMap(out.value)

@@ -255,12 +255,13 @@ extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
 // tile is full of rows that exist; rows and chain keys are named by explicit token lists; the
 // partial masks depend on the sample and are built per tile from the same visibility rule.
 extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t L, int32_t K,
-                                            const int32_t* seg_bounds, int32_t S, int32_t device,
-                                            peagle_tilemap_t** out) {
+                                            const int32_t* seg_bounds, int32_t S, int32_t assignment,
+                                            int32_t device, peagle_tilemap_t** out) {
   if (!out) return PEAGLE_ENULL;
   *out = nullptr;
   if (!depth_count) return PEAGLE_ENULL;
   if (L < 1 || S < 1 || K < 1 || device < -1) return PEAGLE_EINVAL;
+  if (assignment != PEAGLE_ASSIGN_BY_ANCHOR && assignment != PEAGLE_ASSIGN_ALGORITHM1) return PEAGLE_EINVAL;
   if (K > kRowsPerTile) return PEAGLE_EUNSUPPORTED;
   if ((int64_t)L * K > (int64_t)1 << 30) return PEAGLE_EUNSUPPORTED;
   if (!seg_bounds && S != 1) return PEAGLE_ENULL;
@@ -293,17 +294,37 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
   tm->T_tokens = next;
   tm->tok_pos.assign(next, -1);
 
+  // Segment of an anchor's rows.  Depth 0 always goes by the anchor.  The deeper rows of anchor i
+  // either follow it (by anchor), or go where Algorithm 1 puts them: the depth-1 position is
+  // p = i + 1 and is assigned by its own position, deeper depths inherit from (p-1, g-1), so the
+  // whole chain of anchor i lands in the segment that holds position i + 1 (the last one if
+  // i + 1 is past the sequence).
+  std::vector<int32_t> seg_of_pos(L + 1);
+  for (int32_t sg = 0; sg < S; ++sg)
+    for (int32_t i = b[sg]; i < b[sg + 1]; ++i) seg_of_pos[i] = sg;
+  seg_of_pos[L] = S - 1;
+  auto chain_seg = [&](int32_t i) { return assignment == PEAGLE_ASSIGN_ALGORITHM1 ? seg_of_pos[i + 1] : seg_of_pos[i]; };
+  auto rows_in = [&](int32_t i, int32_t sg) {  // rows of anchor i computed in segment sg
+    return (seg_of_pos[i] == sg ? 1 : 0) + (chain_seg(i) == sg ? depth_count[i] - 1 : 0);
+  };
+
   // greedy packing of anchors into row tiles, one segment at a time
-  std::vector<int32_t> tile_a0, tile_a1;  // anchors [a0, a1) of each row tile
+  std::vector<int32_t> tile_a0, tile_a1, tile_seg;  // anchors [a0, a1) of each row tile and its segment
   tm->seg_rt.assign(S + 1, 0);
   for (int32_t sg = 0; sg < S; ++sg) {
     tm->seg_rt[sg] = (int32_t)tile_a0.size();
-    int32_t a = b[sg];
+    int32_t a = b[sg] > 0 ? b[sg] - 1 : 0;  // the previous anchor's chain may belong here
     while (a < b[sg + 1]) {
+      if (rows_in(a, sg) == 0) {
+        ++a;
+        continue;
+      }
       int32_t rows = 0, e = a;
-      while (e < b[sg + 1] && rows + depth_count[e] <= kRowsPerTile) rows += depth_count[e++];
+      while (e < b[sg + 1] && rows + rows_in(e, sg) <= kRowsPerTile) rows += rows_in(e++, sg);
+      while (e > a && rows_in(e - 1, sg) == 0) --e;  // no trailing anchors without rows
       tile_a0.push_back(a);
       tile_a1.push_back(e);
+      tile_seg.push_back(sg);
       a = e;
     }
   }
@@ -331,9 +352,10 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
     int rows_used = 0;
     key_a.clear();
     key_e.clear();
+    const int32_t sg = tile_seg[R];
     for (int32_t g = 0; g < K; ++g)
       for (int32_t i = a0; i < a1; ++i)
-        if (depth_count[i] > g) {
+        if (depth_count[i] > g && (g == 0 ? seg_of_pos[i] : chain_seg(i)) == sg) {
           row_a[rows_used] = i;
           row_d[rows_used] = g;
           tm->row_tok[(size_t)R * kRowsPerTile + rows_used] = tok_of[(size_t)g * L + i];

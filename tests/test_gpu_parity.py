@@ -408,6 +408,21 @@ def test_sampled_sequences_match_oracle(name, L, K, Hq, Hkv, D, ret, seed, bound
             assert np.array_equal(g1[n], got[n]), n
         for n in ("dK", "dV"):
             assert rel_l2(g1[n], got[n]) <= PART_REL, n
+        # rows assigned to segments as Algorithm 1 does (chains follow position i+1): same outputs
+        tm2 = pe.peagle_build_tilemap_sampled(count, K, bounds, device=0, assignment=pe.ASSIGN_ALGORITHM1)
+        r2 = SampledRun(tm2, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        r2.step(0, S)
+        g2 = r2.results()
+        _check_against_oracle(g2, part, name + " Algorithm 1 assignment")
+        for n in ("dK", "dV"):
+            assert rel_l2(g2[n], got[n]) <= PART_REL, n
+        # resumed run on the same accumulators
+        r3 = SampledRun(tm2, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        r3.step(0, 1)
+        r3.step(1, S)
+        g3 = r3.results()
+        for n in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.array_equal(g3[n], g2[n]), n
     if ret == 1.0:
         # nothing dropped: same storage order as the dense layout; the dense map must agree to rounding order
         dm = pe.peagle_build_tilemap(L, K, bounds, device=0)

@@ -293,14 +293,15 @@ def test_sampled_tilemap_build_rejects_bad_arguments():
     import ctypes as C
     out = C.c_void_p()
     good = (C.c_int32 * 4)(1, 2, 3, 1)
-    assert lib.peagle_build_tilemap_sampled(None, 4, 3, None, 1, -1, C.byref(out)) == -2
-    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 1, -1, None) == -2
-    assert lib.peagle_build_tilemap_sampled(good, 0, 3, None, 1, -1, C.byref(out)) == -1
-    assert lib.peagle_build_tilemap_sampled(good, 4, 2, None, 1, -1, C.byref(out)) == -1          # a count above K
-    assert lib.peagle_build_tilemap_sampled((C.c_int32 * 4)(1, 0, 1, 1), 4, 3, None, 1, -1, C.byref(out)) == -1
-    assert lib.peagle_build_tilemap_sampled(good, 4, 129, None, 1, -1, C.byref(out)) == -5
-    assert lib.peagle_build_tilemap_sampled(good, 4, 3, (C.c_int32 * 3)(0, 3, 5), 2, -1, C.byref(out)) == -4
-    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 2, -1, C.byref(out)) == -2
+    assert lib.peagle_build_tilemap_sampled(None, 4, 3, None, 1, 0, -1, C.byref(out)) == -2
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 1, 0, -1, None) == -2
+    assert lib.peagle_build_tilemap_sampled(good, 0, 3, None, 1, 0, -1, C.byref(out)) == -1
+    assert lib.peagle_build_tilemap_sampled(good, 4, 2, None, 1, 0, -1, C.byref(out)) == -1          # a count above K
+    assert lib.peagle_build_tilemap_sampled((C.c_int32 * 4)(1, 0, 1, 1), 4, 3, None, 1, 0, -1, C.byref(out)) == -1
+    assert lib.peagle_build_tilemap_sampled(good, 4, 129, None, 1, 0, -1, C.byref(out)) == -5
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, (C.c_int32 * 3)(0, 3, 5), 2, 0, -1, C.byref(out)) == -4
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 2, 0, -1, C.byref(out)) == -2
+    assert lib.peagle_build_tilemap_sampled(good, 4, 3, None, 1, 2, -1, C.byref(out)) == -1          # unknown assignment
     assert out.value is None
     assert lib.peagle_tilemap_tokens(None, 4) == -1
 
@@ -320,3 +321,40 @@ def test_sampled_map_serves_only_its_own_length():
     assert call(pe.Shape(64, 4, 2, 1, 64)) == -8                                    # host-only map cannot launch
     assert pe.peagle_workspace_bytes(tm, pe.Shape(64, 4, 2, 1, 64)) > 0
     assert pe.peagle_workspace_bytes(tm, pe.Shape(32, 4, 2, 1, 64)) == 0
+
+
+@pytest.mark.parametrize("L,K,r,seed,S", [(16, 4, None, 0, 2), (16, 4, None, 0, 3), (300, 8, 0.8, 2, 4), (257, 8, 1.0, 3, 3),
+                                           (90, 3, 0.6, 4, 5), (40, 16, 0.9, 5, 2), (64, 1, 1.0, 6, 4)])
+def test_algorithm1_assignment_matches_the_oracle_partition(L, K, r, seed, S):
+    """With PEAGLE_ASSIGN_ALGORITHM1 the rows each segment computes are exactly the positions Algorithm 1
+    assigns to it (oracle partition_assign, boundaries B_s = s n / S), and every row carries its full
+    key set; the by-anchor assignment differs only in where the chains of the boundary anchors go."""
+    from oracle import peagle_oracle as orc
+    from peagle_inputs import cod_depth_counts
+    if r is None:
+        count, K = _paper_example_counts()
+    else:
+        count = cod_depth_counts(L, K, r, seed)
+    ta, td = orc.cod_tokens(count)
+    T = len(ta)
+    positions = [sorted((ta[td == g] + g).tolist()) for g in range(int(td.max()) + 1)]
+    A, N = orc.partition_assign(positions, S, L)
+    want = np.array([A[d][a + d] for a, d in zip(ta.tolist(), td.tolist())])
+    bounds = [-(-s * L // S) for s in range(S + 1)]                  # p in segment s  <=>  ceil(s n/S) <= p < ceil((s+1) n/S)
+    tm = pe.peagle_build_tilemap_sampled(count, K, bounds, device=-1, assignment=pe.ASSIGN_ALGORITHM1)
+    ref = orc.element_mask(L, K, tokens=(ta, td))
+    for s in range(S):
+        bits = np.unpackbits(tm.expand_rows(L, s, 0, T), axis=1, bitorder="little")[:, :T].astype(bool)
+        rows = want == s
+        assert np.array_equal(bits.any(axis=1), rows), s           # every row sees itself, so a computed row is non-empty
+        assert np.array_equal(bits[rows], ref[rows])
+        # the keys a segment touches: its own positions plus the cumulative depth-0 context N_s
+        touched = np.nonzero(bits.any(axis=0))[0]
+        allowed = set(np.nonzero(rows)[0].tolist()) | set(N[s])       # depth-0 token index == position
+        assert set(touched.tolist()) <= allowed
+    assert np.array_equal(_expand_all(tm, L), ref)
+    if r is None and S == 2:
+        # the printed dependency: position 8 at depth 2 shares the segment of position 7 at depth 1 (segment 0)
+        tok = {(int(a), int(d)): t for t, (a, d) in enumerate(zip(ta, td))}
+        bits0 = np.unpackbits(tm.expand_rows(L, 0, 0, T), axis=1, bitorder="little")[:, :T].astype(bool)
+        assert bits0[tok[(6, 2)]].any() and bits0[tok[(6, 1)]].any()  # anchor 6: positions 7 (depth 1) and 8 (depth 2)
