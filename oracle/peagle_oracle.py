@@ -41,7 +41,9 @@ assignment routine.  The sampled-sequence path is pinned on that same worked exa
 positions): token list against the printed position sets, mask against a brute-force rebuild
 from the dependency rules and against the dense mask restricted to kept positions, outputs
 against the dense problem's kept rows, gradients against library autograd, and Algorithm 1
-partitioning against the single pass.  No function here is "parity unpinned".
+partitioning against the single pass.  Packed batches: mask against the block-diagonal assembly of
+per-sequence masks rebuilt from the dependency rules, outputs against each sequence alone and
+against library autograd.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -61,6 +63,7 @@ __all__ = [
     "attn_step_partitioned",
     "attn_step_partitioned_sampled",
     "cod_tokens",
+    "packed_tokens",
     "partition_assign",
     "cod_position_count",
 ]
@@ -102,12 +105,26 @@ def cod_tokens(depth_count: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
     return np.concatenate(anchors), np.concatenate(depths)
 
 
+def packed_tokens(seq_lens: Sequence[int], K: int, depth_count: Optional[Sequence[int]] = None):
+    """Token list (anchor, depth, sequence) of a packed batch: the sequences are concatenated before the
+    n x K expansion of Sec. 3, anchors are numbered across the batch, storage is depth-major over the
+    whole batch (block G0 holds every sequence's depth-0 positions, then G1, ...).  ``depth_count``
+    (per global anchor) selects a drop-token sample; default: every depth kept."""
+    L = int(np.sum(seq_lens))
+    n = np.full(L, K) if depth_count is None else np.asarray(depth_count)
+    ta, td = cod_tokens(n)
+    seq_of_anchor = np.repeat(np.arange(len(seq_lens)), seq_lens)
+    return ta, td, seq_of_anchor[ta]
+
+
 def element_mask(L: int, K: int, rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
                  tokens: Optional[Tuple[np.ndarray, np.ndarray]] = None) -> np.ndarray:
     """Boolean mask M[r, c] over expanded positions, evaluated element by element.
 
     ``rows`` / ``cols`` are token indices (default: all).  ``tokens`` gives the (anchor, depth)
     of every stored token for a sampled sequence; without it the sequence is dense, T = L*K.
+    A third array in ``tokens`` is the sequence id of each token of a packed batch (anchors are
+    then numbered across the whole batch): sequences do not see each other.
     """
     T = L * K if tokens is None else len(tokens[0])
     rows = np.arange(T) if rows is None else np.asarray(rows)
@@ -124,6 +141,9 @@ def element_mask(L: int, K: int, rows: Optional[np.ndarray] = None, cols: Option
     j = j[None, :]
     e = e[None, :]
     depth0 = (e == 0) & (j <= i)
+    if tokens is not None and len(tokens) == 3:
+        ts = np.asarray(tokens[2])
+        depth0 &= ts[rows][:, None] == ts[cols][None, :]
     chain = (e >= 1) & (e <= d) & (j == i)
     return depth0 | chain
 

@@ -441,3 +441,68 @@ def test_cod_depth_counts_follow_geometric_retention():
     for g in range(1, K):
         assert sizes[g] == round(r * sizes[g - 1])
     assert abs(sum(sizes) - orc.cod_position_count(L, K, r)) < K          # the paper's n(1-r^K)/(1-r), up to rounding
+
+
+# ----------------------------------------------------------------------------- packed batches
+
+def _packed_mask_brute_force(seq_lens, K):
+    """Block-diagonal assembly of the per-sequence masks (each rebuilt from the dependency rules) in the
+    packed storage order t = d * L_total + global anchor."""
+    Lt = sum(seq_lens)
+    M = np.zeros((Lt * K, Lt * K), dtype=bool)
+    base = 0
+    for L in seq_lens:
+        m = _mask_from_dependency_rules(L, K)
+        idx = np.array([d * Lt + base + i for d in range(K) for i in range(L)])      # local t = d*L + i
+        M[np.ix_(idx, idx)] = m
+        base += L
+    return M
+
+
+@pytest.mark.parametrize("seq_lens,K", [((5, 3, 8), 3), ((1, 1, 1), 4), ((16,), 4), ((7, 20), 8)])
+def test_packed_mask_is_block_diagonal(seq_lens, K):
+    tok = orc.packed_tokens(seq_lens, K)
+    Lt = sum(seq_lens)
+    assert np.array_equal(orc.element_mask(Lt, K, tokens=tok), _packed_mask_brute_force(seq_lens, K))
+
+
+def test_packed_attention_equals_each_sequence_alone():
+    seq_lens, K, Hq, Hkv, D = (6, 11, 4), 4, 4, 2, 8
+    Lt = sum(seq_lens)
+    q, k, v, do = _rand(Lt, K, Hq, Hkv, D, 31)
+    tok = orc.packed_tokens(seq_lens, K)
+    r = orc.attn_backward(q, k, v, do, Lt, K, 0.3, tokens=tok)
+    base = 0
+    for L in seq_lens:
+        idx = np.array([d * Lt + base + i for d in range(K) for i in range(L)])
+        one = orc.attn_backward(q[idx], k[idx], v[idx], do[idx], L, K, 0.3)
+        for n in ("O", "dQ", "dK", "dV"):
+            assert np.allclose(r[n][idx], one[n], atol=1e-13), n
+        assert np.allclose(r["LSE"][:, idx], one["LSE"], atol=1e-13)
+        base += L
+    # and against library autograd with the brute-force block mask
+    M = torch.from_numpy(_packed_mask_brute_force(seq_lens, K))
+    tq = torch.from_numpy(q).requires_grad_()
+    tk = torch.from_numpy(k).requires_grad_()
+    tv = torch.from_numpy(v).requires_grad_()
+    o = torch.nn.functional.scaled_dot_product_attention(
+        tq.permute(1, 0, 2)[None], tk.permute(1, 0, 2).repeat_interleave(2, 0)[None],
+        tv.permute(1, 0, 2).repeat_interleave(2, 0)[None], attn_mask=M, scale=0.3)[0].permute(1, 0, 2)
+    (o * torch.from_numpy(do)).sum().backward()
+    assert np.allclose(r["O"], o.detach().numpy(), atol=1e-12)
+    for name, t in (("dQ", tq), ("dK", tk), ("dV", tv)):
+        assert np.allclose(r[name], t.grad.numpy(), atol=1e-11), name
+
+
+def test_packed_sampled_tokens_keep_per_sequence_structure():
+    from peagle_inputs import cod_depth_counts
+    seq_lens, K = (9, 14, 5), 4
+    Lt = sum(seq_lens)
+    count = cod_depth_counts(Lt, K, 0.7, 3)
+    ta, td, ts = orc.packed_tokens(seq_lens, K, count)
+    M = orc.element_mask(Lt, K, tokens=(ta, td, ts))
+    dense = _packed_mask_brute_force(seq_lens, K)
+    idx = td * Lt + ta
+    assert np.array_equal(M, dense[np.ix_(idx, idx)])
+    start = np.concatenate([[0], np.cumsum(seq_lens)])[ts]
+    assert np.array_equal(M.sum(axis=1), ta - start + 1 + td)
