@@ -189,6 +189,91 @@ def sampled(args) -> int:
     return 0
 
 
+def packed(args) -> int:
+    """A batch of sequences packed before the expansion and run as one problem (one launch per kernel for the
+    whole batch): lengths at evenly spaced quantiles of the paper's trace-length distribution up to the
+    median, K=8, 64/8 heads, D=64, dense.  Compared with running the same sequences one after another."""
+    import numpy as np
+    import torch
+
+    import paper_2602_01469_amd as pe
+    from peagle_inputs import useful_pairs
+    pe.load_library()
+    torch.cuda.set_device(0)
+    K, Hq, Hkv, D = 8, 64, 8, 64
+    n = args.packed
+    lens = trace_lengths([0.05 + 0.45 * i / max(n - 1, 1) for i in range(n)])
+    L = sum(lens)
+    T = L * K
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    mk = lambda h: torch.randn((T, h, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, do = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+    o, dq = torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+    dk = torch.empty((T, Hkv, D), dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    stream = torch.cuda.current_stream()
+    t0 = time.perf_counter()
+    tm = pe.peagle_build_tilemap_packed(lens, K, None, None, device=0)
+    build_ms = (time.perf_counter() - t0) * 1e3
+    shape = pe.Shape(L, K, Hq, Hkv, D)
+    ws = torch.empty(pe.peagle_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+    step = lambda: pe.peagle_attn_step_partitioned(tm, shape, 0, 1, q, k, v, do, o, lse, dq, dk, dv, None, None, ws, stream)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+
+    ms_packed = timed(step)
+    finite = bool(torch.isfinite(dk).all().item() and torch.isfinite(dv).all().item() and torch.isfinite(o.float()).all().item())
+    # the same sequences one after another, each with its own dense map and tensors
+    singles = []
+    for Lq in lens:
+        Tq = Lq * K
+        mkq = lambda h: torch.randn((Tq, h, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        tq, tk, tv, tdo = mkq(Hq), mkq(Hkv), mkq(Hkv), mkq(Hq)
+        one = {"tm": pe.peagle_build_tilemap(Lq, K, None, device=0), "shape": pe.Shape(Lq, K, Hq, Hkv, D),
+               "t": (tq, tk, tv, tdo, torch.empty_like(tq), torch.empty((Hq, Tq), dtype=torch.float32, device="cuda"),
+                     torch.empty_like(tq), torch.empty((Tq, Hkv, D), dtype=torch.float32, device="cuda"),
+                     torch.empty((Tq, Hkv, D), dtype=torch.float32, device="cuda"))}
+        one["ws"] = torch.empty(pe.peagle_workspace_bytes(one["tm"], one["shape"]), dtype=torch.uint8, device="cuda")
+        singles.append(one)
+
+    def run_singles():
+        for one in singles:
+            tq, tk, tv, tdo, to, tl, tdq, tdk, tdv = one["t"]
+            pe.peagle_attn_step_partitioned(one["tm"], one["shape"], 0, 1, tq, tk, tv, tdo, to, tl, tdq, tdk, tdv, None,
+                                            None, one["ws"], stream)
+    ms_singles = timed(run_singles)
+    prof = pe.peagle_attn_step_profiled(tm, shape, 0, 1, q, k, v, do, o, lse, dq, dk, dv, ws, stream)
+    prof_singles = {}
+    for one in singles:
+        tq, tk, tv, tdo, to, tl, tdq, tdk, tdv = one["t"]
+        pr = pe.peagle_attn_step_profiled(one["tm"], one["shape"], 0, 1, tq, tk, tv, tdo, to, tl, tdq, tdk, tdv, one["ws"],
+                                          stream)
+        for name, (ms, _) in pr.items():
+            prof_singles[name] = prof_singles.get(name, 0.0) + ms
+    flops = 14 * D * Hq * sum(useful_pairs(Lq, K) for Lq in lens)
+    info = tm.info()
+    print(json.dumps({
+        "metric": "effective masked-attn TFLOP/s fwd+bwd (useful FLOPs), packed variable-length batch",
+        "value": flops / (ms_packed * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_packed, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{n} sequences of {lens} anchors packed into one problem, K={K} Hq={Hq} Hkv={Hkv} D={D}"},
+        "one_by_one_ms": ms_singles, "one_by_one_tflops": flops / (ms_singles * 1e-3) / 1e12,
+        "kernels_ms": {name: v[0] for name, v in prof.items()}, "one_by_one_kernels_ms": prof_singles,
+        "tilemap_build_ms": build_ms, "tilemap": {"n_row_tiles": info["n_row_tiles"], "n_full": info["n_full"],
+                                                  "n_partial": info["n_partial"], "device_bytes": info["device_bytes"]},
+        "finite": finite}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,6 +289,8 @@ def main() -> int:
     ap.add_argument("--cod-retention", type=float, default=None,
                     help="instead of the headline (dense) workload, time the same shape under drop-token sampling "
                          "with this retention rate")
+    ap.add_argument("--packed", type=int, default=None,
+                    help="instead of the headline workload, time a packed batch of this many short sequences")
     ap.add_argument("--seg-anchors", type=int, default=None,
                     help="override the anchors per query-row segment (diagnostic; the default is the workload's)")
     args = ap.parse_args()
@@ -215,6 +302,8 @@ def main() -> int:
         return sweep(args)
     if args.cod_retention is not None:
         return sampled(args)
+    if args.packed is not None:
+        return packed(args)
 
     import torch
 

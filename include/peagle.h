@@ -208,6 +208,28 @@ int peagle_attn_step_partitioned(const peagle_tilemap_t* tm, const peagle_shape_
 int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t L, int32_t K, const int32_t* seg_bounds,
                                  int32_t S, int32_t assignment, int32_t device, peagle_tilemap_t** out);
 
+/*
+ * The general form of peagle_build_tilemap_sampled: a batch of n_seq sequences packed before the
+ * n x K expansion of Sec. 3 (variable-length batches; the paper trains on sequences between a few
+ * hundred and 20,000 tokens, Fig. 1), with or without drop-token sampling.
+ *
+ *   depth_count  host, int32[L] as above, or NULL: every anchor keeps all K depths (dense)
+ *   L            total anchors of the batch
+ *   seq_start    host, int32[n_seq+1], 0 = s_0 < ... < s_{n_seq} = L: sequence q owns the anchors
+ *                [s_q, s_{q+1}); NULL with n_seq = 1 means one sequence
+ *   seg_bounds   as above, over the anchors of the whole batch
+ *
+ * Anchors are numbered across the batch and storage is depth-major over the whole batch: block G0
+ * holds every sequence's depth-0 positions, then G1, ... (the layout obtained by packing first and
+ * expanding afterwards).  A row sees the depth-0 keys of its own sequence up to its anchor, and its
+ * own chain; sequences do not see each other.  Row tiles never span two sequences.  Under
+ * PEAGLE_ASSIGN_ALGORITHM1 a chain whose position i+1 is past its sequence stays in its anchor's
+ * segment.
+ */
+int peagle_build_tilemap_packed(const int32_t* depth_count, int32_t L, int32_t K, const int32_t* seq_start,
+                                int32_t n_seq, const int32_t* seg_bounds, int32_t S, int32_t assignment,
+                                int32_t device, peagle_tilemap_t** out);
+
 /* Stored tokens T of a length-L sequence under this map: L*K for a dense map, the kept positions
  * for a sampled one (which accepts only its own L).  -1 on a bad argument. */
 int64_t peagle_tilemap_tokens(const peagle_tilemap_t* tm, int32_t L);

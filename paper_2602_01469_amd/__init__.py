@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     peagle_attn_fwd,
     peagle_attn_step_partitioned,
     peagle_attn_step_profiled,
+    peagle_build_tilemap_packed,
     peagle_build_tilemap_sampled,
     peagle_measure_mfma_ceiling,
     peagle_build_tilemap,

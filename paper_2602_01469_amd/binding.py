@@ -34,7 +34,8 @@ class _InfoC(C.Structure):
 EXPORTS = [
     "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
-    "peagle_attn_step_partitioned", "peagle_build_tilemap_sampled", "peagle_tilemap_tokens",
+    "peagle_attn_step_partitioned", "peagle_build_tilemap_sampled", "peagle_build_tilemap_packed",
+    "peagle_tilemap_tokens",
     "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
@@ -82,6 +83,9 @@ def load_library():
     lib.peagle_build_tilemap_sampled.argtypes = [C.POINTER(i32), i32, i32, C.POINTER(i32), i32, i32, i32,
                                                  C.POINTER(vp)]
     lib.peagle_build_tilemap_sampled.restype = C.c_int
+    lib.peagle_build_tilemap_packed.argtypes = [C.POINTER(i32), i32, i32, C.POINTER(i32), i32, C.POINTER(i32), i32,
+                                                i32, i32, C.POINTER(vp)]
+    lib.peagle_build_tilemap_packed.restype = C.c_int
     lib.peagle_tilemap_tokens.argtypes = [vp, i32]
     lib.peagle_tilemap_tokens.restype = i64
     lib.peagle_attn_step_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -205,6 +209,27 @@ def peagle_build_tilemap_sampled(depth_count: Sequence[int], K: int, seg_bounds:
                                               C.byref(out))
     if rc != 0:
         raise PeagleError(rc, "peagle_build_tilemap_sampled")
+    return TileMap(out.value)
+
+
+def peagle_build_tilemap_packed(seq_lens: Sequence[int], K: int, depth_count: Optional[Sequence[int]] = None,
+                                seg_bounds: Optional[Sequence[int]] = None, device: int = 0,
+                                assignment: int = ASSIGN_BY_ANCHOR) -> TileMap:
+    """Tile map of a packed batch: `seq_lens` anchors per sequence; `depth_count` per global anchor or None (dense)."""
+    lib = load_library()
+    i32p = C.POINTER(C.c_int32)
+    start = np.ascontiguousarray(np.concatenate([[0], np.cumsum(seq_lens)]), dtype=np.int32)
+    L = int(start[-1])
+    n = None if depth_count is None else np.ascontiguousarray(depth_count, dtype=np.int32)
+    if n is not None and len(n) != L:
+        raise ValueError("depth_count must have one entry per anchor of the batch")
+    b = None if seg_bounds is None else np.ascontiguousarray(seg_bounds, dtype=np.int32)
+    out = C.c_void_p()
+    rc = lib.peagle_build_tilemap_packed(None if n is None else n.ctypes.data_as(i32p), L, K, start.ctypes.data_as(i32p),
+                                         len(start) - 1, None if b is None else b.ctypes.data_as(i32p),
+                                         1 if b is None else len(b) - 1, assignment, device, C.byref(out))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_build_tilemap_packed")
     return TileMap(out.value)
 
 

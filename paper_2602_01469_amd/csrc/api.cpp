@@ -139,7 +139,7 @@ extern "C" int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t*
   if (tm->device < 0) return PEAGLE_ENODEVICE;
   const BwdParams p = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, accumulate);
   const int acc_below = accumulate ? INT_MAX : 0;
-  return peagle::launch_bwd(p, shape->D, sr.a_hi, acc_below, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK
+  return peagle::launch_bwd(p, shape->D, sr.key_lo, sr.a_hi, acc_below, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK
                                                                                                    : PEAGLE_EHIP;
 }
 
@@ -164,7 +164,7 @@ static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, in
     // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
     // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
     const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
-    if (peagle::launch_bwd(bp, shape->D, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
+    if (peagle::launch_bwd(bp, shape->D, sr.key_lo, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
   }
   if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
     const size_t n = tokens_of(tm, shape) * shape->Hkv * shape->D;

@@ -40,7 +40,8 @@ struct BwdParams {
   int rt_lo, rt_hi;
   int s_lo, s_hi, cropped;  // segment boundary indices of the row range; cropped: rt_hi cuts the last segment short
   int n_d0_items;       // filled by the launcher: depth-0 work items (key-tile pairs x query heads)
-  int n_d0_tiles;       // filled by the launcher: depth-0 key tiles visible to the segment
+  int n_d0_tiles;       // filled by the launcher: depth-0 key tiles visible to the segment are [d0_tile_lo, n_d0_tiles)
+  int d0_tile_lo;
   int chain_accumulate; // chain keys: add to dk_acc/dv_acc instead of overwriting
   float c_log2, scale;
 };
@@ -60,7 +61,7 @@ struct KernelTimer {
 hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer* timer = nullptr);
 // a_hi: end anchor of the segment (depth-0 keys [0, a_hi) are visible); depth-0 keys with anchor
 // below acc_below are added to dk_acc/dv_acc, the others overwritten.
-hipError_t launch_bwd(const BwdParams& p, int D, int a_hi, int acc_below, hipStream_t stream,
+hipError_t launch_bwd(const BwdParams& p, int D, int key_lo, int a_hi, int acc_below, hipStream_t stream,
                       KernelTimer* timer = nullptr);
 // Dense bf16 MFMA issue loop on every CU: the measured matrix-core ceiling of the device, in TFLOP/s.
 hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops);

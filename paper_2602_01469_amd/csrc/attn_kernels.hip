@@ -11,6 +11,7 @@
 #include "attn_kernels.h"
 #include "mfma_util.h"
 
+#include <climits>
 #include <type_traits>
 
 namespace peagle {
@@ -145,19 +146,38 @@ __device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& t
   r.stat_row = srow;
   return r;
 }
+// Tokens of the rows this lane copies for one row tile (-1: the row does not exist).  For a dense map
+// they are arithmetic; a sampled / packed map lists them, and the loads are issued an iteration
+// before the copy that needs them so that their latency does not add to the copy's.
+template <int D, int NW>
+struct RowTokens {
+  int tok[RowDmaLane<D, NW>::kPer];
+  int stat_tok;
+};
+template <int D, int NW, bool LISTED>
+__device__ __forceinline__ RowTokens<D, NW> row_tokens(const DeviceTileMap& tm, const RowDmaLane<D, NW>& rl, int rt,
+                                                       int L) {
+  RowTokens<D, NW> t;
+  if (LISTED) {
+    const int32_t* list = tm.row_tok + (size_t)rt * kRowsPerTile;
+#pragma unroll
+    for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) t.tok[i] = list[rl.row[i]];
+    t.stat_tok = list[rl.stat_row];
+  } else {
+    const int i0 = rt * tm.A;
+#pragma unroll
+    for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) t.tok[i] = i0 + rl.a[i] < L ? rl.tok0[i] + i0 : -1;  // padding rows carry a huge anchor offset
+    t.stat_tok = i0 + rl.stat_a < L ? rl.stat_tok0 + i0 : -1;
+  }
+  return t;
+}
 template <int D, int NW>
 __device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base, int Hq, int h, const DeviceTileMap& tm,
-                                             const RowDmaLane<D, NW>& rl, int rt, int L, int wave) {
-  const int i0 = rt * tm.A;
+                                             const RowDmaLane<D, NW>& rl, const RowTokens<D, NW>& t, int wave) {
 #pragma unroll
   for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
-    bool ok = i0 + rl.a[i] < L;  // padding rows carry a huge anchor offset
-    int tok = rl.tok0[i] + i0;
-    if (tm.row_tok) {
-      tok = tm.row_tok[(size_t)rt * kRowsPerTile + rl.row[i]];
-      ok = tok >= 0;
-    }
-    const size_t off = ((size_t)(ok ? tok : 0) * Hq + h) * D + rl.chunk[i];
+    const bool ok = t.tok[i] >= 0;
+    const size_t off = ((size_t)(ok ? t.tok[i] : 0) * Hq + h) * D + rl.chunk[i];
     dma16(ok ? (const void*)(base + off) : tm.zeros, lds_tile + (i * NW + wave) * 1024);
   }
 }
@@ -166,16 +186,9 @@ __device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base,
 // caller each fill 64 rows (half = wave & 1).
 template <int D, int NW>
 __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base, int T, int h, const DeviceTileMap& tm,
-                                             const RowDmaLane<D, NW>& rl, int rt, int L, int half) {
-  const int i0 = rt * tm.A;
-  bool ok = i0 + rl.stat_a < L;
-  int tok = rl.stat_tok0 + i0;
-  if (tm.row_tok) {
-    tok = tm.row_tok[(size_t)rt * kRowsPerTile + rl.stat_row];
-    ok = tok >= 0;
-  }
-  dma4(ok ? (const void*)(base + (size_t)h * T + tok) : tm.zeros,
-       reinterpret_cast<char*>(lds_stat + half * 64));
+                                             const RowTokens<D, NW>& t, int half) {
+  const bool ok = t.stat_tok >= 0;
+  dma4(ok ? (const void*)(base + (size_t)h * T + t.stat_tok) : tm.zeros, reinterpret_cast<char*>(lds_stat + half * 64));
 }
 
 // Bit `pos` of w selects x, otherwise -inf.
@@ -558,12 +571,15 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
 //   depth-0 key tiles: one query head per workgroup, result to the per-head partial buffer;
 //   chain key tiles:   all heads of the KV group, result straight to dk_acc / dv_acc.
 // =====================================================================================
-template <int D, int RB, bool MASKED>
+// MODE 0: every element visible; 1: bitmask; 2: every element visible except for lanes whose key
+// belongs to another sequence of a packed batch (lane_off = true): those lanes contribute nothing.
+template <int D, int RB, int MODE>
 __device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds, const float* nlse_lds,
                                           const float* ndelta_lds, const NatOff<D>& no, const TrOff<D>& to,
                                           const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
                                           f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], int row_base, int g, int ln,
-                                          const uint32_t* mrow, float c) {
+                                          const uint32_t* mrow, float c, bool lane_off = false) {
+  constexpr bool MASKED = MODE == 1;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int r0 = row_base + rb * 32;  // multiple of 32
@@ -577,7 +593,7 @@ __device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds,
       const f32x4 d4 = *reinterpret_cast<const f32x4*>(ndelta_lds + r0 + 8 * q4 + 4 * g);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        s[4 * q4 + j] = l4[j];
+        s[4 * q4 + j] = MODE == 2 && lane_off ? -__builtin_inff() : l4[j];
         dp[4 * q4 + j] = d4[j];
       }
     }
@@ -619,7 +635,10 @@ __device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds,
   }
 }
 
-template <int D, int RH>
+// LISTED: the map names rows by explicit token lists (sampled / packed maps); their tokens are then
+// fetched an iteration before the copy that uses them.  A dense map computes them when it issues
+// the copy and carries no token registers.
+template <int D, int RH, bool LISTED>
 __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_kernel(BwdParams p) {
   constexpr int RB = 4 / RH;  // 32-row blocks per wave per row tile
   constexpr int kTileBytes = kRowsPerTile * D * 2;
@@ -640,10 +659,10 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     // Workgroups are dealt round-robin to the XCDs, so b % Hkv pins a KV head to an XCD's L2;
     // within it the key-tile pairs of one query head are adjacent, so the workgroups that are
     // resident together stream the same head's Q / dO rows and share them in L2.
-    const int n_pairs = (p.n_d0_tiles + 1) / 2;
+    const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
     kvh = b % p.Hkv;
     b /= p.Hkv;
-    kt0 = 2 * (b % n_pairs);
+    kt0 = p.d0_tile_lo + 2 * (b % n_pairs);
     h_lo = kvh * group + b / n_pairs;
     h_hi = h_lo + 1;
     n_tiles = kt0 + 1 < p.n_d0_tiles ? 2 : 1;
@@ -689,6 +708,7 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   bf16x8 kf[D / 16], vf[D / 16];
   int key_tok = 0;
   const bool key_ok = tile_present && key_token(tm, kt, (kblk & 1) * 32 + ln, p.L, key_tok);
+  const int key_anchor = kt * kKeysPerTile + (kblk & 1) * 32 + ln;  // meaningful for depth-0 tiles only
   {
     const size_t off = ((size_t)(key_ok ? key_tok : 0) * p.Hkv + kvh) * D + g * 8;
 #pragma unroll
@@ -713,21 +733,27 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   // Q / dO row tiles and their per-row terms (-lse/scale, -Delta, prepared by the dQ kernel) go
   // straight from global memory into the LDS buffer that the next iteration reads.
   const RowDmaLane<D, 4 * RH> rl = row_dma_lane<D, 4 * RH>(tm, p.L, wave, lane);
-  auto issue = [&](int hh, int rt, int buf) {
+  using Toks = RowTokens<D, 4 * RH>;
+  auto issue = [&](int hh, const Toks& t, int buf) {
     char* base = lds + buf * kBufBytes;
-    dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rl, rt, p.L, wave);
-    dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rl, rt, p.L, wave);
+    dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rl, t, wave);
+    dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rl, t, wave);
     float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
-    if (wave < 2) dma_row_stat<D, 4 * RH>(stat, p.nlse, p.T, hh, tm, rl, rt, p.L, wave & 1);
-    else if (wave < 4) dma_row_stat<D, 4 * RH>(stat + kRowsPerTile, p.delta, p.T, hh, tm, rl, rt, p.L, wave & 1);
+    if (wave < 2) dma_row_stat<D, 4 * RH>(stat, p.nlse, p.T, hh, tm, t, wave & 1);
+    else if (wave < 4) dma_row_stat<D, 4 * RH>(stat + kRowsPerTile, p.delta, p.T, hh, tm, t, wave & 1);
   };
   // Iteration `it` handles row tile ei = it % n_row_tiles of head h_lo + it / n_row_tiles.  The
-  // list entries are read two iterations ahead (row tile for the copy issued one iteration
-  // ahead, mask for the compute), as wave-uniform values; entry -2 marks a row tile that does
-  // not see this wave's key tile.
+  // pipeline runs three deep: the list entry of iteration it+3 is fetched now and moved to scalar
+  // registers after the barrier; the row tokens of it+2 are fetched now (they need that
+  // iteration's row tile); the copy of it+1 is issued now; the mask of it+2 is fetched now.  Key-
+  // side mask ids: -1 every element visible, >= 0 a bitmask, INT_MIN nothing to do (a row tile
+  // that does not see this wave's key tile; also set by the map for row tiles listed only for the
+  // other tile of the pair), other ids <= -2 visible for keys with anchor >= -id - 2 (the row
+  // tile's sequence starts inside the key tile).
   auto fetch_row_tile = [&](int ei) { return fetch_entry(tm.key_entries, e_lo + ei); };
   auto fetch_mask = [&](int ei) { return fetch_entry(tm.key_entries, ei >= my_skip ? my_lo + ei - my_skip : e_lo + ei); };
-  auto mask_of = [&](int ei, const TileEntry& en) { return ei >= my_skip ? en.mask_id : -2; };
+  constexpr int kSkip = INT_MIN;
+  auto mask_of = [&](int ei, const TileEntry& en) { return ei >= my_skip ? en.mask_id : kSkip; };
   auto step = [&](int& ei, int& hh) {  // advance (ei, hh) by one iteration
     if (++ei == n_row_tiles) {
       ei = 0;
@@ -735,49 +761,71 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     }
   };
 
-  int ei_n = 0, hh_n = h_lo;        // next iteration (its copy is issued now)
-  int ei_a = 0, hh_a = h_lo;        // two ahead (its entries are loaded now)
-  int rt_n = 0, mask_c = -2, mask_n = -2;
+  int ei_n = 0, hh_n = h_lo;        // iteration it+1 (its copy is issued now)
+  int ei_a = 0, hh_a = h_lo;        // it+2 (its row tokens and mask are fetched now)
+  int ei_b = 0, hh_b = h_lo;        // it+3 (its list entry is fetched now)
+  int rt_n = 0, rt_a = 0, mask_c = kSkip, mask_n = kSkip;
+  Toks tok_n{};
   if (n_iter > 0) {
-    issue(h_lo, take_entry(fetch_row_tile(0)).tile, 0);
+    const Toks t0 = row_tokens<D, 4 * RH, LISTED>(tm, rl, take_entry(fetch_row_tile(0)).tile, p.L);
+    issue(h_lo, t0, 0);
+    tok_n = t0;
     mask_c = mask_of(0, take_entry(fetch_mask(0)));
     step(ei_n, hh_n);
     step(ei_a, hh_a);
+    step(ei_a, hh_a);
+    step(ei_b, hh_b);
+    step(ei_b, hh_b);
+    step(ei_b, hh_b);
     if (n_iter > 1) {
       rt_n = take_entry(fetch_row_tile(ei_n)).tile;
+      if (LISTED) tok_n = row_tokens<D, 4 * RH, LISTED>(tm, rl, rt_n, p.L);
       mask_n = mask_of(ei_n, take_entry(fetch_mask(ei_n)));
     }
-    step(ei_a, hh_a);
+    if (n_iter > 2) rt_a = take_entry(fetch_row_tile(ei_a)).tile;
   }
   dma_publish();
 
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
-    const bool have_ahead = it + 2 < n_iter;
-    const u32x2 rt_raw = fetch_row_tile(have_ahead ? ei_a : 0);
-    const u32x2 mask_raw = fetch_mask(have_ahead ? ei_a : 0);
-    if (it + 1 < n_iter) issue(hh_n, rt_n, buf ^ 1);
-    if (mask_c != -2) {
+    const bool have2 = it + 2 < n_iter, have3 = it + 3 < n_iter;
+    const u32x2 rt_raw = fetch_row_tile(have3 ? ei_b : 0);
+    const u32x2 mask_raw = fetch_mask(have2 ? ei_a : 0);
+    Toks tok_a = tok_n;
+    if (LISTED) {
+      if (have2) tok_a = row_tokens<D, 4 * RH, LISTED>(tm, rl, rt_a, p.L);
+      if (it + 1 < n_iter) issue(hh_n, tok_n, buf ^ 1);
+    } else {
+      if (it + 1 < n_iter) issue(hh_n, row_tokens<D, 4 * RH, LISTED>(tm, rl, rt_n, p.L), buf ^ 1);
+    }
+    if (mask_c != kSkip) {
       const char* q_lds = lds + buf * kBufBytes;
       const char* do_lds = q_lds + kTileBytes;
       const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * kTileBytes);
       const float* delta_lds = lse_lds + kRowsPerTile;
       const int row_base = part * (kRowsPerTile / RH);
-      if (mask_c < 0) {
-        dkdv_tile<D, RB, false>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
-                                p.c_log2);
-      } else {
+      if (mask_c == -1) {
+        dkdv_tile<D, RB, 0>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
+                            p.c_log2);
+      } else if (mask_c >= 0) {
         const uint32_t* mrow = tm.masks + (size_t)mask_c * kRowsPerTile * 2 + (kblk & 1);
-        dkdv_tile<D, RB, true>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, mrow,
-                               p.c_log2);
+        dkdv_tile<D, RB, 1>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, mrow,
+                            p.c_log2);
+      } else if (LISTED) {  // only packed maps carry such ids
+        const bool lane_off = key_anchor < -mask_c - 2;
+        dkdv_tile<D, RB, 2>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
+                            p.c_log2, lane_off);
       }
     }
     dma_publish();
-    rt_n = take_entry(rt_raw).tile;
+    if (LISTED) tok_n = tok_a;
+    rt_n = rt_a;
+    rt_a = take_entry(rt_raw).tile;
     mask_c = mask_n;
-    mask_n = have_ahead ? mask_of(ei_a, take_entry(mask_raw)) : -2;
+    mask_n = have2 ? mask_of(ei_a, take_entry(mask_raw)) : kSkip;
     step(ei_n, hh_n);
     step(ei_a, hh_a);
+    step(ei_b, hh_b);
   }
 
   // sum the row parts through LDS (part 0 owns the result), then store from registers:
@@ -858,19 +906,19 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   }
 }
 
-// Sum the per-head partials of the depth-0 keys [0, n_keys) over each KV group into dk_acc /
-// dv_acc; keys with anchor < acc_below are added to, the others overwritten.
+// Sum the per-head partials of the depth-0 keys [key_first, key_end) over each KV group into
+// dk_acc / dv_acc; keys with anchor < acc_below are added to, the others overwritten.
 template <int D>
-__global__ __launch_bounds__(256) void reduce_partials_kernel(BwdParams p, int n_keys, int acc_below) {
+__global__ __launch_bounds__(256) void reduce_partials_kernel(BwdParams p, int key_first, int key_end, int acc_below) {
   const int group = p.Hq / p.Hkv;
-  const size_t per = (size_t)n_keys * p.Hkv * (D / 4);
+  const size_t per = (size_t)(key_end - key_first) * p.Hkv * (D / 4);
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < 2 * per; idx += (size_t)gridDim.x * blockDim.x) {
     const int which = idx >= per;
     size_t rem = which ? idx - per : idx;
     const int c4 = rem % (D / 4);
     rem /= (D / 4);
     const int kvh = rem % p.Hkv;
-    const int j = (int)(rem / p.Hkv);
+    const int j = key_first + (int)(rem / p.Hkv);
     const float* part = which ? p.dv_part : p.dk_part;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     for (int hh = 0; hh < group; ++hh)
@@ -993,7 +1041,8 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
   return span.finish();
 }
 
-hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipStream_t stream, KernelTimer* timer) {
+hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc_below, hipStream_t stream,
+                      KernelTimer* timer) {
   BwdParams p = pin;
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
@@ -1007,25 +1056,33 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int a_hi, int acc_below, hipS
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
-  p.n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi
-  p.n_d0_items = (p.n_d0_tiles + 1) / 2 * p.Hq;            // key-tile pairs x query heads
+  p.n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi ...
+  p.d0_tile_lo = key_lo / kKeysPerTile & ~1;                // ... from the (even) tile pair of the first visible key on
+  p.n_d0_items = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2 * p.Hq;  // key-tile pairs x query heads
   const int n_chain_items = n_rt * ((p.tm.n_csub + 1) / 2) * p.Hkv;
   {
     const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
     TimedSpan span(timer, kKindDkDv, stream);
-    if (D == 64) hipLaunchKernelGGL((dkdv_kernel<64, 1>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((dkdv_kernel<128, 1>), grid, dim3(256), 0, stream, p);
+    const bool listed = p.tm.row_tok != nullptr;
+    if (D == 64) {
+      if (listed) hipLaunchKernelGGL((dkdv_kernel<64, 1, true>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((dkdv_kernel<64, 1, false>), grid, dim3(256), 0, stream, p);
+    } else {
+      if (listed) hipLaunchKernelGGL((dkdv_kernel<128, 1, true>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((dkdv_kernel<128, 1, false>), grid, dim3(256), 0, stream, p);
+    }
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
   {
-    const size_t n = 2 * (size_t)a_hi * p.Hkv * (D / 4);
+    const int key_first = p.d0_tile_lo * kKeysPerTile;
+    const size_t n = 2 * (size_t)(a_hi - key_first) * p.Hkv * (D / 4);
     size_t blocks = (n + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     const dim3 grid((unsigned)blocks), block(256);
     TimedSpan span(timer, kKindReduce, stream);
-    if (D == 64) hipLaunchKernelGGL((reduce_partials_kernel<64>), grid, block, 0, stream, p, a_hi, acc_below);
-    else hipLaunchKernelGGL((reduce_partials_kernel<128>), grid, block, 0, stream, p, a_hi, acc_below);
+    if (D == 64) hipLaunchKernelGGL((reduce_partials_kernel<64>), grid, block, 0, stream, p, key_first, a_hi, acc_below);
+    else hipLaunchKernelGGL((reduce_partials_kernel<128>), grid, block, 0, stream, p, key_first, a_hi, acc_below);
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }

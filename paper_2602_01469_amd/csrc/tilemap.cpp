@@ -12,6 +12,7 @@
 #include <cstring>
 #include <map>
 #include <new>
+#include <unordered_map>
 
 using peagle::kKeysPerTile;
 using peagle::kMaskWords;
@@ -51,15 +52,35 @@ namespace {
 // `key_count[t]` = entries that name key tile t.  Takes ownership of tm (deleted on failure).
 int finish_map(peagle_tilemap* tm, const std::vector<int32_t>& key_count, int32_t device, peagle_tilemap_t** out) {
   // key tile -> row tiles (ascending), same mask ids
-  tm->key_ptr.assign(tm->n_key_tiles + 1, 0);
-  for (int32_t t = 0; t < tm->n_key_tiles; ++t) tm->key_ptr[t + 1] = tm->key_ptr[t] + key_count[t];
-  tm->key_entries.resize(tm->row_entries.size());
-  std::vector<int32_t> fill(tm->key_ptr.begin(), tm->key_ptr.end() - 1);
+  (void)key_count;
+  std::vector<std::vector<TileEntry>> lists(tm->n_key_tiles);
   for (int32_t R = 0; R < tm->n_row_tiles; ++R)
     for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
       const TileEntry& en = tm->row_entries[e];
-      tm->key_entries[fill[en.tile]++] = TileEntry{R, en.mask_id};
+      // Key side of a pair that is partial only because the row tile's sequence starts inside the key
+      // tile: the keys of the earlier sequence are separate lanes of the dK/dV kernel, which drops
+      // them by anchor (id -2 - first anchor of the sequence) instead of reading a bitmask.
+      const int32_t id = tm->key_side_id.empty() ? en.mask_id : tm->key_side_id[e];
+      lists[en.tile].push_back(TileEntry{R, id});
     }
+  // The dK/dV kernel walks depth-0 key tiles in pairs (2m, 2m+1) along the list of the first and
+  // expects the list of the second to be a suffix of it.  That holds for one sequence (a row tile
+  // that sees tile 2m+1 has anchors past it and sees 2m as well).  In a packed batch a later
+  // sequence may start inside or after tile 2m: its row tiles see 2m+1 only, and they come after
+  // every row tile that sees 2m - they are appended to the list of 2m with the id INT32_MIN, which
+  // tells the waves that own the keys of 2m to sit the iteration out.
+  for (int32_t t0 = 0; t0 + 1 < tm->n_d0; t0 += 2) {
+    std::vector<TileEntry>& first = lists[t0];
+    const std::vector<TileEntry>& second = lists[t0 + 1];
+    const int32_t last_first = first.empty() ? -1 : first.back().tile;
+    for (const TileEntry& en : second)
+      if (en.tile > last_first) first.push_back(TileEntry{en.tile, INT32_MIN});
+  }
+  tm->key_ptr.assign(tm->n_key_tiles + 1, 0);
+  for (int32_t t = 0; t < tm->n_key_tiles; ++t) tm->key_ptr[t + 1] = tm->key_ptr[t] + (int32_t)lists[t].size();
+  tm->key_entries.clear();
+  tm->key_entries.reserve(tm->key_ptr[tm->n_key_tiles]);
+  for (int32_t t = 0; t < tm->n_key_tiles; ++t) tm->key_entries.insert(tm->key_entries.end(), lists[t].begin(), lists[t].end());
 
   // per key tile: where the row tiles of each segment start inside its list
   tm->key_seg_ptr.resize((size_t)tm->n_key_tiles * (tm->S + 1));
@@ -257,16 +278,44 @@ extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
 extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t L, int32_t K,
                                             const int32_t* seg_bounds, int32_t S, int32_t assignment,
                                             int32_t device, peagle_tilemap_t** out) {
+  if (out) *out = nullptr;
+  if (!depth_count) return PEAGLE_ENULL;
+  return peagle_build_tilemap_packed(depth_count, L, K, nullptr, 1, seg_bounds, S, assignment, device, out);
+}
+
+// General builder: explicit position set (depth_count, or every depth if null) of a batch of
+// sequences packed before the expansion (seq_start, or one sequence if null).
+extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_t L, int32_t K,
+                                           const int32_t* seq_start_in, int32_t n_seq, const int32_t* seg_bounds,
+                                           int32_t S, int32_t assignment, int32_t device, peagle_tilemap_t** out) {
   if (!out) return PEAGLE_ENULL;
   *out = nullptr;
-  if (!depth_count) return PEAGLE_ENULL;
-  if (L < 1 || S < 1 || K < 1 || device < -1) return PEAGLE_EINVAL;
+  if (L < 1 || S < 1 || K < 1 || n_seq < 1 || device < -1) return PEAGLE_EINVAL;
   if (assignment != PEAGLE_ASSIGN_BY_ANCHOR && assignment != PEAGLE_ASSIGN_ALGORITHM1) return PEAGLE_EINVAL;
   if (K > kRowsPerTile) return PEAGLE_EUNSUPPORTED;
   if ((int64_t)L * K > (int64_t)1 << 30) return PEAGLE_EUNSUPPORTED;
   if (!seg_bounds && S != 1) return PEAGLE_ENULL;
+  if (!seq_start_in && n_seq != 1) return PEAGLE_ENULL;
+  std::vector<int32_t> all_depths;
+  if (!depth_count_in) all_depths.assign(L, K);
+  const int32_t* depth_count = depth_count_in ? depth_count_in : all_depths.data();
   for (int32_t i = 0; i < L; ++i)
     if (depth_count[i] < 1 || depth_count[i] > K) return PEAGLE_EINVAL;
+  std::vector<int32_t> seq_start(n_seq + 1);
+  if (seq_start_in) seq_start.assign(seq_start_in, seq_start_in + n_seq + 1);
+  else seq_start = {0, L};
+  {
+    bool ok = seq_start[0] == 0 && seq_start[n_seq] == L;
+    for (int q = 0; q < n_seq && ok; ++q) ok = seq_start[q] < seq_start[q + 1];
+    if (!ok) return PEAGLE_EBOUNDS;
+  }
+  // first and one-past-last anchor of the sequence every anchor belongs to
+  std::vector<int32_t> seq_lo(L), seq_hi(L);
+  for (int32_t q = 0; q < n_seq; ++q)
+    for (int32_t i = seq_start[q]; i < seq_start[q + 1]; ++i) {
+      seq_lo[i] = seq_start[q];
+      seq_hi[i] = seq_start[q + 1];
+    }
 
   peagle_tilemap* tm = new (std::nothrow) peagle_tilemap();
   if (!tm) return PEAGLE_EINVAL;
@@ -297,13 +346,15 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
   // Segment of an anchor's rows.  Depth 0 always goes by the anchor.  The deeper rows of anchor i
   // either follow it (by anchor), or go where Algorithm 1 puts them: the depth-1 position is
   // p = i + 1 and is assigned by its own position, deeper depths inherit from (p-1, g-1), so the
-  // whole chain of anchor i lands in the segment that holds position i + 1 (the last one if
-  // i + 1 is past the sequence).
+  // whole chain of anchor i lands in the segment that holds position i + 1 (the anchor's own
+  // segment if i + 1 is past its sequence).
   std::vector<int32_t> seg_of_pos(L + 1);
   for (int32_t sg = 0; sg < S; ++sg)
     for (int32_t i = b[sg]; i < b[sg + 1]; ++i) seg_of_pos[i] = sg;
   seg_of_pos[L] = S - 1;
-  auto chain_seg = [&](int32_t i) { return assignment == PEAGLE_ASSIGN_ALGORITHM1 ? seg_of_pos[i + 1] : seg_of_pos[i]; };
+  auto chain_seg = [&](int32_t i) {  // position i + 1 past the anchor's own sequence: its last segment
+    return assignment == PEAGLE_ASSIGN_ALGORITHM1 && i + 1 < seq_hi[i] ? seg_of_pos[i + 1] : seg_of_pos[i];
+  };
   auto rows_in = [&](int32_t i, int32_t sg) {  // rows of anchor i computed in segment sg
     return (seg_of_pos[i] == sg ? 1 : 0) + (chain_seg(i) == sg ? depth_count[i] - 1 : 0);
   };
@@ -320,7 +371,7 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
         continue;
       }
       int32_t rows = 0, e = a;
-      while (e < b[sg + 1] && rows + rows_in(e, sg) <= kRowsPerTile) rows += rows_in(e++, sg);
+      while (e < b[sg + 1] && e < seq_hi[a] && rows + rows_in(e, sg) <= kRowsPerTile) rows += rows_in(e++, sg);
       while (e > a && rows_in(e - 1, sg) == 0) --e;  // no trailing anchors without rows
       tile_a0.push_back(a);
       tile_a1.push_back(e);
@@ -330,14 +381,27 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
   }
   tm->n_row_tiles = (int32_t)tile_a0.size();
   tm->seg_rt[S] = tm->n_row_tiles;
+  // first depth-0 key a segment's rows can see: the start of the sequence of its first row's anchor
+  tm->seg_key_lo.assign(S, 0);
+  for (int32_t sg = 0; sg < S; ++sg) {
+    const int32_t first = b[sg] > 0 && rows_in(b[sg] - 1, sg) > 0 ? b[sg] - 1 : b[sg];
+    tm->seg_key_lo[sg] = seq_lo[first];
+  }
   tm->n_d0 = (L + kKeysPerTile - 1) / kKeysPerTile;
   tm->n_csub = K > 1 ? kRowsPerTile / kKeysPerTile : 0;  // a tile's chain keys are rows minus anchors: < 128
   tm->n_key_tiles = tm->n_d0 + tm->n_row_tiles * tm->n_csub;
 
-  // the masks of a sampled map depend on the sample: stored one per partial pair, not interned
+  // the masks depend on the sample and on where sequences start; equal ones are stored once
   std::vector<uint32_t> bits(kMaskWords);
+  std::unordered_map<uint64_t, std::vector<int32_t>> by_hash;
   auto append_mask = [&](const std::vector<uint32_t>& m) {
+    uint64_t h = 1469598103934665603ull;
+    for (uint32_t w : m) h = (h ^ w) * 1099511628211ull;
+    std::vector<int32_t>& ids = by_hash[h];
+    for (int32_t id : ids)
+      if (std::memcmp(&tm->masks[(size_t)id * kMaskWords], m.data(), kMaskWords * sizeof(uint32_t)) == 0) return id;
     tm->masks.insert(tm->masks.end(), m.begin(), m.end());
+    ids.push_back(tm->n_masks);
     return tm->n_masks++;
   };
   std::vector<int32_t> chain_index((size_t)K * kRowsPerTile);  // [depth][anchor - a0] -> index in the tile's chain list
@@ -367,30 +431,38 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
             key_e.push_back(g);
           }
         }
-    // depth-0 stream
-    for (int32_t c = 0; c < tm->n_d0; ++c) {
+    // depth-0 stream: keys of the tile's own sequence up to its last anchor.  Depth-0 keys are causal
+    // in the anchor inside a sequence (sees(i, d, j, 0) == j <= i), so row r sees the keys
+    // [sb, row_a[r]] of a tile: a contiguous bit range.  Full tiles are listed first.
+    const int32_t sb = seq_lo[a0];
+    std::vector<TileEntry> partial_entries;
+    std::vector<int32_t> partial_key_ids;
+    for (int32_t c = sb / kKeysPerTile; c < tm->n_d0; ++c) {
       const int64_t j0 = (int64_t)c * kKeysPerTile, j1 = j0 + kKeysPerTile - 1;
       if (j0 > a1 - 1) break;
-      TileEntry en{c, -1};
-      if (j1 <= a0) {
-        ++tm->n_full;
-      } else {
-        // depth-0 keys are causal in the anchor (sees(i, d, j, 0) == j <= i): row r sees the first
-        // row_a[r] - j0 + 1 keys of the tile, a prefix mask
-        std::fill(bits.begin(), bits.end(), 0u);
-        for (int r = 0; r < rows_used; ++r) {
-          const int64_t n_vis = std::min<int64_t>(kKeysPerTile, (int64_t)row_a[r] - j0 + 1);
-          if (n_vis <= 0) continue;
-          const uint64_t m = n_vis >= 64 ? ~0ull : ((1ull << n_vis) - 1);
-          bits[r * kMaskWordsPerRow] = (uint32_t)m;
-          bits[r * kMaskWordsPerRow + 1] = (uint32_t)(m >> 32);
-        }
-        en.mask_id = append_mask(bits);
-        ++tm->n_partial;
-      }
-      tm->row_entries.push_back(en);
       ++key_count[c];
+      if (j0 >= sb && j1 <= a0) {
+        ++tm->n_full;
+        tm->row_entries.push_back(TileEntry{c, -1});
+        tm->key_side_id.push_back(-1);
+        continue;
+      }
+      std::fill(bits.begin(), bits.end(), 0u);
+      for (int r = 0; r < rows_used; ++r) {
+        const int64_t lo = std::max<int64_t>(0, (int64_t)sb - j0);
+        const int64_t hi = std::min<int64_t>(kKeysPerTile - 1, (int64_t)row_a[r] - j0);  // inclusive
+        if (hi < lo) continue;
+        const uint64_t upto_hi = hi >= 63 ? ~0ull : ((1ull << (hi + 1)) - 1);
+        const uint64_t m = upto_hi & ~((1ull << lo) - 1);
+        bits[r * kMaskWordsPerRow] = (uint32_t)m;
+        bits[r * kMaskWordsPerRow + 1] = (uint32_t)(m >> 32);
+      }
+      partial_entries.push_back(TileEntry{c, append_mask(bits)});
+      partial_key_ids.push_back(j1 <= a0 ? -2 - sb : partial_entries.back().mask_id);
+      ++tm->n_partial;
     }
+    tm->row_entries.insert(tm->row_entries.end(), partial_entries.begin(), partial_entries.end());
+    tm->key_side_id.insert(tm->key_side_id.end(), partial_key_ids.begin(), partial_key_ids.end());
     // chain stream
     for (int32_t sub = 0; sub < tm->n_csub; ++sub) {
       const size_t k0 = (size_t)sub * kKeysPerTile;
@@ -409,6 +481,7 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
           if (ck >= 0 && ck < kKeysPerTile) bits[r * kMaskWordsPerRow + ck / 32] |= 1u << (ck % 32);
         }
       tm->row_entries.push_back(TileEntry{kt, append_mask(bits)});
+      tm->key_side_id.push_back(tm->row_entries.back().mask_id);
       ++tm->n_partial;
       ++key_count[kt];
     }
@@ -463,6 +536,8 @@ int peagle::resolve_segment(const peagle_tilemap* tm, int32_t L, int32_t seg, Se
   out->cropped = hi < tm->seg_bounds[out->s_hi];
   out->a_lo = lo;
   out->a_hi = hi;
+  out->key_lo = 0;
+  if (tm->sampled && seg >= 0) out->key_lo = tm->seg_key_lo[seg];
   if (tm->sampled) {  // built for exactly this sequence: no crop, row tiles from the packing
     if (L != tm->L_max) return PEAGLE_ESHAPE;
     out->rt_lo = tm->seg_rt[out->s_lo];

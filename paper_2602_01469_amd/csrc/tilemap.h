@@ -44,7 +44,10 @@ struct peagle_tilemap {
   int32_t sampled = 0;                           // built from a drop-token sampled position set
   int64_t T_tokens = 0;                          // stored tokens of a length-L_max sequence
   std::vector<int32_t> seg_rt;                   // [S+1] first row tile of each segment
+  std::vector<int32_t> seg_key_lo;               // [S] first depth-0 key (anchor) a segment's rows can see (packed batches)
   std::vector<int32_t> row_tok, chain_tok;       // explicit token lists of a sampled map (empty for a dense one)
+  std::vector<int32_t> key_side_id;              // per row entry, packed maps only: the id the key tile -> row tile
+                                                 // list carries when it differs from the row side (see finish_map)
   std::vector<int64_t> tok_pos;                  // sampled map, host only: token -> row tile * 128 + row
   int32_t n_row_tiles = 0, n_d0 = 0, n_csub = 0, n_key_tiles = 0;
   std::vector<int32_t> seg_bounds;               // [S+1] anchors
@@ -68,6 +71,7 @@ namespace peagle {
 // Anchor range [lo, hi) of a segment clipped to a length-L problem, and the row tiles covering it.
 struct SegRange {
   int32_t a_lo, a_hi, rt_lo, rt_hi;
+  int32_t key_lo;      // first depth-0 key any of the rows can see (0 unless the map packs several sequences)
   int32_t s_lo, s_hi;  // segment boundary indices spanned: [bounds[s_lo], bounds[s_hi])
   int32_t cropped;     // the range ends before bounds[s_hi] (L < L_max cuts it short)
 };

@@ -481,3 +481,63 @@ def test_full_size_sampled_c3_retention_08():
         assert np.array_equal(whole[n], got[n]), n
     for n in ("dK", "dV"):
         assert rel_l2(got[n], whole[n]) <= PART_REL, n
+
+
+# ----------------------------------------------------------------------------- packed batches
+
+PACKED = [
+    # name, seq_lens, K, Hq, Hkv, D, retention, seed, bounds, assignment
+    ("three_short", (40, 25, 70), 4, 4, 2, 64, None, 400, None, 0),
+    ("five_mixed_one_segment_each", (100, 37, 64, 1, 90), 8, 4, 2, 64, None, 410, [0, 100, 137, 201, 202, 292], 0),
+    ("segments_across_sequences_sampled", (100, 37, 64, 1, 90), 8, 2, 1, 64, 0.8, 420, [0, 50, 120, 292], 1),
+    ("d128_two", (90, 60), 8, 2, 1, 128, None, 430, [0, 64, 150], 0),
+    ("k1_three", (130, 130, 130), 1, 2, 2, 64, None, 440, [0, 200, 390], 0),
+]
+
+
+@pytest.mark.parametrize("name,seq_lens,K,Hq,Hkv,D,ret,seed,bounds,assign", PACKED, ids=[c[0] for c in PACKED])
+def test_packed_batches_match_oracle(name, seq_lens, K, Hq, Hkv, D, ret, seed, bounds, assign):
+    """Variable-length batches packed before the expansion, one launch per kernel and segment for the whole
+    batch: against the oracle on the packed token list, and (dense case) against each sequence run alone."""
+    from gpu_harness import SampledRun
+    from peagle_inputs import cod_depth_counts
+    L = sum(seq_lens)
+    count = None if ret is None else cod_depth_counts(L, K, ret, seed)
+    tok = orc.packed_tokens(seq_lens, K, count)
+    T = len(tok[0])
+    print(f"case {name}: seq_lens={seq_lens} K={K} Hq={Hq} Hkv={Hkv} D={D} retention={ret} seed={seed} bounds={bounds} "
+          f"assignment={assign} tokens={T}", flush=True)
+    qb, kb, vb, dob = (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1), rand_bits((T, Hkv, D), seed + 2),
+                       rand_bits((T, Hq, D), seed + 3))
+    tm = pe.peagle_build_tilemap_packed(seq_lens, K, count, bounds, device=0, assignment=assign)
+    S = 1 if bounds is None else len(bounds) - 1
+    r = SampledRun(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+    r.step(0, S)
+    got = r.results()
+    q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    ref = orc.attn_backward(q, k, v, do, L, K, r.shape.scale, tokens=tok)
+    _check_against_oracle(got, ref, name)
+    if S > 1:
+        r1 = SampledRun(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        r1.fwd()
+        r1.bwd()
+        g1 = r1.results()
+        for n in ("O", "LSE", "dQ"):
+            assert np.array_equal(g1[n], got[n]), n
+        for n in ("dK", "dV"):
+            assert rel_l2(g1[n], got[n]) <= PART_REL, n
+    if ret is None:
+        base = 0
+        for Lq in seq_lens:
+            idx = np.concatenate([d * L + base + np.arange(Lq) for d in range(K)])
+            one_tm = pe.peagle_build_tilemap(Lq, K, None, device=0)
+            one = Run(one_tm, Lq, K, Hq, Hkv, D, qb[idx], kb[idx], vb[idx], dob[idx])
+            one.fwd()
+            one.bwd()
+            g = one.results()
+            for n in ("O", "dQ"):
+                assert rel_l2(got[n][idx], g[n]) <= 2e-3 or np.abs(got[n][idx] - g[n]).max() <= 1e-2, (n, Lq)
+            assert max_abs(got["LSE"][:, idx], g["LSE"]) <= 1e-5
+            for n in ("dK", "dV"):
+                assert rel_l2(got[n][idx], g[n]) <= PART_REL, (n, Lq)
+            base += Lq

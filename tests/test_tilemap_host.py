@@ -358,3 +358,58 @@ def test_algorithm1_assignment_matches_the_oracle_partition(L, K, r, seed, S):
         tok = {(int(a), int(d)): t for t, (a, d) in enumerate(zip(ta, td))}
         bits0 = np.unpackbits(tm.expand_rows(L, 0, 0, T), axis=1, bitorder="little")[:, :T].astype(bool)
         assert bits0[tok[(6, 2)]].any() and bits0[tok[(6, 1)]].any()  # anchor 6: positions 7 (depth 1) and 8 (depth 2)
+
+
+# ----------------------------------------------------------------------------- packed batches (host)
+
+@pytest.mark.parametrize("seq_lens,K,r,seed,bounds,assign", [
+    ((16,), 4, None, 0, None, 0),
+    ((5, 3, 8), 3, None, 1, None, 0),
+    ((100, 37, 64, 1, 90), 8, None, 2, None, 0),
+    ((100, 37, 64, 1, 90), 8, None, 2, [0, 100, 137, 201, 202, 292], 0),        # one segment per sequence
+    ((100, 37, 64, 1, 90), 8, 0.8, 3, [0, 50, 120, 292], 0),                      # segments cut across sequences
+    ((100, 37, 64, 1, 90), 8, 0.8, 3, [0, 50, 120, 292], 1),
+    ((70, 70, 70), 4, 0.5, 4, [0, 64, 128, 210], 1),
+    ((130,) * 3, 1, None, 5, [0, 200, 390], 0),
+    ((3, 2), 128, 0.95, 6, None, 0),
+])
+def test_packed_tilemap_expands_to_the_oracle_mask_bit_exactly(seq_lens, K, r, seed, bounds, assign):
+    from oracle import peagle_oracle as orc
+    from peagle_inputs import cod_depth_counts
+    L = sum(seq_lens)
+    count = None if r is None else cod_depth_counts(L, K, r, seed)
+    tm = pe.peagle_build_tilemap_packed(seq_lens, K, count, bounds, device=-1, assignment=assign)
+    tok = orc.packed_tokens(seq_lens, K, count)
+    T = len(tok[0])
+    assert tm.tokens(L) == T
+    ref = orc.element_mask(L, K, tokens=tok)
+    assert np.array_equal(_expand_all(tm, L), ref)
+    if bounds is not None:
+        seen = np.zeros(T, dtype=int)
+        for s in range(len(bounds) - 1):
+            bits = np.unpackbits(tm.expand_rows(L, s, 0, T), axis=1, bitorder="little")[:, :T].astype(bool)
+            rows = bits.any(axis=1)
+            assert np.array_equal(bits[rows], ref[rows])
+            seen += rows
+        assert (seen == 1).all()                                    # every row is computed in exactly one segment
+
+
+def test_packed_dense_single_sequence_equals_the_dense_map():
+    """One sequence, nothing dropped: the general builder must describe the same mask as the
+    position-invariant dense map (tile geometry may differ; the expansion may not)."""
+    L, K = 200, 8
+    a = pe.peagle_build_tilemap_packed((L,), K, None, None, device=-1)
+    b = pe.peagle_build_tilemap(L, K, None, device=-1)
+    assert np.array_equal(_expand_all(a, L), _expand_all(b, L))
+    assert a.info()["n_row_tiles"] == b.info()["n_row_tiles"]       # 16 anchors x 8 depths per tile either way
+
+
+def test_packed_build_rejects_bad_arguments():
+    lib = pe.load_library()
+    out = C.c_void_p()
+    i32 = C.c_int32
+    assert lib.peagle_build_tilemap_packed(None, 8, 2, (i32 * 3)(0, 5, 9), 2, None, 1, 0, -1, C.byref(out)) == -4   # ends before L
+    assert lib.peagle_build_tilemap_packed(None, 8, 2, (i32 * 3)(0, 5, 5), 2, None, 1, 0, -1, C.byref(out)) == -4   # empty sequence
+    assert lib.peagle_build_tilemap_packed(None, 8, 2, None, 2, None, 1, 0, -1, C.byref(out)) == -2
+    assert lib.peagle_build_tilemap_packed(None, 8, 2, (i32 * 3)(0, 5, 8), 0, None, 1, 0, -1, C.byref(out)) == -1
+    assert out.value is None
