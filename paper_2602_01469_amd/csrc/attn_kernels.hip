@@ -750,10 +750,17 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   // that does not see this wave's key tile; also set by the map for row tiles listed only for the
   // other tile of the pair), other ids <= -2 visible for keys with anchor >= -id - 2 (the row
   // tile's sequence starts inside the key tile).
-  auto fetch_row_tile = [&](int ei) { return fetch_entry(tm.key_entries, e_lo + ei); };
-  auto fetch_mask = [&](int ei) { return fetch_entry(tm.key_entries, ei >= my_skip ? my_lo + ei - my_skip : e_lo + ei); };
+  // The list is walked from its last row tile down: every key tile of a launch ends at the same
+  // row tile, so workgroups of one head that start together then read the same Q / dO rows at the
+  // same time (they share them in L2) whether their lists are long or short.
+  auto list_pos = [&](int ei) { return n_row_tiles - 1 - ei; };
+  auto fetch_row_tile = [&](int ei) { return fetch_entry(tm.key_entries, e_lo + list_pos(ei)); };
+  auto fetch_mask = [&](int ei) {
+    const int li = list_pos(ei);
+    return fetch_entry(tm.key_entries, li >= my_skip ? my_lo + li - my_skip : e_lo + li);
+  };
   constexpr int kSkip = INT_MIN;
-  auto mask_of = [&](int ei, const TileEntry& en) { return ei >= my_skip ? en.mask_id : kSkip; };
+  auto mask_of = [&](int ei, const TileEntry& en) { return list_pos(ei) >= my_skip ? en.mask_id : kSkip; };
   auto step = [&](int& ei, int& hh) {  // advance (ei, hh) by one iteration
     if (++ei == n_row_tiles) {
       ei = 0;
