@@ -230,6 +230,23 @@ int peagle_build_tilemap_packed(const int32_t* depth_count, int32_t L, int32_t K
                                 int32_t n_seq, const int32_t* seg_bounds, int32_t S, int32_t assignment,
                                 int32_t device, peagle_tilemap_t** out);
 
+/*
+ * Replaces the position set of a map made by peagle_build_tilemap_sampled / _packed, in place.
+ * Drop-token samples change with every training example (Sec. 3, PARD paragraph); this keeps the
+ * handle, its device allocation and its pinned staging buffer (they grow only when the new map
+ * needs more room), so a training loop allocates nothing per step.  K stays that of the map;
+ * the other arguments are those of peagle_build_tilemap_packed.
+ *
+ * The new map is copied to the device with one asynchronous copy on `stream` and is visible to
+ * work enqueued on that stream after this call; work already enqueued on it keeps reading the old
+ * map.  Work on other streams that still uses the map must have finished before the call.  The
+ * call blocks only to wait for the previous rebuild's copy (the staging buffer is reused).
+ * On error the map is unchanged if the arguments were rejected (EINVAL, ENULL, EBOUNDS,
+ * EUNSUPPORTED: a dense map cannot be rebuilt) and unusable after PEAGLE_EHIP.
+ */
+int peagle_tilemap_rebuild(peagle_tilemap_t* tm, const int32_t* depth_count, int32_t L, const int32_t* seq_start,
+                           int32_t n_seq, const int32_t* seg_bounds, int32_t S, int32_t assignment, void* stream);
+
 /* Stored tokens T of a length-L sequence under this map: L*K for a dense map, the kept positions
  * for a sampled one (which accepts only its own L).  -1 on a bad argument. */
 int64_t peagle_tilemap_tokens(const peagle_tilemap_t* tm, int32_t L);

@@ -35,7 +35,7 @@ EXPORTS = [
     "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
     "peagle_attn_step_partitioned", "peagle_build_tilemap_sampled", "peagle_build_tilemap_packed",
-    "peagle_tilemap_tokens",
+    "peagle_tilemap_rebuild", "peagle_tilemap_tokens",
     "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
@@ -86,6 +86,8 @@ def load_library():
     lib.peagle_build_tilemap_packed.argtypes = [C.POINTER(i32), i32, i32, C.POINTER(i32), i32, C.POINTER(i32), i32,
                                                 i32, i32, C.POINTER(vp)]
     lib.peagle_build_tilemap_packed.restype = C.c_int
+    lib.peagle_tilemap_rebuild.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(i32), i32, C.POINTER(i32), i32, i32, vp]
+    lib.peagle_tilemap_rebuild.restype = C.c_int
     lib.peagle_tilemap_tokens.argtypes = [vp, i32]
     lib.peagle_tilemap_tokens.restype = i64
     lib.peagle_attn_step_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -157,6 +159,25 @@ class TileMap:
         if T < 0:
             raise PeagleError(-3, "peagle_tilemap_tokens")
         return T
+
+    def rebuild(self, seq_lens: Sequence[int], depth_count: Optional[Sequence[int]] = None,
+                seg_bounds: Optional[Sequence[int]] = None, assignment: int = 0, stream=None) -> None:
+        """peagle_tilemap_rebuild: new position set for a sampled / packed map, in place."""
+        i32p = C.POINTER(C.c_int32)
+        start = np.ascontiguousarray(np.concatenate([[0], np.cumsum(seq_lens)]), dtype=np.int32)
+        L = int(start[-1])
+        n = None if depth_count is None else np.ascontiguousarray(depth_count, dtype=np.int32)
+        if n is not None and len(n) != L:
+            raise ValueError("depth_count must have one entry per anchor of the batch")
+        b = None if seg_bounds is None else np.ascontiguousarray(seg_bounds, dtype=np.int32)
+        sp = None
+        if self.info()["device_bytes"] > 0:
+            sp = _stream_ptr(stream)
+        rc = load_library().peagle_tilemap_rebuild(
+            self.handle, None if n is None else n.ctypes.data_as(i32p), L, start.ctypes.data_as(i32p), len(start) - 1,
+            None if b is None else b.ctypes.data_as(i32p), 1 if b is None else len(b) - 1, assignment, sp)
+        if rc != 0:
+            raise PeagleError(rc, "peagle_tilemap_rebuild")
 
     def expand_rows(self, L: int, seg: int, row_begin: int, row_end: int) -> np.ndarray:
         """Packed element-mask bits [row_end-row_begin, ceil(T/8)] (uint8, little bit order)."""

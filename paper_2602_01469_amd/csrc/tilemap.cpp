@@ -48,11 +48,9 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 namespace {
 
-// Second half of both builders: key tile -> row tile lists, per-segment offsets, device copy.
-// `key_count[t]` = entries that name key tile t.  Takes ownership of tm (deleted on failure).
-int finish_map(peagle_tilemap* tm, const std::vector<int32_t>& key_count, int32_t device, peagle_tilemap_t** out) {
+// Second half of both builders, host part: key tile -> row tile lists and per-segment offsets.
+void build_key_lists(peagle_tilemap* tm) {
   // key tile -> row tiles (ascending), same mask ids
-  (void)key_count;
   std::vector<std::vector<TileEntry>> lists(tm->n_key_tiles);
   for (int32_t R = 0; R < tm->n_row_tiles; ++R)
     for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1]; ++e) {
@@ -93,57 +91,109 @@ int finish_map(peagle_tilemap* tm, const std::vector<int32_t>& key_count, int32_
     }
   }
 
-  tm->device = device;
-  if (device >= 0) {
-    int prev = -1;
-    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) {
-      delete tm;
-      return PEAGLE_EHIP;
+}
+
+// Device copy of a finished map: all arrays packed into one blob, staged in pinned host memory and
+// sent with a single copy on `stream`.  The device allocation and the staging buffer are kept in
+// the handle and reused while they are large enough, so that rebuilding a map (a new sample every
+// training step) allocates nothing.  With wait = true the copy has completed on return.
+int upload_map(peagle_tilemap* tm, hipStream_t stream, bool wait) {
+  if (tm->device < 0) return PEAGLE_OK;
+  int prev = -1;
+  if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(tm->device) != hipSuccess) return PEAGLE_EHIP;
+  constexpr int kArrays = 10;
+  static const char kZeros[256] = {0};
+  const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
+                              tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
+                              tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
+                              sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t),
+                              tm->row_tok.size() * sizeof(int32_t), tm->chain_tok.size() * sizeof(int32_t)};
+  const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
+                              tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
+                              tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data()};
+  size_t off[kArrays], total = 0;
+  for (int i = 0; i < kArrays; ++i) {
+    off[i] = total;
+    total += align256(sz[i] ? sz[i] : 4);
+  }
+  hipError_t err = hipSuccess;
+  if (tm->copy_done) err = hipEventSynchronize((hipEvent_t)tm->copy_done);  // the staging buffer is free again
+  if (err == hipSuccess && total > (size_t)tm->dev_capacity) {
+    // grow with headroom; the old blob may still be read by kernels already enqueued: wait for them
+    const size_t cap = total + total / 4;
+    if (tm->dev_blob) {
+      err = hipDeviceSynchronize();
+      (void)hipFree(tm->dev_blob);
+      (void)hipHostFree(tm->staging);
+      tm->dev_blob = tm->staging = nullptr;
+      tm->dev_capacity = 0;
     }
-    constexpr int kArrays = 10;
-    static const char kZeros[256] = {0};
-    const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
-                                tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
-                                tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
-                                sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t),
-                                tm->row_tok.size() * sizeof(int32_t), tm->chain_tok.size() * sizeof(int32_t)};
-    const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
-                                tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
-                                tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data()};
-    size_t off[kArrays], total = 0;
-    for (int i = 0; i < kArrays; ++i) {
-      off[i] = total;
-      total += align256(sz[i] ? sz[i] : 4);
+    if (err == hipSuccess) err = hipMalloc(&tm->dev_blob, cap);
+    if (err == hipSuccess) err = hipHostMalloc(&tm->staging, cap, hipHostMallocDefault);
+    if (err == hipSuccess) tm->dev_capacity = (int64_t)cap;
+  }
+  if (err == hipSuccess && !tm->copy_done) {
+    hipEvent_t ev = nullptr;
+    err = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    tm->copy_done = ev;
+  }
+  if (err == hipSuccess) {
+    for (int i = 0; i < kArrays; ++i)
+      if (sz[i]) std::memcpy((char*)tm->staging + off[i], src[i], sz[i]);
+    err = hipMemcpyAsync(tm->dev_blob, tm->staging, total, hipMemcpyHostToDevice, stream);
+  }
+  if (err == hipSuccess) err = hipEventRecord((hipEvent_t)tm->copy_done, stream);
+  if (err == hipSuccess && wait) err = hipEventSynchronize((hipEvent_t)tm->copy_done);
+  (void)hipSetDevice(prev);
+  if (err != hipSuccess) return PEAGLE_EHIP;
+  tm->dev_bytes = (int64_t)total;
+  char* base = (char*)tm->dev_blob;
+  tm->dview.row_ptr = (const int32_t*)(base + off[0]);
+  tm->dview.row_entries = (const TileEntry*)(base + off[1]);
+  tm->dview.key_ptr = (const int32_t*)(base + off[2]);
+  tm->dview.key_entries = (const TileEntry*)(base + off[3]);
+  tm->dview.masks = (const uint32_t*)(base + off[4]);
+  tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
+  tm->dview.zeros = base + off[6];
+  tm->dview.row_lead = (const int32_t*)(base + off[7]);
+  tm->dview.row_tok = tm->row_tok.empty() ? nullptr : (const int32_t*)(base + off[8]);
+  tm->dview.chain_tok = tm->chain_tok.empty() ? nullptr : (const int32_t*)(base + off[9]);
+  tm->dview.A = tm->A;
+  tm->dview.K = tm->K;
+  tm->dview.S = tm->S;
+  tm->dview.n_row_tiles = tm->n_row_tiles;
+  tm->dview.n_d0 = tm->n_d0;
+  tm->dview.n_csub = tm->n_csub;
+  tm->dview.n_key_tiles = tm->n_key_tiles;
+  return PEAGLE_OK;
+}
+
+void release_device(peagle_tilemap* tm) {
+  if (tm->device < 0 || (!tm->dev_blob && !tm->staging && !tm->copy_done)) return;
+  int prev = -1;
+  if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(tm->device) == hipSuccess) {
+    if (tm->copy_done) {
+      (void)hipEventSynchronize((hipEvent_t)tm->copy_done);
+      (void)hipEventDestroy((hipEvent_t)tm->copy_done);
     }
-    hipError_t err = hipMalloc(&tm->dev_blob, total);
-    for (int i = 0; i < kArrays && err == hipSuccess; ++i)
-      if (sz[i]) err = hipMemcpy((char*)tm->dev_blob + off[i], src[i], sz[i], hipMemcpyHostToDevice);
-    if (err == hipSuccess) err = hipDeviceSynchronize();
+    if (tm->dev_blob) (void)hipFree(tm->dev_blob);
+    if (tm->staging) (void)hipHostFree(tm->staging);
     (void)hipSetDevice(prev);
-    if (err != hipSuccess) {
-      if (tm->dev_blob) (void)hipFree(tm->dev_blob);
-      delete tm;
-      return PEAGLE_EHIP;
-    }
-    tm->dev_bytes = (int64_t)total;
-    char* base = (char*)tm->dev_blob;
-    tm->dview.row_ptr = (const int32_t*)(base + off[0]);
-    tm->dview.row_entries = (const TileEntry*)(base + off[1]);
-    tm->dview.key_ptr = (const int32_t*)(base + off[2]);
-    tm->dview.key_entries = (const TileEntry*)(base + off[3]);
-    tm->dview.masks = (const uint32_t*)(base + off[4]);
-    tm->dview.key_seg_ptr = (const int32_t*)(base + off[5]);
-    tm->dview.zeros = base + off[6];
-    tm->dview.row_lead = (const int32_t*)(base + off[7]);
-    tm->dview.row_tok = tm->row_tok.empty() ? nullptr : (const int32_t*)(base + off[8]);
-    tm->dview.chain_tok = tm->chain_tok.empty() ? nullptr : (const int32_t*)(base + off[9]);
-    tm->dview.A = tm->A;
-    tm->dview.K = tm->K;
-    tm->dview.S = tm->S;
-    tm->dview.n_row_tiles = tm->n_row_tiles;
-    tm->dview.n_d0 = tm->n_d0;
-    tm->dview.n_csub = tm->n_csub;
-    tm->dview.n_key_tiles = tm->n_key_tiles;
+  }
+  tm->dev_blob = tm->staging = nullptr;
+  tm->copy_done = nullptr;
+  tm->dev_capacity = 0;
+}
+
+// Common tail of the builders.  Takes ownership of tm (released on failure).
+int finish_map(peagle_tilemap* tm, int32_t device, peagle_tilemap_t** out) {
+  build_key_lists(tm);
+  tm->device = device;
+  const int rc = upload_map(tm, nullptr, true);
+  if (rc != PEAGLE_OK) {
+    release_device(tm);
+    delete tm;
+    return rc;
   }
   *out = tm;
   return PEAGLE_OK;
@@ -198,7 +248,6 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
   const int rows_used = A * K;
 
   tm->row_ptr.assign(tm->n_row_tiles + 1, 0);
-  std::vector<int32_t> key_count(tm->n_key_tiles, 0);
   for (int32_t R = 0; R < tm->n_row_tiles; ++R) {
     const int64_t i0 = (int64_t)R * A;        // first anchor of the row tile
     const int64_t i1 = i0 + A - 1;            // last anchor (position-invariant: not clipped to L_max)
@@ -221,7 +270,6 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
         ++tm->n_partial;
       }
       tm->row_entries.push_back(en);
-      ++key_count[c];
     }
     // chain stream: key kk of the stream is depth 1 + kk/A, anchor i0 + kk%A
     for (int32_t s = 0; s < tm->n_csub; ++s) {
@@ -243,7 +291,6 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
       const int32_t kt = tm->n_d0 + R * tm->n_csub + s;
       tm->row_entries.push_back(TileEntry{kt, pool.intern(bits)});
       ++tm->n_partial;
-      ++key_count[kt];
     }
     tm->row_ptr[R + 1] = (int32_t)tm->row_entries.size();
     int32_t lead = 0;
@@ -254,18 +301,12 @@ extern "C" int peagle_build_tilemap(int32_t L_max, int32_t K, const int32_t* seg
   tm->seg_rt.resize(S + 1);
   for (int32_t sg = 0; sg <= S; ++sg) tm->seg_rt[sg] = sg == S ? tm->n_row_tiles : b[sg] / A;
   tm->T_tokens = (int64_t)L_max * K;
-  return finish_map(tm, key_count, device, out);
+  return finish_map(tm, device, out);
 }
 
 extern "C" void peagle_tilemap_destroy(peagle_tilemap_t* tm) {
   if (!tm) return;
-  if (tm->dev_blob) {
-    int prev = -1;
-    if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(tm->device) == hipSuccess) {
-      (void)hipFree(tm->dev_blob);
-      (void)hipSetDevice(prev);
-    }
-  }
+  release_device(tm);
   delete tm;
 }
 
@@ -283,14 +324,13 @@ extern "C" int peagle_build_tilemap_sampled(const int32_t* depth_count, int32_t 
   return peagle_build_tilemap_packed(depth_count, L, K, nullptr, 1, seg_bounds, S, assignment, device, out);
 }
 
-// General builder: explicit position set (depth_count, or every depth if null) of a batch of
-// sequences packed before the expansion (seq_start, or one sequence if null).
-extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_t L, int32_t K,
-                                           const int32_t* seq_start_in, int32_t n_seq, const int32_t* seg_bounds,
-                                           int32_t S, int32_t assignment, int32_t device, peagle_tilemap_t** out) {
-  if (!out) return PEAGLE_ENULL;
-  *out = nullptr;
-  if (L < 1 || S < 1 || K < 1 || n_seq < 1 || device < -1) return PEAGLE_EINVAL;
+namespace {
+
+// Fills the host arrays of `tm` (any previous content is dropped) for the given position set; the
+// device side is untouched.  Every argument is checked before tm is modified.
+int fill_packed(peagle_tilemap* tm, const int32_t* depth_count_in, int32_t L, int32_t K, const int32_t* seq_start_in,
+                int32_t n_seq, const int32_t* seg_bounds, int32_t S, int32_t assignment) {
+  if (L < 1 || S < 1 || K < 1 || n_seq < 1) return PEAGLE_EINVAL;
   if (assignment != PEAGLE_ASSIGN_BY_ANCHOR && assignment != PEAGLE_ASSIGN_ALGORITHM1) return PEAGLE_EINVAL;
   if (K > kRowsPerTile) return PEAGLE_EUNSUPPORTED;
   if ((int64_t)L * K > (int64_t)1 << 30) return PEAGLE_EUNSUPPORTED;
@@ -309,6 +349,14 @@ extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_
     for (int q = 0; q < n_seq && ok; ++q) ok = seq_start[q] < seq_start[q + 1];
     if (!ok) return PEAGLE_EBOUNDS;
   }
+  std::vector<int32_t> b;
+  if (seg_bounds) b.assign(seg_bounds, seg_bounds + S + 1);
+  else b = {0, L};
+  {
+    bool ok = b[0] == 0 && b[S] == L;
+    for (int s = 0; s < S && ok; ++s) ok = b[s] < b[s + 1];
+    if (!ok) return PEAGLE_EBOUNDS;
+  }
   // first and one-past-last anchor of the sequence every anchor belongs to
   std::vector<int32_t> seq_lo(L), seq_hi(L);
   for (int32_t q = 0; q < n_seq; ++q)
@@ -317,22 +365,18 @@ extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_
       seq_hi[i] = seq_start[q + 1];
     }
 
-  peagle_tilemap* tm = new (std::nothrow) peagle_tilemap();
-  if (!tm) return PEAGLE_EINVAL;
   tm->L_max = L;
   tm->K = K;
   tm->S = S;
   tm->A = 0;  // anchors per row tile vary
   tm->sampled = 1;
-  if (seg_bounds) tm->seg_bounds.assign(seg_bounds, seg_bounds + S + 1);
-  else tm->seg_bounds = {0, L};
-  const std::vector<int32_t>& b = tm->seg_bounds;
-  bool ok = b[0] == 0 && b[S] == L;
-  for (int s = 0; s < S && ok; ++s) ok = b[s] < b[s + 1];
-  if (!ok) {
-    delete tm;
-    return PEAGLE_EBOUNDS;
-  }
+  tm->seg_bounds = b;
+  tm->n_full = tm->n_partial = 0;
+  tm->n_masks = 0;
+  tm->row_entries.clear();
+  tm->row_lead.clear();
+  tm->masks.clear();
+  tm->key_side_id.clear();
 
   // token of (depth, anchor): depth-major storage, kept anchors ascending
   std::vector<int32_t> tok_of((size_t)L * K, -1);
@@ -408,7 +452,6 @@ extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_
   tm->row_ptr.assign(tm->n_row_tiles + 1, 0);
   tm->row_tok.assign((size_t)tm->n_row_tiles * kRowsPerTile, -1);
   tm->chain_tok.assign((size_t)tm->n_row_tiles * tm->n_csub * kKeysPerTile, -1);
-  std::vector<int32_t> key_count(tm->n_key_tiles, 0);
   std::vector<int32_t> row_a(kRowsPerTile), row_d(kRowsPerTile), key_a, key_e;
   for (int32_t R = 0; R < tm->n_row_tiles; ++R) {
     const int32_t a0 = tile_a0[R], a1 = tile_a1[R];
@@ -440,7 +483,6 @@ extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_
     for (int32_t c = sb / kKeysPerTile; c < tm->n_d0; ++c) {
       const int64_t j0 = (int64_t)c * kKeysPerTile, j1 = j0 + kKeysPerTile - 1;
       if (j0 > a1 - 1) break;
-      ++key_count[c];
       if (j0 >= sb && j1 <= a0) {
         ++tm->n_full;
         tm->row_entries.push_back(TileEntry{c, -1});
@@ -483,14 +525,44 @@ extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count_in, int32_
       tm->row_entries.push_back(TileEntry{kt, append_mask(bits)});
       tm->key_side_id.push_back(tm->row_entries.back().mask_id);
       ++tm->n_partial;
-      ++key_count[kt];
     }
     tm->row_ptr[R + 1] = (int32_t)tm->row_entries.size();
     int32_t lead = 0;
     for (int32_t e = tm->row_ptr[R]; e < tm->row_ptr[R + 1] && tm->row_entries[e].mask_id < 0; ++e) ++lead;
     tm->row_lead.push_back(lead);
   }
-  return finish_map(tm, key_count, device, out);
+  return PEAGLE_OK;
+}
+
+}  // namespace
+
+// General builder: explicit position set (depth_count, or every depth if null) of a batch of
+// sequences packed before the expansion (seq_start, or one sequence if null).
+extern "C" int peagle_build_tilemap_packed(const int32_t* depth_count, int32_t L, int32_t K, const int32_t* seq_start,
+                                           int32_t n_seq, const int32_t* seg_bounds, int32_t S, int32_t assignment,
+                                           int32_t device, peagle_tilemap_t** out) {
+  if (!out) return PEAGLE_ENULL;
+  *out = nullptr;
+  if (device < -1) return PEAGLE_EINVAL;
+  peagle_tilemap* tm = new (std::nothrow) peagle_tilemap();
+  if (!tm) return PEAGLE_EINVAL;
+  const int rc = fill_packed(tm, depth_count, L, K, seq_start, n_seq, seg_bounds, S, assignment);
+  if (rc != PEAGLE_OK) {
+    delete tm;
+    return rc;
+  }
+  return finish_map(tm, device, out);
+}
+
+extern "C" int peagle_tilemap_rebuild(peagle_tilemap_t* tm, const int32_t* depth_count, int32_t L,
+                                      const int32_t* seq_start, int32_t n_seq, const int32_t* seg_bounds, int32_t S,
+                                      int32_t assignment, void* stream) {
+  if (!tm) return PEAGLE_ENULL;
+  if (!tm->sampled) return PEAGLE_EUNSUPPORTED;  // the dense map is position-invariant: nothing to rebuild
+  const int rc = fill_packed(tm, depth_count, L, tm->K, seq_start, n_seq, seg_bounds, S, assignment);
+  if (rc != PEAGLE_OK) return rc;
+  build_key_lists(tm);
+  return upload_map(tm, (hipStream_t)stream, false);
 }
 
 extern "C" int64_t peagle_tilemap_tokens(const peagle_tilemap_t* tm, int32_t L) {

@@ -62,7 +62,10 @@ struct peagle_tilemap {
   int32_t n_masks = 0;
   int32_t device = -1;
   void* dev_blob = nullptr;                      // one allocation holding all device arrays
-  int64_t dev_bytes = 0;
+  void* staging = nullptr;                       // pinned host image of the blob (source of the upload copy)
+  void* copy_done = nullptr;                     // hipEvent_t recorded after the last upload copy
+  int64_t dev_capacity = 0;                      // bytes allocated for dev_blob and staging
+  int64_t dev_bytes = 0;                         // bytes in use
   peagle::DeviceTileMap dview{};
 };
 

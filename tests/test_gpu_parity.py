@@ -541,3 +541,33 @@ def test_packed_batches_match_oracle(name, seq_lens, K, Hq, Hkv, D, ret, seed, b
             for n in ("dK", "dV"):
                 assert rel_l2(got[n][idx], g[n]) <= PART_REL, (n, Lq)
             base += Lq
+
+
+def test_rebuilding_a_sampled_map_in_place_between_steps():
+    """A new drop-token sample every step on one handle: the rebuilt map (asynchronous upload on the launch
+    stream) must give exactly what a freshly built map gives, while the step before it keeps its results."""
+    from gpu_harness import SampledRun
+    from peagle_inputs import cod_depth_counts
+    L, K, Hq, Hkv, D = 600, 8, 4, 2, 64
+    bounds = [0, 256, 600]
+    tm = pe.peagle_build_tilemap_sampled(cod_depth_counts(L, K, 0.8, 1), K, bounds, device=0)
+    for step, (r, seed, Ls) in enumerate([(0.8, 2, L), (0.5, 3, L), (0.9, 4, 900), (0.7, 5, 300)]):
+        count = cod_depth_counts(Ls, K, r, seed)
+        b = [0, Ls // 2, Ls]
+        print(f"step {step}: L={Ls} retention={r} kept={int(count.sum())}", flush=True)
+        tm.rebuild((Ls,), count, b)
+        T = tm.tokens(Ls)
+        qb, kb, vb, dob = (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1),
+                           rand_bits((T, Hkv, D), seed + 2), rand_bits((T, Hq, D), seed + 3))
+        run = SampledRun(tm, Ls, K, Hq, Hkv, D, qb, kb, vb, dob)
+        run.step(0, 2)
+        got = run.results()
+        fresh = pe.peagle_build_tilemap_sampled(count, K, b, device=0)
+        ref_run = SampledRun(fresh, Ls, K, Hq, Hkv, D, qb, kb, vb, dob)
+        ref_run.step(0, 2)
+        ref = ref_run.results()
+        for n in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.array_equal(got[n], ref[n]), (step, n)
+    ta, td = orc.cod_tokens(count)
+    q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    _check_against_oracle(got, orc.attn_backward(q, k, v, do, Ls, K, run.shape.scale, tokens=(ta, td)), "after rebuilds")

@@ -413,3 +413,45 @@ def test_packed_build_rejects_bad_arguments():
     assert lib.peagle_build_tilemap_packed(None, 8, 2, None, 2, None, 1, 0, -1, C.byref(out)) == -2
     assert lib.peagle_build_tilemap_packed(None, 8, 2, (i32 * 3)(0, 5, 8), 0, None, 1, 0, -1, C.byref(out)) == -1
     assert out.value is None
+
+
+# ----------------------------------------------------------------------------- rebuilding a map in place (host)
+
+def test_rebuild_in_place_gives_the_same_map_as_a_fresh_build():
+    from oracle import peagle_oracle as orc
+    from peagle_inputs import cod_depth_counts
+    K = 8
+    tm = pe.peagle_build_tilemap_sampled(cod_depth_counts(300, K, 0.8, 1), K, [0, 100, 300], device=-1)
+    cases = [((500,), 0.8, 2, [0, 250, 500], 0), ((40,), 0.5, 3, None, 1), ((100, 37, 64), 0.9, 4, [0, 90, 201], 1),
+             ((300,), None, 5, None, 0)]
+    for seq_lens, r, seed, bounds, assign in cases:
+        L = sum(seq_lens)
+        count = None if r is None else cod_depth_counts(L, K, r, seed)
+        tm.rebuild(seq_lens, count, bounds, assign)
+        fresh = pe.peagle_build_tilemap_packed(seq_lens, K, count, bounds, device=-1, assignment=assign)
+        a, b = tm.info(), fresh.info()
+        assert {k: a[k] for k in a if k != "device_bytes"} == {k: b[k] for k in b if k != "device_bytes"}
+        tok = orc.packed_tokens(seq_lens, K, count)
+        assert np.array_equal(_expand_all(tm, L), orc.element_mask(L, K, tokens=tok))
+        S = 1 if bounds is None else len(bounds) - 1
+        T = tm.tokens(L)
+        for s in range(S):
+            assert np.array_equal(tm.expand_rows(L, s, 0, T), fresh.expand_rows(L, s, 0, T))
+
+
+def test_rebuild_rejects_bad_arguments_and_keeps_the_map():
+    from peagle_inputs import cod_depth_counts
+    lib = pe.load_library()
+    K, L = 4, 64
+    count = cod_depth_counts(L, K, 0.7, 9)
+    tm = pe.peagle_build_tilemap_sampled(count, K, None, device=-1)
+    before = _expand_all(tm, L)
+    i32 = C.c_int32
+    bad = (i32 * L)(*([5] * L))                                          # counts above K
+    assert lib.peagle_tilemap_rebuild(tm.handle, bad, L, None, 1, None, 1, 0, None) == -1
+    assert lib.peagle_tilemap_rebuild(tm.handle, None, L, None, 2, None, 1, 0, None) == -2
+    assert lib.peagle_tilemap_rebuild(tm.handle, None, L, None, 1, (i32 * 3)(0, 70, 64), 2, 0, None) == -4
+    assert lib.peagle_tilemap_rebuild(None, None, L, None, 1, None, 1, 0, None) == -2
+    assert np.array_equal(_expand_all(tm, L), before)
+    dense = pe.peagle_build_tilemap(L, K, None, device=-1)
+    assert lib.peagle_tilemap_rebuild(dense.handle, None, L, None, 1, None, 1, 0, None) == -5
