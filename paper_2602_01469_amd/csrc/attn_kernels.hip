@@ -659,11 +659,25 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     // Workgroups are dealt round-robin to the XCDs, so b % Hkv pins a KV head to an XCD's L2;
     // within it the key-tile pairs of one query head are adjacent, so the workgroups that are
     // resident together stream the same head's Q / dO rows and share them in L2.
+    // The pairs are dealt in two passes over the heads, [0, d0_split) first: the key tiles inside a
+    // segment have lists that shrink with the pair index, and starting all long lists before any
+    // short one lets the short ones fill the slots that free up (the launcher sets d0_split to the
+    // pair count - one pass - when all lists are equally long).
     const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
     kvh = b % p.Hkv;
     b /= p.Hkv;
-    kt0 = p.d0_tile_lo + 2 * (b % n_pairs);
-    h_lo = kvh * group + b / n_pairs;
+    int pair, head;
+    if (b < p.d0_split * group) {
+      pair = b % p.d0_split;
+      head = b / p.d0_split;
+    } else {
+      b -= p.d0_split * group;
+      const int rest = n_pairs - p.d0_split;
+      pair = p.d0_split + b % rest;
+      head = b / rest;
+    }
+    kt0 = p.d0_tile_lo + 2 * pair;
+    h_lo = kvh * group + head;
     h_hi = h_lo + 1;
     n_tiles = kt0 + 1 < p.n_d0_tiles ? 2 : 1;
   } else {
@@ -1066,6 +1080,13 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
   p.n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi ...
   p.d0_tile_lo = key_lo / kKeysPerTile & ~1;                // ... from the (even) tile pair of the first visible key on
   p.n_d0_items = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2 * p.Hq;  // key-tile pairs x query heads
+  {
+    // pairs wholly below the segment's first anchor see every row tile (equal lists); the others shrink
+    const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
+    const int equal = acc_below == INT_MAX ? 0 : (acc_below / kKeysPerTile - p.d0_tile_lo) / 2;
+    const int shrinking = n_pairs - (equal > 0 ? equal : 0);
+    p.d0_split = shrinking >= 8 ? n_pairs - shrinking / 2 : n_pairs;
+  }
   const int n_chain_items = n_rt * ((p.tm.n_csub + 1) / 2) * p.Hkv;
   {
     const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
