@@ -659,23 +659,22 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     // Workgroups are dealt round-robin to the XCDs, so b % Hkv pins a KV head to an XCD's L2;
     // within it the key-tile pairs of one query head are adjacent, so the workgroups that are
     // resident together stream the same head's Q / dO rows and share them in L2.
-    // The pairs are dealt in two passes over the heads, [0, d0_split) first: the key tiles inside a
-    // segment have lists that shrink with the pair index, and starting all long lists before any
-    // short one lets the short ones fill the slots that free up (the launcher sets d0_split to the
-    // pair count - one pass - when all lists are equally long).
+    // The pairs are dealt in passes over the heads: pass 0 takes the pairs [0, d0_split), each later
+    // pass the next d0_step pairs.  The key tiles inside a segment have lists that shrink with the
+    // pair index, and starting the long lists of every head before the short ones lets the short
+    // ones fill the slots that free up (one pass - d0_split = pair count - when all lists are
+    // equally long).
     const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
     kvh = b % p.Hkv;
     b /= p.Hkv;
-    int pair, head;
-    if (b < p.d0_split * group) {
-      pair = b % p.d0_split;
-      head = b / p.d0_split;
-    } else {
-      b -= p.d0_split * group;
-      const int rest = n_pairs - p.d0_split;
-      pair = p.d0_split + b % rest;
-      head = b / rest;
+    int first = 0, count = p.d0_split;
+    while (b >= count * group) {  // at most a few passes
+      b -= count * group;
+      first += count;
+      count = n_pairs - first < p.d0_step ? n_pairs - first : p.d0_step;
     }
+    const int pair = first + b % count;
+    const int head = b / count;
     kt0 = p.d0_tile_lo + 2 * pair;
     h_lo = kvh * group + head;
     h_hi = h_lo + 1;
@@ -1085,7 +1084,11 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
     const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
     const int equal = acc_below == INT_MAX ? 0 : (acc_below / kKeysPerTile - p.d0_tile_lo) / 2;
     const int shrinking = n_pairs - (equal > 0 ? equal : 0);
-    p.d0_split = shrinking >= 8 ? n_pairs - shrinking / 2 : n_pairs;
+    constexpr int kPasses = 4;
+    p.d0_step = (shrinking + kPasses - 1) / kPasses;
+    if (p.d0_step < 2) p.d0_step = 2;
+    p.d0_split = n_pairs - shrinking + p.d0_step;
+    if (p.d0_split > n_pairs) p.d0_split = n_pairs;
   }
   const int n_chain_items = n_rt * ((p.tm.n_csub + 1) / 2) * p.Hkv;
   {
