@@ -571,3 +571,42 @@ def test_rebuilding_a_sampled_map_in_place_between_steps():
     ta, td = orc.cod_tokens(count)
     q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
     _check_against_oracle(got, orc.attn_backward(q, k, v, do, Ls, K, run.shape.scale, tokens=(ta, td)), "after rebuilds")
+
+
+def test_random_small_problems_match_oracle():
+    """Seeded sweep over batches, depths, head shapes, retention rates, segmentations and assignments:
+    the partitioned step on the general tile map against the oracle, every output."""
+    from gpu_harness import SampledRun
+    from peagle_inputs import cod_depth_counts
+    rng = np.random.default_rng(77)
+    for case in range(10):
+        K = int(rng.choice([1, 2, 4, 5, 8, 16]))
+        n_seq = int(rng.integers(1, 4))
+        seq_lens = tuple(int(x) for x in rng.integers(1, 120, size=n_seq))
+        L = sum(seq_lens)
+        D = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2]))
+        Hq = Hkv * int(rng.choice([1, 2, 3]))
+        r = float(rng.choice([0.5, 0.8, 1.0]))
+        count = None if rng.random() < 0.3 else cod_depth_counts(L, K, r, int(rng.integers(1 << 30)))
+        S = int(rng.integers(1, 4))
+        bounds = None
+        if S > 1 and L > S:
+            cuts = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False))
+            bounds = [0] + [int(c) for c in cuts] + [L]
+        S = 1 if bounds is None else len(bounds) - 1
+        assign = int(rng.integers(0, 2))
+        tok = orc.packed_tokens(seq_lens, K, count)
+        T = len(tok[0])
+        what = (f"case {case}: seq_lens={seq_lens} K={K} Hq={Hq} Hkv={Hkv} D={D} sampled={count is not None} r={r} "
+                f"bounds={bounds} assign={assign} tokens={T}")
+        print(what, flush=True)
+        seed = 1000 + 10 * case
+        qb, kb, vb, dob = (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1),
+                           rand_bits((T, Hkv, D), seed + 2), rand_bits((T, Hq, D), seed + 3))
+        tm = pe.peagle_build_tilemap_packed(seq_lens, K, count, bounds, device=0, assignment=assign)
+        run = SampledRun(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        run.step(0, S)
+        got = run.results()
+        q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+        _check_against_oracle(got, orc.attn_backward(q, k, v, do, L, K, run.shape.scale, tokens=tok), what)

@@ -455,3 +455,42 @@ def test_rebuild_rejects_bad_arguments_and_keeps_the_map():
     assert np.array_equal(_expand_all(tm, L), before)
     dense = pe.peagle_build_tilemap(L, K, None, device=-1)
     assert lib.peagle_tilemap_rebuild(dense.handle, None, L, None, 1, None, 1, 0, None) == -5
+
+
+def test_random_position_sets_expand_to_the_oracle_mask():
+    """Seeded sweep over batches, depths, retention rates, segmentations and both assignments: the general
+    builder against the oracle's element mask, bit for bit, and every row in exactly one segment."""
+    from oracle import peagle_oracle as orc
+    from peagle_inputs import cod_depth_counts
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        K = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 33]))
+        n_seq = int(rng.integers(1, 5))
+        seq_lens = tuple(int(x) for x in rng.integers(1, 150, size=n_seq))
+        L = sum(seq_lens)
+        r = float(rng.choice([0.0, 0.3, 0.6, 0.8, 0.95, 1.0]))
+        count = None if rng.random() < 0.25 else cod_depth_counts(L, K, r, int(rng.integers(1 << 30)))
+        S = int(rng.integers(1, 5))
+        bounds = None
+        if S > 1 and L > S:
+            cuts = np.sort(rng.choice(np.arange(1, L), size=S - 1, replace=False))
+            bounds = [0] + [int(c) for c in cuts] + [L]
+        assign = int(rng.integers(0, 2))
+        what = f"case {case}: seq_lens={seq_lens} K={K} r={r} sampled={count is not None} bounds={bounds} assign={assign}"
+        tm = pe.peagle_build_tilemap_packed(seq_lens, K, count, bounds, device=-1, assignment=assign)
+        tok = orc.packed_tokens(seq_lens, K, count)
+        T = len(tok[0])
+        ref = orc.element_mask(L, K, tokens=tok)
+        assert tm.tokens(L) == T, what
+        assert np.array_equal(_expand_all(tm, L), ref), what
+        if bounds is not None:
+            seen = np.zeros(T, dtype=int)
+            for s in range(len(bounds) - 1):
+                bits = np.unpackbits(tm.expand_rows(L, s, 0, T), axis=1, bitorder="little")[:, :T].astype(bool)
+                rows = bits.any(axis=1)
+                assert np.array_equal(bits[rows], ref[rows]), what
+                seen += rows
+            assert (seen == 1).all(), what
+        cls = tm.classes()
+        inf = tm.info()
+        assert (cls == 1).sum() == inf["n_full"] and (cls == 2).sum() == inf["n_partial"], what
