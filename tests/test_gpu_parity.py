@@ -610,3 +610,40 @@ def test_random_small_problems_match_oracle():
         got = run.results()
         q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
         _check_against_oracle(got, orc.attn_backward(q, k, v, do, L, K, run.shape.scale, tokens=tok), what)
+
+
+def test_partitioned_step_replays_from_a_hip_graph():
+    """The step allocates nothing and synchronises nothing, so a caller may capture it: every replay, with
+    eager work and synchronisations in between, must reproduce the eager results bit for bit."""
+    L, K, Hq, Hkv, D = 300, 8, 4, 2, 64
+    bounds = [0, 128, 300]
+    T = L * K
+    qb, kb, vb, dob = (rand_bits((T, Hq, D), 500), rand_bits((T, Hkv, D), 501), rand_bits((T, Hkv, D), 502),
+                       rand_bits((T, Hq, D), 503))
+    tm = pe.peagle_build_tilemap(L, K, bounds, device=0)
+    eager = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+    eager.step(0, 2)
+    want = eager.results()
+    r = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r.step(0, 2)                                    # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        r.step(0, 2)
+    for replay in range(4):
+        for t in (r.o, r.dq):
+            t.fill_(float("nan"))
+        r.lse.fill_(float("nan"))
+        r.dk.fill_(float("nan"))
+        r.dv.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = r.results()
+        for n in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.array_equal(got[n], want[n]), (replay, n)
+        eager.step(0, 2)                                # the program's own eager work between replays
+        torch.cuda.synchronize()
