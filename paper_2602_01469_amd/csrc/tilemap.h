@@ -1,7 +1,8 @@
 // Internal representation of the tile map (host side) and the device view handed to kernels.
 //
-// Geometry (see include/peagle.h): a row tile is A = 128/K anchors at all K depths; key tiles are
-// 64 wide and come from two streams (depth-0 anchors, and the chain positions of a row tile's own
+// Geometry (see include/peagle.h): a row tile is A = 128/K anchors at all K depths (dense map) or a
+// run of anchors whose kept positions fill 128 rows (sampled / packed maps); key tiles are 64 wide
+// and come from two streams (depth-0 anchors, and the chain positions of a row tile's own
 // anchors).  The classification follows the parallel-prediction mask of Sec. 3 of the paper.
 #pragma once
 
@@ -19,7 +20,9 @@ constexpr int kMaskWords = kRowsPerTile * kMaskWordsPerRow;           // 256 x u
 
 struct TileEntry {
   int32_t tile;     // key-tile id in the row-tile lists, row-tile id in the key-tile lists
-  int32_t mask_id;  // -1: every element of the pair is visible; else index into the mask pool
+  int32_t mask_id;  // -1: every element of the pair is visible; >= 0: index into the mask pool.  Key-tile lists
+                    // of packed maps also use INT32_MIN (listed for the pair's other tile only: nothing to do)
+                    // and -2 - a (visible for keys with anchor >= a: the row tile's sequence starts at a)
 };
 
 // Pointers into device memory; passed to kernels by value.
