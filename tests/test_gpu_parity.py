@@ -75,6 +75,9 @@ SMALL = [
     ("d128_one_head", 96, 8, 1, 1, 128, 210, None, None),
     ("d128_segments_cropped", 200, 8, 2, 1, 128, 220, [0, 64, 128, 256], 256),
     ("several_tiles", 700, 4, 4, 2, 64, 230, [0, 256, 512, 700], None),
+    ("group_of_12", 150, 8, 12, 1, 64, 240, [0, 64, 150], None),
+    ("seven_mha_heads", 90, 4, 7, 7, 64, 250, None, None),
+    ("odd_group_d128", 70, 8, 9, 3, 128, 260, None, None),
 ]
 
 
