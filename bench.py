@@ -354,6 +354,28 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
 
+    # the same steps once more with an event pair around each (median and minimum), and the
+    # unpartitioned pass over the same inputs (what within-sequence partitioning costs)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.steps, 1))]
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+
+    def whole():
+        pe.peagle_attn_fwd(tm, shape, -1, q, k, v, o, lse, stream)
+        pe.peagle_attn_bwd(tm, shape, -1, q, k, v, o, do, lse, dq, dk, dv, 0, ws, stream)
+    for _ in range(2):
+        whole()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(max(args.steps // 2, 1)):
+        whole()
+    torch.cuda.synchronize()
+    ms_whole = (time.perf_counter() - t0) * 1e3 / max(args.steps // 2, 1)
+
     # per-kernel launch durations: HIP events on the launch stream, same workload, same launches
     prof_reps = 5
     acc = {}
@@ -393,6 +415,10 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_median": per_step[len(per_step) // 2],
+        "ms_per_step_min": per_step[0],
+        "unpartitioned_ms_per_step": ms_whole,
+        "partition_overhead": ms_per_step / ms_whole,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

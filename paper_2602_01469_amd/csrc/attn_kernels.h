@@ -42,6 +42,7 @@ struct BwdParams {
   int n_d0_items;       // filled by the launcher: depth-0 work items (key-tile pairs x query heads)
   int n_d0_tiles;       // filled by the launcher: depth-0 key tiles visible to the segment are [d0_tile_lo, n_d0_tiles)
   int d0_tile_lo;
+  int clip_rows;        // filled by the launcher: [rt_lo, rt_hi) covers only part of the segments s_lo..s_hi
   int d0_split, d0_step;  // filled by the launcher: depth-0 pairs are dealt in passes, [0, d0_split) then d0_step at a time
   int chain_accumulate; // chain keys: add to dk_acc/dv_acc instead of overwriting
   float c_log2, scale;

@@ -695,18 +695,20 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   const bool tile_present = my_tile < n_tiles;
 
   // row tiles that see a key tile, clipped to [rt_lo, rt_hi): the map stores where each segment
-  // starts inside a key tile's (ascending) list; only a cropped range needs a search for its end
+  // starts inside a key tile's (ascending) list.  A launch that covers only part of its segments
+  // (a cropped length, or one chunk of a long segment; dense maps only) cuts the range further by
+  // position: the row tiles in a dense map's list are consecutive.
   auto clip = [&](int t, int& lo_out, int& hi_out) {
     const int32_t* sp = tm.key_seg_ptr + (size_t)t * (tm.S + 1);
     int lo = sp[p.s_lo], hi = sp[p.s_hi];
-    lo_out = lo;
-    if (p.cropped) {
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (tm.key_entries[mid].tile < p.rt_hi) lo = mid + 1; else hi = mid;
-      }
-      hi = lo;
+    if (p.clip_rows && lo < hi) {
+      const int first = tm.key_entries[lo].tile;
+      const int nlo = lo + (p.rt_lo > first ? p.rt_lo - first : 0);
+      const int nhi = lo + (p.rt_hi > first ? p.rt_hi - first : 0);
+      lo = nlo < hi ? nlo : hi;
+      hi = nhi < hi ? nhi : hi;
     }
+    lo_out = lo;
     hi_out = hi;
   };
   int e_lo, e_hi;            // list of the pair's first tile: drives the loop
@@ -1076,46 +1078,62 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
-  p.n_d0_tiles = (a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi ...
-  p.d0_tile_lo = key_lo / kKeysPerTile & ~1;                // ... from the (even) tile pair of the first visible key on
-  p.n_d0_items = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2 * p.Hq;  // key-tile pairs x query heads
-  {
-    // pairs wholly below the segment's first anchor see every row tile (equal lists); the others shrink
-    const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
-    const int equal = acc_below == INT_MAX ? 0 : (acc_below / kKeysPerTile - p.d0_tile_lo) / 2;
-    const int shrinking = n_pairs - (equal > 0 ? equal : 0);
-    constexpr int kPasses = 4;
-    p.d0_step = (shrinking + kPasses - 1) / kPasses;
-    if (p.d0_step < 2) p.d0_step = 2;
-    p.d0_split = n_pairs - shrinking + p.d0_step;
-    if (p.d0_split > n_pairs) p.d0_split = n_pairs;
-  }
-  const int n_chain_items = n_rt * ((p.tm.n_csub + 1) / 2) * p.Hkv;
-  {
-    const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
-    TimedSpan span(timer, kKindDkDv, stream);
-    const bool listed = p.tm.row_tok != nullptr;
-    if (D == 64) {
-      if (listed) hipLaunchKernelGGL((dkdv_kernel<64, 1, true>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((dkdv_kernel<64, 1, false>), grid, dim3(256), 0, stream, p);
-    } else {
-      if (listed) hipLaunchKernelGGL((dkdv_kernel<128, 1, true>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((dkdv_kernel<128, 1, false>), grid, dim3(256), 0, stream, p);
+  // dK/dV runs over chunks of at most 64 row tiles (dense maps): within a chunk the key tiles below
+  // its first anchor have equally long lists, which balances the workgroups the way the paper's
+  // segments do; each chunk is followed by its own reduction, later chunks adding to what the
+  // earlier ones wrote.
+  const bool listed_map = p.tm.row_tok != nullptr;
+  const int chunk = listed_map ? n_rt : 64;
+  const int seg_rt_lo = p.rt_lo, seg_rt_hi = p.rt_hi;
+  for (int c0 = seg_rt_lo; c0 < seg_rt_hi; c0 += chunk) {
+    p.rt_lo = c0;
+    p.rt_hi = c0 + chunk < seg_rt_hi ? c0 + chunk : seg_rt_hi;
+    const bool partial = p.rt_lo != seg_rt_lo || p.rt_hi != seg_rt_hi;
+    p.clip_rows = (pin.cropped || partial) ? 1 : 0;
+    const int c_a_hi = listed_map || p.rt_hi * p.tm.A > a_hi ? a_hi : p.rt_hi * p.tm.A;
+    const int c_acc = c0 == seg_rt_lo || acc_below == INT_MAX ? acc_below
+                                                                : (acc_below > c0 * p.tm.A ? acc_below : c0 * p.tm.A);
+    p.n_d0_tiles = (c_a_hi + kKeysPerTile - 1) / kKeysPerTile;  // depth-0 key tiles visible to rows < a_hi ...
+    p.d0_tile_lo = key_lo / kKeysPerTile & ~1;                // ... from the (even) tile pair of the first visible key on
+    p.n_d0_items = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2 * p.Hq;  // key-tile pairs x query heads
+    {
+      // pairs wholly below the segment's first anchor see every row tile (equal lists); the others shrink
+      const int n_pairs = (p.n_d0_tiles - p.d0_tile_lo + 1) / 2;
+      const int equal = c_acc == INT_MAX ? 0 : (c_acc / kKeysPerTile - p.d0_tile_lo) / 2;
+      const int shrinking = n_pairs - (equal > 0 ? equal : 0);
+      constexpr int kPasses = 4;
+      p.d0_step = (shrinking + kPasses - 1) / kPasses;
+      if (p.d0_step < 2) p.d0_step = 2;
+      p.d0_split = n_pairs - shrinking + p.d0_step;
+      if (p.d0_split > n_pairs) p.d0_split = n_pairs;
     }
-    hipError_t e = span.finish();
-    if (e != hipSuccess) return e;
-  }
-  {
-    const int key_first = p.d0_tile_lo * kKeysPerTile;
-    const size_t n = 2 * (size_t)(a_hi - key_first) * p.Hkv * (D / 4);
-    size_t blocks = (n + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    const dim3 grid((unsigned)blocks), block(256);
-    TimedSpan span(timer, kKindReduce, stream);
-    if (D == 64) hipLaunchKernelGGL((reduce_partials_kernel<64>), grid, block, 0, stream, p, key_first, a_hi, acc_below);
-    else hipLaunchKernelGGL((reduce_partials_kernel<128>), grid, block, 0, stream, p, key_first, a_hi, acc_below);
-    hipError_t e = span.finish();
-    if (e != hipSuccess) return e;
+    const int n_chain_items = (p.rt_hi - p.rt_lo) * ((p.tm.n_csub + 1) / 2) * p.Hkv;
+    {
+      const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
+      TimedSpan span(timer, kKindDkDv, stream);
+      const bool listed = p.tm.row_tok != nullptr;
+      if (D == 64) {
+        if (listed) hipLaunchKernelGGL((dkdv_kernel<64, 1, true>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((dkdv_kernel<64, 1, false>), grid, dim3(256), 0, stream, p);
+      } else {
+        if (listed) hipLaunchKernelGGL((dkdv_kernel<128, 1, true>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((dkdv_kernel<128, 1, false>), grid, dim3(256), 0, stream, p);
+      }
+      hipError_t e = span.finish();
+      if (e != hipSuccess) return e;
+    }
+    {
+      const int key_first = p.d0_tile_lo * kKeysPerTile;
+      const size_t n = 2 * (size_t)(c_a_hi - key_first) * p.Hkv * (D / 4);
+      size_t blocks = (n + 255) / 256;
+      if (blocks > 256 * 16) blocks = 256 * 16;
+      const dim3 grid((unsigned)blocks), block(256);
+      TimedSpan span(timer, kKindReduce, stream);
+      if (D == 64) hipLaunchKernelGGL((reduce_partials_kernel<64>), grid, block, 0, stream, p, key_first, c_a_hi, c_acc);
+      else hipLaunchKernelGGL((reduce_partials_kernel<128>), grid, block, 0, stream, p, key_first, c_a_hi, c_acc);
+      hipError_t e = span.finish();
+      if (e != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }
