@@ -495,6 +495,9 @@ PACKED = [
     ("segments_across_sequences_sampled", (100, 37, 64, 1, 90), 8, 2, 1, 64, 0.8, 420, [0, 50, 120, 292], 1),
     ("d128_two", (90, 60), 8, 2, 1, 128, None, 430, [0, 64, 150], 0),
     ("k1_three", (130, 130, 130), 1, 2, 2, 64, None, 440, [0, 200, 390], 0),
+    # more than 64 row tiles in a segment: the dK/dV launches are split into chunks
+    ("long_packed_chunks", (700, 900, 500), 8, 2, 1, 64, None, 450, None, 0),
+    ("long_sampled_chunks_alg1", (1500, 800), 8, 2, 1, 64, 0.8, 460, [0, 2050, 2300], 1),
 ]
 
 
