@@ -289,6 +289,8 @@ def main() -> int:
     ap.add_argument("--cod-retention", type=float, default=None,
                     help="instead of the headline (dense) workload, time the same shape under drop-token sampling "
                          "with this retention rate")
+    ap.add_argument("--partitioned-only", action="store_true",
+                    help="skip the unpartitioned comparison pass (keeps a profiler trace to the partitioned launches)")
     ap.add_argument("--packed", type=int, default=None,
                     help="instead of the headline workload, time a packed batch of this many short sequences")
     ap.add_argument("--seg-anchors", type=int, default=None,
@@ -367,14 +369,16 @@ def main() -> int:
     def whole():
         pe.peagle_attn_fwd(tm, shape, -1, q, k, v, o, lse, stream)
         pe.peagle_attn_bwd(tm, shape, -1, q, k, v, o, do, lse, dq, dk, dv, 0, ws, stream)
-    for _ in range(2):
-        whole()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(max(args.steps // 2, 1)):
-        whole()
-    torch.cuda.synchronize()
-    ms_whole = (time.perf_counter() - t0) * 1e3 / max(args.steps // 2, 1)
+    ms_whole = None
+    if not args.partitioned_only:
+        for _ in range(2):
+            whole()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(args.steps // 2, 1)):
+            whole()
+        torch.cuda.synchronize()
+        ms_whole = (time.perf_counter() - t0) * 1e3 / max(args.steps // 2, 1)
 
     # per-kernel launch durations: HIP events on the launch stream, same workload, same launches
     prof_reps = 5
@@ -418,7 +422,7 @@ def main() -> int:
         "ms_per_step_median": per_step[len(per_step) // 2],
         "ms_per_step_min": per_step[0],
         "unpartitioned_ms_per_step": ms_whole,
-        "partition_overhead": ms_per_step / ms_whole,
+        "partition_overhead": ms_per_step / ms_whole if ms_whole else None,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
