@@ -43,7 +43,11 @@ from the dependency rules and against the dense mask restricted to kept position
 against the dense problem's kept rows, gradients against library autograd, and Algorithm 1
 partitioning against the single pass.  Packed batches: mask against the block-diagonal assembly of
 per-sequence masks rebuilt from the dependency rules, outputs against each sequence alone and
-against library autograd.  No function here is "parity unpinned".
+against library autograd.  Rotary embedding (Sec. 2): the D = 2 case against complex multiplication,
+a hand-computed D = 4 vector, norm and inverse identities, position ids against the rows the worked
+example of Sec. 3.2 names by (position, depth), invariance of the whole step under a common shift
+of all positions, and finite differences of the loss with respect to the unrotated Q and K.  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -66,6 +70,10 @@ __all__ = [
     "packed_tokens",
     "partition_assign",
     "cod_position_count",
+    "position_ids",
+    "rope_angles",
+    "rope_rotate",
+    "attn_step_rope",
 ]
 
 
@@ -356,3 +364,66 @@ def cod_position_count(n: int, K: int, r: float) -> float:
     if r == 1.0:
         return float(n * K)
     return n * (1.0 - r ** K) / (1.0 - r)
+
+
+# --------------------------------------------------------------------------------------
+# rotary position embedding around the attention (Sec. 2: the drafter is a LLaMA 3 style
+# decoder with RoPE, Su et al. 2024)
+# --------------------------------------------------------------------------------------
+
+def position_ids(L: int, K: int, tokens: Optional[Tuple[np.ndarray, ...]] = None) -> np.ndarray:
+    """Sequence position of every stored token.  Depth d predicts the token d+1 ahead of its
+    anchor (Sec. 3), so the row (anchor i, depth d) stands at position p = i + d - the same rows
+    are written (p, d) in Sec. 3.2.  In a packed batch positions restart with every sequence."""
+    if tokens is None:
+        i, d = token_coords(np.arange(L * K), L)
+        return i + d
+    ta, td = np.asarray(tokens[0]), np.asarray(tokens[1])
+    if len(tokens) == 3:
+        ts = np.asarray(tokens[2])
+        first = np.full(int(ts.max()) + 1, np.iinfo(np.int64).max)
+        np.minimum.at(first, ts, ta)          # first anchor of each sequence
+        return ta - first[ts] + td
+    return ta + td
+
+
+def rope_angles(pos: np.ndarray, D: int, base: float) -> np.ndarray:
+    """angle[t, j] = pos[t] * base^(-2j/D), j = 0 .. D/2-1 (RoFormer, Eq. 15)."""
+    j = np.arange(D // 2, dtype=np.float64)
+    return np.asarray(pos, dtype=np.float64)[:, None] * np.float64(base) ** (-2.0 * j / D)
+
+
+def rope_rotate(x: np.ndarray, pos: np.ndarray, base: float, inverse: bool = False) -> np.ndarray:
+    """Rotate every head vector of x [T, H, D] by its token's position: the pair of features
+    (j, j + D/2) turns by angle[t, j] (the half-split pairing of the LLaMA implementations; the
+    paper names the architecture only).  ``inverse`` turns the other way (the transpose of the
+    rotation, which is what gradients take)."""
+    T, H, D = x.shape
+    a = rope_angles(pos, D, base)
+    c, s = np.cos(a)[:, None, :], np.sin(a)[:, None, :]
+    if inverse:
+        s = -s
+    x1, x2 = x[..., :D // 2], x[..., D // 2:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def attn_step_rope(q, k, v, do, L: int, K: int, scale: float, seg_bounds: Sequence[int], base: float,
+                   tokens: Optional[Tuple[np.ndarray, ...]] = None, pos: Optional[np.ndarray] = None,
+                   row_block: int = 1024) -> Dict[str, np.ndarray]:
+    """The attention step on unrotated Q and K: both are rotated by their positions, the attention
+    runs on the rotated tensors, and dQ, dK come back with respect to the unrotated inputs (a rotation's
+    Jacobian is the rotation itself, so each gradient vector is turned back).  Dense sequences run
+    segment by segment (:func:`attn_step_partitioned`); an explicit token list runs as one pass
+    (gradients do not depend on the partition).  ``pos`` overrides the position ids."""
+    if pos is None:
+        pos = position_ids(L, K, tokens)
+    qr = rope_rotate(q, pos, base)
+    kr = rope_rotate(k, pos, base)
+    if tokens is None:
+        r = attn_step_partitioned(qr, kr, v, do, L, K, scale, seg_bounds, row_block=row_block)
+    else:
+        r = attn_backward(qr, kr, v, do, L, K, scale, row_block=row_block, tokens=tokens)
+    r = dict(r)
+    r["dQ"] = rope_rotate(r["dQ"], pos, base, inverse=True)
+    r["dK"] = rope_rotate(r["dK"], pos, base, inverse=True)
+    return r

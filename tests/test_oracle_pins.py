@@ -506,3 +506,127 @@ def test_packed_sampled_tokens_keep_per_sequence_structure():
     assert np.array_equal(M, dense[np.ix_(idx, idx)])
     start = np.concatenate([[0], np.cumsum(seq_lens)])[ts]
     assert np.array_equal(M.sum(axis=1), ta - start + 1 + td)
+
+
+# ----------------------------------------------------------------------------- rotary embedding (Sec. 2)
+
+def test_rope_two_dimensional_case_is_complex_multiplication():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((7, 3, 2))
+    pos = np.array([0, 1, 2, 5, 9, 100, 4097])
+    got = orc.rope_rotate(x, pos, base=10000.0)
+    z = (x[..., 0] + 1j * x[..., 1]) * np.exp(1j * pos.astype(np.float64))[:, None]   # D = 2: the only frequency is 1
+    np.testing.assert_allclose(got[..., 0], z.real, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(got[..., 1], z.imag, rtol=0, atol=1e-12)
+
+
+def test_rope_hand_computed_vector_and_frequencies():
+    # D = 4, base 10000: frequencies 1 and 1/100; features (0,2) and (1,3) are the rotated pairs
+    np.testing.assert_allclose(orc.rope_angles(np.array([3]), 4, 10000.0), [[3.0, 0.03]], rtol=1e-15)
+    x = np.array([[[1.0, 0.0, 0.0, 2.0]]])
+    got = orc.rope_rotate(x, np.array([3]), 10000.0)[0, 0]
+    want = [np.cos(3.0), -2.0 * np.sin(0.03), np.sin(3.0), 2.0 * np.cos(0.03)]
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-15)
+    # LLaMA 3 base, D = 64: the slowest frequency is base^(-62/64)
+    a = orc.rope_angles(np.array([1]), 64, 500000.0)
+    assert abs(a[0, 31] - 500000.0 ** (-62.0 / 64.0)) < 1e-18 and a[0, 0] == 1.0
+
+
+def test_rope_is_an_isometry_with_the_transpose_as_inverse():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((40, 2, 16))
+    y = rng.standard_normal((40, 2, 16))
+    pos = rng.integers(0, 30000, size=40)
+    rx = orc.rope_rotate(x, pos, 500000.0)
+    np.testing.assert_allclose(np.linalg.norm(rx, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    np.testing.assert_allclose(orc.rope_rotate(rx, pos, 500000.0, inverse=True), x, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(orc.rope_rotate(x, np.zeros(40, dtype=int), 500000.0), x)
+    # <R x, y> = <x, R^T y>: the inverse is the transpose (what the gradient takes)
+    lhs = (rx * y).sum()
+    rhs = (x * orc.rope_rotate(y, pos, 500000.0, inverse=True)).sum()
+    assert abs(lhs - rhs) < 1e-10
+    # scores depend on the position difference only
+    q, k = rng.standard_normal((1, 1, 16)), rng.standard_normal((1, 1, 16))
+    s1 = (orc.rope_rotate(q, np.array([17]), 1e4) * orc.rope_rotate(k, np.array([5]), 1e4)).sum()
+    s2 = (orc.rope_rotate(q, np.array([1012]), 1e4) * orc.rope_rotate(k, np.array([1000]), 1e4)).sum()
+    assert abs(s1 - s2) < 1e-10
+
+
+def test_position_ids_follow_the_rows_named_in_the_paper_example():
+    # Sec. 3.2 names rows by (position, depth): "position 8 at depth 2 depends on position 7 at depth 1",
+    # i.e. both belong to anchor 6; stored tokens of the worked example carry those positions.
+    count, d = _paper_example_depth_counts()
+    ta, td = orc.cod_tokens(count)
+    pos = orc.position_ids(len(count), d["K"], tokens=(ta, td))
+    for g in range(d["K"]):
+        assert sorted(pos[td == g].tolist()) == d[f"depth{g}"]
+    t8 = [t for t in range(len(ta)) if td[t] == 2 and pos[t] == 8][0]
+    t7 = [t for t in range(len(ta)) if td[t] == 1 and pos[t] == 7][0]
+    assert ta[t8] == ta[t7] == 6
+    # dense layout t = d*L + i
+    L, K = 5, 3
+    np.testing.assert_array_equal(orc.position_ids(L, K), [0, 1, 2, 3, 4, 1, 2, 3, 4, 5, 2, 3, 4, 5, 6])
+    # packed batch: positions restart with every sequence
+    tok = orc.packed_tokens([3, 2], 2)
+    np.testing.assert_array_equal(orc.position_ids(5, 2, tokens=tok), [0, 1, 2, 0, 1, 1, 2, 3, 1, 2])
+
+
+def test_rope_step_is_invariant_under_a_common_position_shift():
+    L, K, Hq, Hkv, D = 12, 3, 4, 2, 8
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 31)
+    pos = orc.position_ids(L, K)
+    a = orc.attn_step_rope(q, k, v, do, L, K, 0.3, [0, 5, 12], 10000.0)
+    b = orc.attn_step_rope(q, k, v, do, L, K, 0.3, [0, 5, 12], 10000.0, pos=pos + 777)
+    for name in ("O", "LSE", "dV", "dQ", "dK"):       # raw-space gradients are shift invariant too
+        np.testing.assert_allclose(a[name], b[name], rtol=0, atol=1e-9)
+    # with every token at one position all rotations are equal: scores, and with them every output
+    # and raw-space gradient, are those of the unrotated step
+    same = orc.attn_step_rope(q, k, v, do, L, K, 0.3, [0, 5, 12], 10000.0, pos=np.full(L * K, 9))
+    plain = orc.attn_step_partitioned(q, k, v, do, L, K, 0.3, [0, 5, 12])
+    for name in ("O", "LSE", "dV"):
+        np.testing.assert_allclose(same[name], plain[name], rtol=0, atol=1e-9)
+    np.testing.assert_allclose(same["dQ"], plain["dQ"], rtol=0, atol=1e-9)
+    np.testing.assert_allclose(same["dK"], plain["dK"], rtol=0, atol=1e-9)
+
+
+def test_rope_step_gradients_against_finite_differences():
+    L, K, Hq, Hkv, D = 6, 3, 2, 1, 4
+    q, k, v, do = _rand(L, K, Hq, Hkv, D, 33)
+    base, scale, bounds = 100.0, 0.4, [0, 2, 6]
+    r = orc.attn_step_rope(q, k, v, do, L, K, scale, bounds, base)
+
+    def loss(qq, kk):
+        pos = orc.position_ids(L, K)
+        O, _ = orc.attn_forward(orc.rope_rotate(qq, pos, base), orc.rope_rotate(kk, pos, base), v, L, K, scale)
+        return float((O * do).sum())
+
+    eps = 1e-6
+    rng = np.random.default_rng(34)
+    for _ in range(12):
+        t, d = int(rng.integers(L * K)), int(rng.integers(D))
+        h = int(rng.integers(Hq))
+        e = np.zeros_like(q)
+        e[t, h, d] = eps
+        fd = (loss(q + e, k) - loss(q - e, k)) / (2 * eps)
+        assert abs(fd - r["dQ"][t, h, d]) < 1e-7 * max(1.0, abs(fd))
+        e = np.zeros_like(k)
+        e[t, 0, d] = eps
+        fd = (loss(q, k + e) - loss(q, k - e)) / (2 * eps)
+        assert abs(fd - r["dK"][t, 0, d]) < 1e-7 * max(1.0, abs(fd))
+
+
+def test_rope_step_on_a_packed_batch_equals_each_sequence_alone():
+    K, Hq, Hkv, D = 3, 2, 1, 8
+    seq_lens = [5, 7]
+    tok = orc.packed_tokens(seq_lens, K)
+    L = sum(seq_lens)
+    rng = np.random.default_rng(35)
+    T = len(tok[0])
+    q, k, v, do = (rng.standard_normal((T, Hq, D)), rng.standard_normal((T, Hkv, D)),
+                   rng.standard_normal((T, Hkv, D)), rng.standard_normal((T, Hq, D)))
+    both = orc.attn_step_rope(q, k, v, do, L, K, 0.35, [0, L], 500000.0, tokens=tok)
+    for s, n in enumerate(seq_lens):
+        sel = np.nonzero(tok[2] == s)[0]           # depth-major inside the sequence as well
+        one = orc.attn_step_rope(q[sel], k[sel], v[sel], do[sel], n, K, 0.35, [0, n], 500000.0)
+        for name in ("O", "dQ", "dK", "dV"):
+            np.testing.assert_allclose(both[name][sel], one[name], rtol=0, atol=1e-10)
