@@ -251,12 +251,60 @@ int peagle_tilemap_rebuild(peagle_tilemap_t* tm, const int32_t* depth_count, int
  * for a sampled one (which accepts only its own L).  -1 on a bad argument. */
 int64_t peagle_tilemap_tokens(const peagle_tilemap_t* tm, int32_t L);
 
+/*
+ * Rotary position embedding around the attention step.  The drafter follows the LLaMA 3
+ * architecture with RoPE (Sec. 2), and depth d predicts the token d+1 ahead of its anchor (Sec. 3),
+ * so the stored token (anchor i, depth d) stands at sequence position p = i + d; positions restart
+ * with every sequence of a packed batch.  Feature pair (j, j + D/2) of every head vector of Q and K
+ * turns by the angle p * base^(-2j/D) (half-split pairing; LLaMA 3 uses base = 500000).
+ *
+ * peagle_rope_positions: number of positions a table must cover for a length-L problem under this
+ * map (largest position + 1: L + K - 1 for a dense map); -1 on a bad argument.
+ *
+ * peagle_rope_table: fills table (device, fp32 [n_pos][2][D/2]: per position D/2 cosines, then D/2
+ * sines) on `stream`; angles are formed and reduced in double precision.  Built once per
+ * (base, D, n_pos) and reused, like the tile map.  EINVAL unless base > 1 and n_pos >= 1.
+ */
+int32_t peagle_rope_positions(const peagle_tilemap_t* tm, int32_t L);
+/* Position id of every stored token of a length-L problem: pos_out (host, int32[T]). */
+int peagle_rope_position_ids(const peagle_tilemap_t* tm, int32_t L, int32_t* pos_out);
+int peagle_rope_table(float base, int32_t D, int32_t n_pos, float* table, void* stream);
+
+/*
+ * out = R x (inverse = 0) or R^T x (inverse = 1) for a tensor of the map's tokens:
+ *   x, out      device, bf16 [T, H, D] (H heads; out may not overlap x unless equal to it)
+ *   rope_table  device, from peagle_rope_table with n_pos >= peagle_rope_positions (else ESHAPE)
+ * fp32 arithmetic, one rounding to bf16.  Exposed for tests and for callers that keep rotated copies.
+ */
+int peagle_rope_rotate(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const void* x, int32_t H,
+                       const float* rope_table, int32_t n_pos, int32_t inverse, void* out, void* stream);
+
+/* Bytes of device scratch peagle_attn_step_partitioned_rope needs: the attention workspace plus
+ * rotated bf16 copies of Q and K. */
+size_t peagle_rope_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape);
+
+/*
+ * peagle_attn_step_partitioned on unrotated Q and K: both are rotated by their tokens' positions
+ * (one streaming pass each, into the workspace), every segment's forward and backward run on the
+ * rotated copies, and dQ, dK are returned with respect to the unrotated inputs: the gradient
+ * vectors are turned back (R^T) in fp32 inside the kernels that store them (dQ kernel, chain-key
+ * epilogue of the dK/dV kernel, summation of the depth-0 partials), so dk_acc stays in the
+ * unrotated frame across segments and calls.  Every other argument, and the dK/dV accumulation
+ * rule, are those of peagle_attn_step_partitioned; workspace >= peagle_rope_workspace_bytes().
+ */
+int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin,
+                                      int32_t seg_end, const void* q, const void* k, const void* v,
+                                      const void* d_o, const float* rope_table, int32_t n_pos, void* o, float* lse,
+                                      void* dq, float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
+                                      void* workspace, size_t ws_bytes, void* stream);
+
 /* Kernel kinds reported by peagle_attn_step_profiled. */
 #define PEAGLE_KERNEL_FWD 0      /* forward (O, LSE) */
 #define PEAGLE_KERNEL_DQ 1       /* Delta and dQ */
 #define PEAGLE_KERNEL_DKDV 2     /* dK, dV */
 #define PEAGLE_KERNEL_REDUCE 3   /* sum of the per-head depth-0 dK/dV partials into the accumulators */
-#define PEAGLE_NUM_KERNEL_KINDS 4
+#define PEAGLE_KERNEL_ROPE 4     /* rotation of Q and K (peagle_attn_step_rope_profiled only) */
+#define PEAGLE_NUM_KERNEL_KINDS 5
 
 typedef struct peagle_profile {
   float ms[PEAGLE_NUM_KERNEL_KINDS];          /* summed launch durations per kernel kind, milliseconds */
@@ -272,6 +320,13 @@ int peagle_attn_step_profiled(const peagle_tilemap_t* tm, const peagle_shape_t* 
                               int32_t seg_end, const void* q, const void* k, const void* v, const void* d_o,
                               void* o, float* lse, void* dq, float* dk_acc, float* dv_acc, void* workspace,
                               size_t ws_bytes, void* stream, peagle_profile_t* profile);
+
+/* Measurement aid: the same for peagle_attn_step_partitioned_rope. */
+int peagle_attn_step_rope_profiled(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin,
+                                   int32_t seg_end, const void* q, const void* k, const void* v, const void* d_o,
+                                   const float* rope_table, int32_t n_pos, void* o, float* lse, void* dq,
+                                   float* dk_acc, float* dv_acc, void* workspace, size_t ws_bytes, void* stream,
+                                   peagle_profile_t* profile);
 
 /*
  * Measurement aid: runs a register-only v_mfma_f32_32x32x16_bf16 issue loop on every CU of the

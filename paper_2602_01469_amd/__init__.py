@@ -14,7 +14,14 @@ from .binding import (  # noqa: F401
     peagle_attn_bwd,
     peagle_attn_fwd,
     peagle_attn_step_partitioned,
+    peagle_attn_step_partitioned_rope,
     peagle_attn_step_profiled,
+    peagle_attn_step_rope_profiled,
+    peagle_rope_position_ids,
+    peagle_rope_positions,
+    peagle_rope_rotate,
+    peagle_rope_table,
+    peagle_rope_workspace_bytes,
     peagle_build_tilemap_packed,
     peagle_build_tilemap_sampled,
     peagle_measure_mfma_ceiling,

@@ -36,14 +36,16 @@ EXPORTS = [
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
     "peagle_attn_step_partitioned", "peagle_build_tilemap_sampled", "peagle_build_tilemap_packed",
     "peagle_tilemap_rebuild", "peagle_tilemap_tokens",
+    "peagle_rope_positions", "peagle_rope_position_ids", "peagle_rope_table", "peagle_rope_rotate", "peagle_rope_workspace_bytes",
+    "peagle_attn_step_partitioned_rope", "peagle_attn_step_rope_profiled",
     "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
-KERNEL_KINDS = ("fwd", "dq", "dkdv", "reduce")
+KERNEL_KINDS = ("fwd", "dq", "dkdv", "reduce", "rope")
 
 
 class _ProfileC(C.Structure):
-    _fields_ = [("ms", C.c_float * 4), ("launches", C.c_int32 * 4)]
+    _fields_ = [("ms", C.c_float * len(KERNEL_KINDS)), ("launches", C.c_int32 * len(KERNEL_KINDS))]
 
 
 def lib_path() -> str:
@@ -93,6 +95,22 @@ def load_library():
     lib.peagle_attn_step_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                               sz, vp, C.POINTER(_ProfileC)]
     lib.peagle_attn_step_profiled.restype = C.c_int
+    lib.peagle_rope_positions.argtypes = [vp, i32]
+    lib.peagle_rope_positions.restype = i32
+    lib.peagle_rope_position_ids.argtypes = [vp, i32, C.POINTER(i32)]
+    lib.peagle_rope_position_ids.restype = C.c_int
+    lib.peagle_rope_table.argtypes = [C.c_float, i32, i32, vp, vp]
+    lib.peagle_rope_table.restype = C.c_int
+    lib.peagle_rope_rotate.argtypes = [vp, C.POINTER(_ShapeC), vp, i32, vp, i32, i32, vp, vp]
+    lib.peagle_rope_rotate.restype = C.c_int
+    lib.peagle_rope_workspace_bytes.argtypes = [vp, C.POINTER(_ShapeC)]
+    lib.peagle_rope_workspace_bytes.restype = sz
+    lib.peagle_attn_step_partitioned_rope.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, i32, vp, vp,
+                                                      vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.peagle_attn_step_partitioned_rope.restype = C.c_int
+    lib.peagle_attn_step_rope_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, i32, vp, vp,
+                                                   vp, vp, vp, vp, sz, vp, C.POINTER(_ProfileC)]
+    lib.peagle_attn_step_rope_profiled.restype = C.c_int
     lib.peagle_measure_mfma_ceiling.argtypes = [vp, C.POINTER(C.c_float)]
     lib.peagle_measure_mfma_ceiling.restype = C.c_int
     lib.peagle_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
@@ -344,6 +362,87 @@ def peagle_attn_step_profiled(tm: TileMap, shape: Shape, seg_begin: int, seg_end
         C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream), C.byref(prof))
     if rc != 0:
         raise PeagleError(rc, "peagle_attn_step_profiled")
+    return {name: (float(prof.ms[i]), int(prof.launches[i])) for i, name in enumerate(KERNEL_KINDS)}
+
+
+def peagle_rope_positions(tm: TileMap, L: int) -> int:
+    n = int(load_library().peagle_rope_positions(tm.handle, L))
+    if n < 0:
+        raise PeagleError(-1, "peagle_rope_positions")
+    return n
+
+
+def peagle_rope_position_ids(tm: TileMap, L: int) -> np.ndarray:
+    out = np.zeros(tm.tokens(L), dtype=np.int32)
+    rc = load_library().peagle_rope_position_ids(tm.handle, L, out.ctypes.data_as(C.POINTER(C.c_int32)))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_rope_position_ids")
+    return out
+
+
+def peagle_rope_table(base: float, D: int, n_pos: int, table, stream=None) -> None:
+    """Fills `table` (fp32 GPU tensor [n_pos, 2, D/2]) with the cosines and sines of every position."""
+    import torch
+    rc = load_library().peagle_rope_table(float(base), D, n_pos, _ptr(table, "table", torch.float32, (n_pos, 2, D // 2)),
+                                          _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_rope_table")
+
+
+def peagle_rope_rotate(tm: TileMap, shape: Shape, x, rope_table, out, inverse: bool = False, stream=None) -> None:
+    import torch
+    T = tm.tokens(shape.L)
+    H = x.shape[1]
+    n_pos = rope_table.shape[0]
+    rc = load_library().peagle_rope_rotate(
+        tm.handle, shape.c(), _ptr(x, "x", torch.bfloat16, (T, H, shape.D)), H,
+        _ptr(rope_table, "rope_table", torch.float32, (n_pos, 2, shape.D // 2)), n_pos, int(inverse),
+        _ptr(out, "out", torch.bfloat16, (T, H, shape.D)), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_rope_rotate")
+
+
+def peagle_rope_workspace_bytes(tm: TileMap, shape: Shape) -> int:
+    n = int(load_library().peagle_rope_workspace_bytes(tm.handle, shape.c()))
+    if n == 0:
+        raise PeagleError(-3, "peagle_rope_workspace_bytes")
+    return n
+
+
+def _rope_step_args(tm, shape, seg_begin, seg_end, q, k, v, d_o, rope_table, o, lse, dq, dk_acc, dv_acc):
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    T = tm.tokens(shape.L)
+    qs, ks = (T, shape.Hq, shape.D), (T, shape.Hkv, shape.D)
+    n_pos = rope_table.shape[0]
+    return [tm.handle, shape.c(), seg_begin, seg_end, _ptr(q, "q", bf, qs), _ptr(k, "k", bf, ks), _ptr(v, "v", bf, ks),
+            _ptr(d_o, "d_o", bf, qs), _ptr(rope_table, "rope_table", f32, (n_pos, 2, shape.D // 2)), n_pos,
+            _ptr(o, "o", bf, qs), _ptr(lse, "lse", f32, (shape.Hq, T)), _ptr(dq, "dq", bf, qs),
+            _ptr(dk_acc, "dk_acc", f32, ks), _ptr(dv_acc, "dv_acc", f32, ks)], ks
+
+
+def peagle_attn_step_partitioned_rope(tm: TileMap, shape: Shape, seg_begin: int, seg_end: int, q, k, v, d_o, rope_table,
+                                      o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16, workspace, stream=None) -> None:
+    import torch
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
+    args, ks = _rope_step_args(tm, shape, seg_begin, seg_end, q, k, v, d_o, rope_table, o, lse, dq, dk_acc, dv_acc)
+    rc = load_library().peagle_attn_step_partitioned_rope(
+        *args, _ptr(dk_bf16, "dk_bf16", torch.bfloat16, ks), _ptr(dv_bf16, "dv_bf16", torch.bfloat16, ks),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_step_partitioned_rope")
+
+
+def peagle_attn_step_rope_profiled(tm: TileMap, shape: Shape, seg_begin: int, seg_end: int, q, k, v, d_o, rope_table,
+                                   o, lse, dq, dk_acc, dv_acc, workspace, stream=None) -> dict:
+    """Same work as peagle_attn_step_partitioned_rope; returns {kind: (ms, launches)} from HIP events."""
+    args, _ = _rope_step_args(tm, shape, seg_begin, seg_end, q, k, v, d_o, rope_table, o, lse, dq, dk_acc, dv_acc)
+    prof = _ProfileC()
+    rc = load_library().peagle_attn_step_rope_profiled(*args, C.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                                       _stream_ptr(stream), C.byref(prof))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_step_rope_profiled")
     return {name: (float(prof.ms[i]), int(prof.launches[i])) for i, name in enumerate(KERNEL_KINDS)}
 
 

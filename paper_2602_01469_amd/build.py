@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpeagle_attn.so")
-SOURCES = ["tilemap.cpp", "api.cpp", "attn_kernels.hip"]
+SOURCES = ["tilemap.cpp", "api.cpp", "attn_kernels.hip", "rope_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 

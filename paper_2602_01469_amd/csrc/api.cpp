@@ -11,6 +11,8 @@ using peagle::BwdParams;
 using peagle::FwdParams;
 using peagle::SegRange;
 
+static_assert(PEAGLE_NUM_KERNEL_KINDS == peagle::kNumKinds, "public and internal kernel kinds differ");
+
 namespace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -71,7 +73,8 @@ FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
 
 BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
                    const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
-                   float* dk_acc, float* dv_acc, void* workspace, int chain_accumulate) {
+                   float* dk_acc, float* dv_acc, void* workspace, int chain_accumulate,
+                   const float* rope_table = nullptr) {
   const WsLayout w = ws_layout(tm, s);
   BwdParams p{};
   p.q = (const __bf16*)q;
@@ -101,7 +104,25 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   p.chain_accumulate = chain_accumulate;
   p.c_log2 = s->scale * 1.4426950408889634f;
   p.scale = s->scale;
+  p.rope_table = rope_table;
   return p;
+}
+
+// Rotary embedding: positions the table must cover, and where the rotated copies of Q and K live
+// behind the attention workspace.
+int32_t rope_positions(const peagle_tilemap_t* tm, int32_t L) {
+  return tm->sampled ? tm->max_posid + 1 : L + tm->K - 1;
+}
+struct RopeWs {
+  size_t q_off, k_off, total;
+};
+RopeWs rope_ws(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
+  RopeWs w;
+  const size_t T = tokens_of(tm, s);
+  w.q_off = ws_layout(tm, s).total;
+  w.k_off = w.q_off + align256(T * s->Hq * s->D * 2);
+  w.total = w.k_off + align256(T * s->Hkv * s->D * 2);
+  return w;
 }
 
 }  // namespace
@@ -146,14 +167,32 @@ extern "C" int peagle_attn_bwd(const peagle_tilemap_t* tm, const peagle_shape_t*
 static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int32_t seg_begin, int32_t seg_end,
                      const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
                      float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes,
-                     void* stream, peagle::KernelTimer* timer) {
+                     void* stream, peagle::KernelTimer* timer, const float* rope_table = nullptr,
+                     int32_t rope_n_pos = 0) {
   int rc = check_shape(tm, shape);
   if (rc != PEAGLE_OK) return rc;
   if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
   if (seg_begin < 0 || seg_end > tm->S || seg_begin > seg_end) return PEAGLE_EINVAL;
-  if (!workspace || ws_bytes < ws_layout(tm, shape).total) return PEAGLE_EWORKSPACE;
+  const size_t ws_need = rope_table ? rope_ws(tm, shape).total : ws_layout(tm, shape).total;
+  if (!workspace || ws_bytes < ws_need) return PEAGLE_EWORKSPACE;
+  if (rope_table && rope_n_pos < rope_positions(tm, shape->L)) return PEAGLE_ESHAPE;
   if (tm->device < 0) return PEAGLE_ENODEVICE;
   hipStream_t st = (hipStream_t)stream;
+  if (rope_table) {
+    // Q and K arrive unrotated: the attention runs on rotated copies kept behind the workspace
+    const RopeWs rw = rope_ws(tm, shape);
+    void* q_rot = (char*)workspace + rw.q_off;
+    void* k_rot = (char*)workspace + rw.k_off;
+    const int T = (int)tokens_of(tm, shape);
+    if (peagle::launch_rope_rotate(q, q_rot, shape->Hq, T, shape->D, tm->dview, shape->L, rope_table, false, st,
+                                   timer) != hipSuccess)
+      return PEAGLE_EHIP;
+    if (peagle::launch_rope_rotate(k, k_rot, shape->Hkv, T, shape->D, tm->dview, shape->L, rope_table, false, st,
+                                   timer) != hipSuccess)
+      return PEAGLE_EHIP;
+    q = q_rot;
+    k = k_rot;
+  }
   for (int32_t s = seg_begin; s < seg_end; ++s) {
     SegRange sr;
     rc = peagle::resolve_segment(tm, shape->L, s, &sr);
@@ -163,7 +202,7 @@ static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, in
     if (peagle::launch_fwd(fp, shape->D, st, timer) != hipSuccess) return PEAGLE_EHIP;
     // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
     // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
-    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0);
+    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0, rope_table);
     if (peagle::launch_bwd(bp, shape->D, sr.key_lo, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
   }
   if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
@@ -196,6 +235,79 @@ extern "C" int peagle_attn_step_profiled(const peagle_tilemap_t* tm, const peagl
   peagle::KernelTimer timer;
   int rc = step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr,
                      workspace, ws_bytes, stream, &timer);
+  if (rc != PEAGLE_OK) return rc;
+  return timer.collect(profile->ms, profile->launches) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+}
+
+extern "C" int32_t peagle_rope_positions(const peagle_tilemap_t* tm, int32_t L) {
+  if (!tm || L < 1 || L > tm->L_max || (tm->sampled && L != tm->L_max)) return -1;
+  return rope_positions(tm, L);
+}
+
+extern "C" int peagle_rope_position_ids(const peagle_tilemap_t* tm, int32_t L, int32_t* pos_out) {
+  if (!tm || !pos_out) return PEAGLE_ENULL;
+  if (L < 1 || L > tm->L_max || (tm->sampled && L != tm->L_max)) return PEAGLE_ESHAPE;
+  if (tm->sampled) {
+    for (size_t t = 0; t < tm->tok_posid.size(); ++t) pos_out[t] = tm->tok_posid[t];
+  } else {
+    for (int32_t d = 0; d < tm->K; ++d)
+      for (int32_t i = 0; i < L; ++i) pos_out[(size_t)d * L + i] = i + d;
+  }
+  return PEAGLE_OK;
+}
+
+extern "C" int peagle_rope_table(float base, int32_t D, int32_t n_pos, float* table, void* stream) {
+  if (!table) return PEAGLE_ENULL;
+  if (!(base > 1.f) || !std::isfinite(base) || n_pos < 1) return PEAGLE_EINVAL;
+  if (D != 64 && D != 128) return PEAGLE_EUNSUPPORTED;
+  return peagle::launch_rope_table((double)base, D, n_pos, table, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK
+                                                                                                      : PEAGLE_EHIP;
+}
+
+extern "C" int peagle_rope_rotate(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const void* x, int32_t H,
+                                  const float* rope_table, int32_t n_pos, int32_t inverse, void* out, void* stream) {
+  int rc = check_shape(tm, shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!x || !out || !rope_table) return PEAGLE_ENULL;
+  if (H < 1 || (inverse != 0 && inverse != 1)) return PEAGLE_EINVAL;
+  if (n_pos < rope_positions(tm, shape->L)) return PEAGLE_ESHAPE;
+  if (tm->device < 0) return PEAGLE_ENODEVICE;
+  return peagle::launch_rope_rotate(x, out, H, (int)tokens_of(tm, shape), shape->D, tm->dview, shape->L, rope_table,
+                                    inverse != 0, (hipStream_t)stream) == hipSuccess
+             ? PEAGLE_OK
+             : PEAGLE_EHIP;
+}
+
+extern "C" size_t peagle_rope_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape) {
+  if (check_shape(tm, shape) != PEAGLE_OK) return 0;
+  return rope_ws(tm, shape).total;
+}
+
+extern "C" int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
+                                                 int32_t seg_begin, int32_t seg_end, const void* q, const void* k,
+                                                 const void* v, const void* d_o, const float* rope_table,
+                                                 int32_t n_pos, void* o, float* lse, void* dq, float* dk_acc,
+                                                 float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace,
+                                                 size_t ws_bytes, void* stream) {
+  if (!rope_table) return PEAGLE_ENULL;
+  return step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
+                   workspace, ws_bytes, stream, nullptr, rope_table, n_pos);
+}
+
+extern "C" int peagle_attn_step_rope_profiled(const peagle_tilemap_t* tm, const peagle_shape_t* shape,
+                                              int32_t seg_begin, int32_t seg_end, const void* q, const void* k,
+                                              const void* v, const void* d_o, const float* rope_table, int32_t n_pos,
+                                              void* o, float* lse, void* dq, float* dk_acc, float* dv_acc,
+                                              void* workspace, size_t ws_bytes, void* stream,
+                                              peagle_profile_t* profile) {
+  if (!profile || !rope_table) return PEAGLE_ENULL;
+  for (int i = 0; i < PEAGLE_NUM_KERNEL_KINDS; ++i) {
+    profile->ms[i] = 0.f;
+    profile->launches[i] = 0;
+  }
+  peagle::KernelTimer timer;
+  int rc = step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr,
+                     workspace, ws_bytes, stream, &timer, rope_table, n_pos);
   if (rc != PEAGLE_OK) return rc;
   return timer.collect(profile->ms, profile->launches) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }

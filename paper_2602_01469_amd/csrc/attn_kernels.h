@@ -46,10 +46,12 @@ struct BwdParams {
   int d0_split, d0_step;  // filled by the launcher: depth-0 pairs are dealt in passes, [0, d0_split) then d0_step at a time
   int chain_accumulate; // chain keys: add to dk_acc/dv_acc instead of overwriting
   float c_log2, scale;
+  const float* rope_table;  // null, or [positions][2][D/2] cosines and sines: q and k are rotated copies, and dQ / dK
+                            // are turned back to the unrotated inputs' frame before they are stored
 };
 
 // Optional per-kernel timing: an event pair is recorded around every launch on the launch stream.
-enum KernelKind { kKindFwd = 0, kKindDq = 1, kKindDkDv = 2, kKindReduce = 3, kNumKinds = 4 };
+enum KernelKind { kKindFwd = 0, kKindDq = 1, kKindDkDv = 2, kKindReduce = 3, kKindRope = 4, kNumKinds = 5 };
 struct KernelTimer {
   struct Span { hipEvent_t start, stop; int kind; };
   std::vector<Span> spans;
@@ -68,5 +70,10 @@ hipError_t launch_bwd(const BwdParams& p, int D, int key_lo, int a_hi, int acc_b
 // Dense bf16 MFMA issue loop on every CU: the measured matrix-core ceiling of the device, in TFLOP/s.
 hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t stream);
+// Rotary embedding: table [n_pos][2][D/2] of cosines and sines; rotation of a bf16 [T, H, D] tensor
+// by each token's position (inverse: the transpose).
+hipError_t launch_rope_table(double base, int D, int n_pos, float* table, hipStream_t stream);
+hipError_t launch_rope_rotate(const void* x, void* out, int H, int T, int D, const DeviceTileMap& tm, int L,
+                              const float* table, bool inverse, hipStream_t stream, KernelTimer* timer = nullptr);
 
 }  // namespace peagle

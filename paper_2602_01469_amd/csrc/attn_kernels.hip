@@ -10,6 +10,7 @@
 // from LDS with ds_read_b64_tr_b16.
 #include "attn_kernels.h"
 #include "mfma_util.h"
+#include "rope_util.h"
 
 #include <climits>
 #include <type_traits>
@@ -545,6 +546,34 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   }
 
   if (row_ok) {
+    if (p.rope_table) {
+      // q was the rotated copy: turn dQ back.  The lane holds features db*32 + 8*q4 + 4g + j of its
+      // row, so both members of every pair (feature, feature + D/2) are in its own registers.
+      const float* rope = p.rope_table + (size_t)token_position(tm, tq, p.L) * D;
+#pragma unroll
+      for (int db = 0; db < D / 64; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = db * 32 + 8 * q4 + 4 * g;
+          const f32x4 cs = *reinterpret_cast<const f32x4*>(rope + d0);
+          const f32x4 sn = *reinterpret_cast<const f32x4*>(rope + D / 2 + d0);
+#pragma unroll
+          for (int hh = 0; hh < NH; ++hh) {
+            f32x4 lo, hi;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              lo[j] = dq[hh][db][4 * q4 + j];
+              hi[j] = dq[hh][db + D / 64][4 * q4 + j];
+            }
+            rope_turn4<true>(lo, hi, cs, sn);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              dq[hh][db][4 * q4 + j] = lo[j];
+              dq[hh][db + D / 64][4 * q4 + j] = hi[j];
+            }
+          }
+        }
+    }
 #pragma unroll
     for (int hh = 0; hh < NH; ++hh) {
       __bf16* drow = p.dq + ((size_t)tq * p.Hq + h0 + hh) * D;
@@ -905,6 +934,30 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
       dkd = p.dk_acc + row * D;
       dvd = p.dv_acc + row * D;
     }
+    if (write && chain && p.rope_table) {
+      // k was the rotated copy: turn the chain keys' dK back (lane <-> key, both members of a feature
+      // pair in its registers).  Depth-0 keys are turned back where their per-head partials are summed.
+      const float* rope = p.rope_table + (size_t)token_position(tm, key_tok, p.L) * D;
+#pragma unroll
+      for (int db = 0; db < D / 64; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = db * 32 + 8 * q4 + 4 * g;
+          f32x4 lo, hi;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            lo[j] = dk[db][4 * q4 + j];
+            hi[j] = dk[db + D / 64][4 * q4 + j];
+          }
+          rope_turn4<true>(lo, hi, *reinterpret_cast<const f32x4*>(rope + d0),
+                           *reinterpret_cast<const f32x4*>(rope + D / 2 + d0));
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            dk[db][4 * q4 + j] = lo[j];
+            dk[db + D / 64][4 * q4 + j] = hi[j];
+          }
+        }
+    }
     if (write) {
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
@@ -942,10 +995,23 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(BwdParams p, int k
     const int kvh = rem % p.Hkv;
     const int j = key_first + (int)(rem / p.Hkv);
     const float* part = which ? p.dv_part : p.dk_part;
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (int hh = 0; hh < group; ++hh)
-      sum += *reinterpret_cast<const f32x4*>(part + (((size_t)(kvh * group + hh) * p.L64 + j) * D + c4 * 4));
+    // With rotary embedding the summed dK is turned back to the unrotated keys' frame: the thread of
+    // a lower-half piece also sums its partner piece of the upper half and stores both.
+    const bool turn = !which && p.rope_table != nullptr;
+    if (turn && c4 >= D / 8) continue;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f}, sum_hi = {0.f, 0.f, 0.f, 0.f};
+    for (int hh = 0; hh < group; ++hh) {
+      const float* src = part + (((size_t)(kvh * group + hh) * p.L64 + j) * D + c4 * 4);
+      sum += *reinterpret_cast<const f32x4*>(src);
+      if (turn) sum_hi += *reinterpret_cast<const f32x4*>(src + D / 2);
+    }
     float* dst = (which ? p.dv_acc : p.dk_acc) + (((size_t)j * p.Hkv + kvh) * D + c4 * 4);
+    if (turn) {
+      const float* rope = p.rope_table + (size_t)token_position(p.tm, j, p.L) * D + c4 * 4;  // depth-0 key j is token j
+      rope_turn4<true>(sum, sum_hi, *reinterpret_cast<const f32x4*>(rope), *reinterpret_cast<const f32x4*>(rope + D / 2));
+      if (j < acc_below) sum_hi += *reinterpret_cast<const f32x4*>(dst + D / 2);
+      *reinterpret_cast<f32x4*>(dst + D / 2) = sum_hi;
+    }
     if (j < acc_below) sum += *reinterpret_cast<const f32x4*>(dst);
     *reinterpret_cast<f32x4*>(dst) = sum;
   }

@@ -101,16 +101,17 @@ int upload_map(peagle_tilemap* tm, hipStream_t stream, bool wait) {
   if (tm->device < 0) return PEAGLE_OK;
   int prev = -1;
   if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(tm->device) != hipSuccess) return PEAGLE_EHIP;
-  constexpr int kArrays = 10;
+  constexpr int kArrays = 11;
   static const char kZeros[256] = {0};
   const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
                               tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
                               tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
                               sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t),
-                              tm->row_tok.size() * sizeof(int32_t), tm->chain_tok.size() * sizeof(int32_t)};
+                              tm->row_tok.size() * sizeof(int32_t), tm->chain_tok.size() * sizeof(int32_t),
+                              tm->tok_posid.size() * sizeof(int32_t)};
   const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
                               tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
-                              tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data()};
+                              tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data(), tm->tok_posid.data()};
   size_t off[kArrays], total = 0;
   for (int i = 0; i < kArrays; ++i) {
     off[i] = total;
@@ -158,6 +159,7 @@ int upload_map(peagle_tilemap* tm, hipStream_t stream, bool wait) {
   tm->dview.row_lead = (const int32_t*)(base + off[7]);
   tm->dview.row_tok = tm->row_tok.empty() ? nullptr : (const int32_t*)(base + off[8]);
   tm->dview.chain_tok = tm->chain_tok.empty() ? nullptr : (const int32_t*)(base + off[9]);
+  tm->dview.tok_posid = tm->tok_posid.empty() ? nullptr : (const int32_t*)(base + off[10]);
   tm->dview.A = tm->A;
   tm->dview.K = tm->K;
   tm->dview.S = tm->S;
@@ -378,12 +380,19 @@ int fill_packed(peagle_tilemap* tm, const int32_t* depth_count_in, int32_t L, in
   tm->masks.clear();
   tm->key_side_id.clear();
 
-  // token of (depth, anchor): depth-major storage, kept anchors ascending
+  // token of (depth, anchor): depth-major storage, kept anchors ascending; its sequence position is
+  // the anchor's offset in its sequence plus the depth (depth g predicts the token g+1 ahead, Sec. 3)
   std::vector<int32_t> tok_of((size_t)L * K, -1);
   int32_t next = 0;
+  tm->tok_posid.clear();
+  tm->max_posid = 0;
   for (int32_t g = 0; g < K; ++g)
     for (int32_t i = 0; i < L; ++i)
-      if (depth_count[i] > g) tok_of[(size_t)g * L + i] = next++;
+      if (depth_count[i] > g) {
+        tok_of[(size_t)g * L + i] = next++;
+        tm->tok_posid.push_back(i - seq_lo[i] + g);
+        tm->max_posid = std::max(tm->max_posid, i - seq_lo[i] + g);
+      }
   tm->T_tokens = next;
   tm->tok_pos.assign(next, -1);
 

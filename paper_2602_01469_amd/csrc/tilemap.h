@@ -37,6 +37,7 @@ struct DeviceTileMap {
   const void* zeros;          // 256 zero bytes: source of rows that do not exist, for direct-to-LDS loads
   const int32_t* row_tok;     // sampled maps only (else null): [n_row_tiles][128] token of each row, -1 = no row
   const int32_t* chain_tok;   // sampled maps only: [n_row_tiles * n_csub][64] token of each chain key, -1 = none
+  const int32_t* tok_posid;   // sampled maps only: [T] sequence position (anchor - sequence start + depth) of each token
   int32_t A, K, S, n_row_tiles, n_d0, n_csub, n_key_tiles;
 };
 
@@ -52,6 +53,8 @@ struct peagle_tilemap {
   std::vector<int32_t> key_side_id;              // per row entry, packed maps only: the id the key tile -> row tile
                                                  // list carries when it differs from the row side (see finish_map)
   std::vector<int64_t> tok_pos;                  // sampled map, host only: token -> row tile * 128 + row
+  std::vector<int32_t> tok_posid;                // sampled map: token -> sequence position (rotary embedding)
+  int32_t max_posid = 0;                         // largest entry of tok_posid
   int32_t n_row_tiles = 0, n_d0 = 0, n_csub = 0, n_key_tiles = 0;
   std::vector<int32_t> seg_bounds;               // [S+1] anchors
   std::vector<int32_t> row_ptr;

@@ -77,3 +77,19 @@ def rel_l2(a, b):
 
 def max_abs(a, b):
     return float(np.abs(a - b).max())
+
+
+def attach_rope(run, base):
+    """Adds a rotary table and the larger workspace to a Run / SampledRun; returns run.step_rope."""
+    L, D = run.shape.L, run.shape.D
+    n_pos = pe.peagle_rope_positions(run.tm, L)
+    run.rope_table = torch.full((n_pos, 2, D // 2), float("nan"), dtype=torch.float32, device="cuda")
+    pe.peagle_rope_table(base, D, n_pos, run.rope_table)
+    run.ws = torch.empty(pe.peagle_rope_workspace_bytes(run.tm, run.shape), dtype=torch.uint8, device="cuda")
+
+    def step_rope(seg_begin, seg_end, dk_bf16=None, dv_bf16=None):
+        pe.peagle_attn_step_partitioned_rope(run.tm, run.shape, seg_begin, seg_end, run.q, run.k, run.v, run.do,
+                                             run.rope_table, run.o, run.lse, run.dq, run.dk, run.dv, dk_bf16, dv_bf16,
+                                             run.ws)
+    run.step_rope = step_rope
+    return run

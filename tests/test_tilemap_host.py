@@ -494,3 +494,56 @@ def test_random_position_sets_expand_to_the_oracle_mask():
         cls = tm.classes()
         inf = tm.info()
         assert (cls == 1).sum() == inf["n_full"] and (cls == 2).sum() == inf["n_partial"], what
+
+
+# ----------------------------------------------------------------------------- rotary embedding: host side
+
+def test_rope_position_ids_equal_the_oracle_for_every_kind_of_map():
+    """Position p = anchor + depth (Sec. 3), restarting per sequence of a packed batch: index work, bit-exact."""
+    from peagle_inputs import cod_depth_counts
+    tm = pe.peagle_build_tilemap(300, 5, None, device=-1)
+    for L in (300, 129, 1):
+        np.testing.assert_array_equal(pe.peagle_rope_position_ids(tm, L), orc.position_ids(L, 5))
+        assert pe.peagle_rope_positions(tm, L) == L + 4
+    count = cod_depth_counts(200, 8, 0.7, 3)
+    tm = pe.peagle_build_tilemap_sampled(count, 8, [0, 90, 200], device=-1)
+    want = orc.position_ids(200, 8, tokens=orc.cod_tokens(count))
+    np.testing.assert_array_equal(pe.peagle_rope_position_ids(tm, 200), want)
+    assert pe.peagle_rope_positions(tm, 200) == want.max() + 1
+    seq_lens = (100, 37, 64, 1, 90)
+    count = cod_depth_counts(sum(seq_lens), 8, 0.8, 4)
+    tm = pe.peagle_build_tilemap_packed(seq_lens, 8, count, None, device=-1)
+    want = orc.position_ids(sum(seq_lens), 8, tokens=orc.packed_tokens(seq_lens, 8, count))
+    np.testing.assert_array_equal(pe.peagle_rope_position_ids(tm, sum(seq_lens)), want)
+    assert pe.peagle_rope_positions(tm, sum(seq_lens)) == want.max() + 1
+    # a rebuild replaces the position ids with the map
+    tm.rebuild((50, 242), cod_depth_counts(292, 8, 0.6, 5))
+    want = orc.position_ids(292, 8, tokens=orc.packed_tokens((50, 242), 8, cod_depth_counts(292, 8, 0.6, 5)))
+    np.testing.assert_array_equal(pe.peagle_rope_position_ids(tm, 292), want)
+
+
+def test_rope_entry_points_validate_before_launch():
+    lib = pe.load_library()
+    tm = pe.peagle_build_tilemap(256, 8, [0, 128, 256], device=-1)
+    one = C.c_void_p(16)  # never dereferenced: validation fails first
+    ok = pe.Shape(256, 8, 4, 2, 64)
+    assert lib.peagle_rope_table(C.c_float(500000.0), 64, 10, None, None) == -2
+    assert lib.peagle_rope_table(C.c_float(1.0), 64, 10, one, None) == -1           # base must exceed 1
+    assert lib.peagle_rope_table(C.c_float(1e4), 64, 0, one, None) == -1
+    assert lib.peagle_rope_table(C.c_float(1e4), 96, 10, one, None) == -5
+    assert lib.peagle_rope_positions(tm.handle, 257) == -1
+    assert lib.peagle_rope_rotate(tm.handle, ok.c(), one, 4, one, 262, 0, one, None) == -3   # table covers too few positions
+    assert lib.peagle_rope_rotate(tm.handle, ok.c(), one, 4, None, 263, 0, one, None) == -2
+    assert lib.peagle_rope_rotate(tm.handle, ok.c(), one, 0, one, 263, 0, one, None) == -1
+    assert lib.peagle_rope_rotate(tm.handle, ok.c(), one, 4, one, 263, 2, one, None) == -1
+    assert lib.peagle_rope_rotate(tm.handle, ok.c(), one, 4, one, 263, 0, one, None) == -8   # host-only map
+    assert pe.peagle_rope_workspace_bytes(tm, ok) >= pe.peagle_workspace_bytes(tm, ok) + 256 * 8 * (4 + 2) * 64 * 2
+
+    def step(table=one, n_pos=263, ws=1 << 40, seg=(0, 2)):
+        return lib.peagle_attn_step_partitioned_rope(tm.handle, ok.c(), seg[0], seg[1], one, one, one, one, table, n_pos,
+                                                     one, one, one, one, one, None, None, one, ws, None)
+    assert step(table=None) == -2
+    assert step(n_pos=262) == -3
+    assert step(ws=pe.peagle_workspace_bytes(tm, ok)) == -6      # the plain workspace is too small
+    assert step(seg=(2, 1)) == -1
+    assert step() == -8
