@@ -274,6 +274,86 @@ def packed(args) -> int:
     return 0
 
 
+def rope(args) -> int:
+    """The named workload with rotary embedding around the step (unrotated Q and K in, gradients in the
+    unrotated frame out): whole-step time beside the plain step on the same inputs, per-kernel times from
+    HIP events, and the rotation kernel against the HBM roofline (it streams Q and K once each way)."""
+    import numpy as np
+    import torch
+
+    import paper_2602_01469_amd as pe
+    from peagle_inputs import CONFIGS, make_inputs, useful_flops
+    pe.load_library()
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.workload]
+    bounds = cfg.seg_bounds()
+    S = len(bounds) - 1
+    tm = pe.peagle_build_tilemap(cfg.L, cfg.K, bounds, device=0)
+    T = cfg.T
+    dev = lambda x: torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    q, k, v, do = (dev(x) for x in make_inputs(cfg))
+    shape = pe.Shape(cfg.L, cfg.K, cfg.Hq, cfg.Hkv, cfg.D, cfg.scale)
+    o, dq = torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty((cfg.Hq, T), dtype=torch.float32, device="cuda")
+    dk = torch.empty((T, cfg.Hkv, cfg.D), dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    ws = torch.empty(pe.peagle_rope_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+    n_pos = pe.peagle_rope_positions(tm, cfg.L)
+    table = torch.empty((n_pos, 2, cfg.D // 2), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pe.peagle_rope_table(args.rope, cfg.D, n_pos, table, stream)
+    torch.cuda.synchronize()
+    table_ms = (time.perf_counter() - t0) * 1e3
+    plain = lambda: pe.peagle_attn_step_partitioned(tm, shape, 0, S, q, k, v, do, o, lse, dq, dk, dv, None, None, ws,
+                                                    stream)
+    roped = lambda: pe.peagle_attn_step_partitioned_rope(tm, shape, 0, S, q, k, v, do, table, o, lse, dq, dk, dv, None,
+                                                         None, ws, stream)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+
+    ms_plain = timed(plain) if not args.partitioned_only else None
+    ms = timed(roped)
+    flops = useful_flops(cfg.L, cfg.K, cfg.Hq, cfg.D)
+    out = {
+        "metric": "effective masked-attn TFLOP/s fwd+bwd (useful FLOPs), rotary embedding of Q and K inside the step",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} with rotary embedding (base {args.rope:g}): L={cfg.L} K={cfg.K} Hq={cfg.Hq} "
+                               f"Hkv={cfg.Hkv} D={cfg.D}, {S} segments, seed {cfg.seed}"},
+        "plain_ms_per_step": ms_plain, "rope_overhead": None if ms_plain is None else ms / ms_plain,
+        "rope_table_ms": table_ms, "rope_positions": n_pos,
+        "finite": bool(torch.isfinite(dk).all().item() and torch.isfinite(dv).all().item())}
+    if not args.partitioned_only:
+        reps, prof = 5, {}
+        for rep in range(reps + 1):     # the first profiled step (event creation, cold) is not counted
+            pr = pe.peagle_attn_step_rope_profiled(tm, shape, 0, S, q, k, v, do, table, o, lse, dq, dk, dv, ws, stream)
+            if rep:
+                for name, (kms, n) in pr.items():
+                    a = prof.setdefault(name, [0.0, 0])
+                    a[0] += kms / reps
+                    a[1] = n
+        out["kernel_ms_per_step"] = {name: prof[name][0] for name in prof}
+        out["kernel_launches_per_step"] = {name: prof[name][1] for name in prof}
+        # rotation: two launches per step (Q, then K), each element read once and written once
+        moved = 2 * 2 * T * (cfg.Hq + cfg.Hkv) * cfg.D
+        rope_ms = prof["rope"][0]
+        out["roofline"] = {"bound": "hbm", "kernel": "rope_rotate_kernel", "achieved": moved / (rope_ms * 1e-3) / 1e9,
+                           "peak": 8000.0, "unit": "GB/s", "frac": moved / (rope_ms * 1e-3) / 1e9 / 8000.0,
+                           "traffic": None, "bytes_per_step": moved, "ms_per_step": rope_ms}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -293,6 +373,8 @@ def main() -> int:
                     help="skip the unpartitioned comparison pass (keeps a profiler trace to the partitioned launches)")
     ap.add_argument("--packed", type=int, default=None,
                     help="instead of the headline workload, time a packed batch of this many short sequences")
+    ap.add_argument("--rope", type=float, default=None, metavar="BASE",
+                    help="run the workload with rotary embedding of Q and K inside the step (e.g. 500000)")
     ap.add_argument("--seg-anchors", type=int, default=None,
                     help="override the anchors per query-row segment (diagnostic; the default is the workload's)")
     args = ap.parse_args()
@@ -306,6 +388,8 @@ def main() -> int:
         return sampled(args)
     if args.packed is not None:
         return packed(args)
+    if args.rope is not None:
+        return rope(args)
 
     import torch
 
@@ -390,7 +474,7 @@ def main() -> int:
             a[0] += ms
             a[1] += n
     kernels = {name: {"ms_per_step": a[0] / prof_reps, "launches_per_step": a[1] // prof_reps,
-                      "avg_launch_ms": a[0] / max(a[1], 1)} for name, a in acc.items()}
+                      "avg_launch_ms": a[0] / max(a[1], 1)} for name, a in acc.items() if a[1] > 0}
     mfma_ceiling = pe.peagle_measure_mfma_ceiling(stream)
     torch.cuda.synchronize()
     if args.calibrate_copy:
