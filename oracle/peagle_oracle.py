@@ -46,8 +46,10 @@ per-sequence masks rebuilt from the dependency rules, outputs against each seque
 against library autograd.  Rotary embedding (Sec. 2): the D = 2 case against complex multiplication,
 a hand-computed D = 4 vector, norm and inverse identities, position ids against the rows the worked
 example of Sec. 3.2 names by (position, depth), invariance of the whole step under a common shift
-of all positions, and finite differences of the loss with respect to the unrotated Q and K.  No
-function here is "parity unpinned".
+of all positions, and finite differences of the loss with respect to the unrotated Q and K.
+Inference-side drafting: against the rows of the last anchor of the training-time problem (mask rebuilt
+from the dependency rules), a library attention routine with an explicit mask, and the zero-query closed
+form.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -74,6 +76,7 @@ __all__ = [
     "rope_angles",
     "rope_rotate",
     "attn_step_rope",
+    "draft_decode",
 ]
 
 
@@ -427,3 +430,39 @@ def attn_step_rope(q, k, v, do, L: int, K: int, scale: float, seg_bounds: Sequen
     r["dQ"] = rope_rotate(r["dQ"], pos, base, inverse=True)
     r["dK"] = rope_rotate(r["dK"], pos, base, inverse=True)
     return r
+
+
+# --------------------------------------------------------------------------------------
+# inference-side parallel drafting (Sec. 2: all K draft tokens in one forward pass)
+# --------------------------------------------------------------------------------------
+
+def draft_decode(q_new: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, k_ctx: np.ndarray, v_ctx: np.ndarray,
+                 scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Attention of one drafting step of one request.  The step adds K positions after a context of n
+    tokens: the next-token position (depth 0, with real inputs) and K-1 multi-token positions (depths
+    1..K-1), all belonging to the anchor n.  They are the rows (n, 0..K-1) of the parallel-prediction
+    mask: row d sees the n context keys (depth-0 keys of earlier anchors, held in the KV cache), the
+    new depth-0 key and its own chain, i.e. the new keys e <= d.
+
+    q_new [K, Hq, D]; k_new, v_new [K, Hkv, D]; k_ctx, v_ctx [n, Hkv, D] (n may be 0).
+    Returns O [K, Hq, D] and LSE [Hq, K] (natural log, scale included)."""
+    K, Hq, D = q_new.shape
+    Hkv = k_new.shape[1]
+    n = k_ctx.shape[0]
+    keys = np.concatenate([k_ctx, k_new], axis=0)
+    vals = np.concatenate([v_ctx, v_new], axis=0)
+    M = np.ones((K, n + K), dtype=bool)
+    for d in range(K):
+        for e in range(K):
+            M[d, n + e] = visible(n, d, n, e)
+    O = np.zeros((K, Hq, D))
+    LSE = np.zeros((Hq, K))
+    for h in range(Hq):
+        g = _kv_head(h, Hq, Hkv)
+        S = np.where(M, scale * (q_new[:, h, :] @ keys[:, g, :].T), -np.inf)
+        m = S.max(axis=1, keepdims=True)
+        E = np.exp(S - m)
+        Z = E.sum(axis=1, keepdims=True)
+        O[:, h, :] = (E / Z) @ vals[:, g, :]
+        LSE[h] = (m + np.log(Z))[:, 0]
+    return O, LSE

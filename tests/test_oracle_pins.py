@@ -630,3 +630,47 @@ def test_rope_step_on_a_packed_batch_equals_each_sequence_alone():
         one = orc.attn_step_rope(q[sel], k[sel], v[sel], do[sel], n, K, 0.35, [0, n], 500000.0)
         for name in ("O", "dQ", "dK", "dV"):
             np.testing.assert_allclose(both[name][sel], one[name], rtol=0, atol=1e-10)
+
+
+# ----------------------------------------------------------------------------- inference-side drafting (Sec. 2)
+
+def test_draft_decode_equals_the_last_anchor_of_the_training_problem():
+    """The K rows of a drafting step are the rows (n, 0..K-1) of the expanded training sequence of n+1
+    anchors: same visible keys (mask rebuilt from the dependency rules), same outputs."""
+    n, K, Hq, Hkv, D = 9, 4, 4, 2, 8
+    L = n + 1
+    q, k, v, _ = _rand(L, K, Hq, Hkv, D, 41)
+    M = _mask_from_dependency_rules(L, K)
+    rows = np.array([d * L + n for d in range(K)])
+    O, LSE = orc.draft_decode(q[rows], k[rows], v[rows], k[:n], v[:n], 0.3)
+    for d in range(K):                                   # visible set of row (n, d): context, (n,0), own chain
+        vis = set(np.nonzero(M[rows[d]])[0].tolist())
+        assert vis == set(range(n)) | {e * L + n for e in range(d + 1)}
+    Ot, LSEt = orc.attn_forward(q, k, v, L, K, 0.3, rows=rows)
+    np.testing.assert_allclose(O, Ot, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(LSE, LSEt, rtol=0, atol=1e-12)
+
+
+def test_draft_decode_against_library_attention_and_closed_forms():
+    n, K, Hq, Hkv, D = 37, 5, 6, 2, 16
+    rng = np.random.default_rng(42)
+    qn, kn, vn = rng.standard_normal((K, Hq, D)), rng.standard_normal((K, Hkv, D)), rng.standard_normal((K, Hkv, D))
+    kc, vc = rng.standard_normal((n, Hkv, D)), rng.standard_normal((n, Hkv, D))
+    O, LSE = orc.draft_decode(qn, kn, vn, kc, vc, 0.25)
+    mask = torch.ones(K, n + K, dtype=torch.bool)
+    mask[:, n:] = torch.tril(torch.ones(K, K, dtype=torch.bool))       # new key e visible to row d iff e <= d
+    keys = torch.from_numpy(np.concatenate([kc, kn])).repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)
+    vals = torch.from_numpy(np.concatenate([vc, vn])).repeat_interleave(Hq // Hkv, dim=1).permute(1, 0, 2)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(qn).permute(1, 0, 2), keys, vals,
+                                                           attn_mask=mask, scale=0.25)
+    np.testing.assert_allclose(O, ref.permute(1, 0, 2).numpy(), rtol=0, atol=1e-12)
+    # zero queries: uniform weights over the n + d + 1 visible keys
+    O0, LSE0 = orc.draft_decode(np.zeros_like(qn), kn, vn, kc, vc, 0.25)
+    allv = np.concatenate([vc, vn])
+    for d in range(K):
+        np.testing.assert_allclose(O0[d, 0], allv[:n + d + 1, 0].mean(axis=0), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(LSE0[:, d], np.log(n + d + 1), rtol=0, atol=1e-12)
+    # empty context: row 0 sees only the new depth-0 key
+    O1, LSE1 = orc.draft_decode(qn, kn, vn, kc[:0], vc[:0], 0.25)
+    np.testing.assert_allclose(O1[0, 0], vn[0, 0], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(LSE1[0, 0], 0.25 * qn[0, 0] @ kn[0, 0], rtol=0, atol=1e-12)
