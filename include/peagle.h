@@ -298,6 +298,45 @@ int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_s
                                       void* dq, float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16,
                                       void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * Inference-side parallel drafting (Sec. 2: the drafter produces all K draft tokens in a single
+ * forward pass; the serving experiments run K = 3, 5, 7 at concurrency 2-4).  One drafting step adds K
+ * positions after a request's cached context of n tokens: the next-token position (depth 0) and K-1
+ * multi-token positions (depths 1..K-1), all of the anchor that follows the context.  They are the
+ * last anchor's rows of the parallel-prediction mask (Sec. 3): the row of depth d sees the n cached
+ * keys and the new keys of depth 0..d.  This call computes that attention for C requests at once.
+ *
+ * The cache is paged: page = PEAGLE_PAGE_TOKENS (64) consecutive tokens of one request, all KV heads.
+ *
+ *   shape        C requests, K new positions each, Hq / Hkv heads (Hq % Hkv == 0, K * Hq/Hkv <= 128),
+ *                D in {64, 128}, scale > 0, n_pages pages in the pools, max_pages block-table columns
+ *   q_new        device, bf16 [C, K, Hq, D]          k_new, v_new  device, bf16 [C, K, Hkv, D]
+ *   k_pages, v_pages   device, bf16 [n_pages, Hkv, 64, D]  (the tail of a request's last page may hold
+ *                anything: it is never used in arithmetic)
+ *   block_table  device, int32 [C, max_pages]: page holding tokens [64 b, 64 b + 64) of request c
+ *   ctx_len      device, int32 [C]: cached tokens n of each request, 0 <= n <= 64 * max_pages
+ *   o            device, bf16 [C, K, Hq, D] (out)    lse  device, fp32 [C, Hq, K] (out; natural log)
+ *   status       device, int32 [C] or NULL (out): 1 if a block-table entry the request uses is outside
+ *                [0, n_pages) or its ctx_len is out of range (such blocks are skipped, the length is
+ *                clamped, nothing is read out of bounds), else 0
+ *   workspace    device, >= peagle_draft_decode_workspace_bytes(); contents undefined before and after
+ *
+ * The context of every request is cut into peagle_draft_decode_splits() pieces that run in
+ * parallel (one workgroup per piece, KV head and request) and are merged by a second launch.
+ * Nothing is allocated and nothing is copied to the host: the call can sit in a serving loop.
+ */
+#define PEAGLE_PAGE_TOKENS 64
+typedef struct peagle_decode_shape {
+  int32_t C, K, Hq, Hkv, D;
+  float scale;
+  int32_t n_pages, max_pages;
+} peagle_decode_shape_t;
+int32_t peagle_draft_decode_splits(const peagle_decode_shape_t* shape);
+size_t peagle_draft_decode_workspace_bytes(const peagle_decode_shape_t* shape);
+int peagle_draft_decode(const peagle_decode_shape_t* shape, const void* q_new, const void* k_new, const void* v_new,
+                        const void* k_pages, const void* v_pages, const int32_t* block_table, const int32_t* ctx_len,
+                        void* o, float* lse, int32_t* status, void* workspace, size_t ws_bytes, void* stream);
+
 /* Kernel kinds reported by peagle_attn_step_profiled. */
 #define PEAGLE_KERNEL_FWD 0      /* forward (O, LSE) */
 #define PEAGLE_KERNEL_DQ 1       /* Delta and dQ */

@@ -6,6 +6,7 @@ used only for device buffers and streams; every step of the path runs in the HIP
 from .binding import (  # noqa: F401
     ASSIGN_ALGORITHM1,
     ASSIGN_BY_ANCHOR,
+    DecodeShape,
     PeagleError,
     Shape,
     TileMap,
@@ -27,6 +28,9 @@ from .binding import (  # noqa: F401
     peagle_measure_mfma_ceiling,
     peagle_build_tilemap,
     peagle_device_info,
+    peagle_draft_decode,
+    peagle_draft_decode_splits,
+    peagle_draft_decode_workspace_bytes,
     peagle_strerror,
     peagle_workspace_bytes,
 )

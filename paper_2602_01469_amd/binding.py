@@ -31,6 +31,11 @@ class _InfoC(C.Structure):
                 ("tokens", C.c_int64), ("sampled", C.c_int32)]
 
 
+class _DecodeShapeC(C.Structure):
+    _fields_ = [("C", C.c_int32), ("K", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+                ("scale", C.c_float), ("n_pages", C.c_int32), ("max_pages", C.c_int32)]
+
+
 EXPORTS = [
     "peagle_build_tilemap", "peagle_tilemap_destroy", "peagle_tilemap_info", "peagle_tilemap_expand_rows",
     "peagle_tilemap_classes", "peagle_workspace_bytes", "peagle_attn_fwd", "peagle_attn_bwd",
@@ -38,6 +43,7 @@ EXPORTS = [
     "peagle_tilemap_rebuild", "peagle_tilemap_tokens",
     "peagle_rope_positions", "peagle_rope_position_ids", "peagle_rope_table", "peagle_rope_rotate", "peagle_rope_workspace_bytes",
     "peagle_attn_step_partitioned_rope", "peagle_attn_step_rope_profiled",
+    "peagle_draft_decode_splits", "peagle_draft_decode_workspace_bytes", "peagle_draft_decode",
     "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
@@ -111,6 +117,12 @@ def load_library():
     lib.peagle_attn_step_rope_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, i32, vp, vp,
                                                    vp, vp, vp, vp, sz, vp, C.POINTER(_ProfileC)]
     lib.peagle_attn_step_rope_profiled.restype = C.c_int
+    lib.peagle_draft_decode_splits.argtypes = [C.POINTER(_DecodeShapeC)]
+    lib.peagle_draft_decode_splits.restype = i32
+    lib.peagle_draft_decode_workspace_bytes.argtypes = [C.POINTER(_DecodeShapeC)]
+    lib.peagle_draft_decode_workspace_bytes.restype = sz
+    lib.peagle_draft_decode.argtypes = [C.POINTER(_DecodeShapeC), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.peagle_draft_decode.restype = C.c_int
     lib.peagle_measure_mfma_ceiling.argtypes = [vp, C.POINTER(C.c_float)]
     lib.peagle_measure_mfma_ceiling.restype = C.c_int
     lib.peagle_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
@@ -444,6 +456,49 @@ def peagle_attn_step_rope_profiled(tm: TileMap, shape: Shape, seg_begin: int, se
     if rc != 0:
         raise PeagleError(rc, "peagle_attn_step_rope_profiled")
     return {name: (float(prof.ms[i]), int(prof.launches[i])) for i, name in enumerate(KERNEL_KINDS)}
+
+
+class DecodeShape:
+    """Shape of one inference-side drafting step: C requests, K new positions each, paged KV cache."""
+
+    def __init__(self, C_: int, K: int, Hq: int, Hkv: int, D: int, n_pages: int, max_pages: int,
+                 scale: Optional[float] = None):
+        self.C, self.K, self.Hq, self.Hkv, self.D, self.n_pages, self.max_pages = C_, K, Hq, Hkv, D, n_pages, max_pages
+        self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(D))
+
+    def c(self):
+        return C.byref(_DecodeShapeC(self.C, self.K, self.Hq, self.Hkv, self.D, self.scale, self.n_pages,
+                                     self.max_pages))
+
+
+def peagle_draft_decode_splits(shape: DecodeShape) -> int:
+    return int(load_library().peagle_draft_decode_splits(shape.c()))
+
+
+def peagle_draft_decode_workspace_bytes(shape: DecodeShape) -> int:
+    n = int(load_library().peagle_draft_decode_workspace_bytes(shape.c()))
+    if n == 0:
+        raise PeagleError(-3, "peagle_draft_decode_workspace_bytes")
+    return n
+
+
+def peagle_draft_decode(shape: DecodeShape, q_new, k_new, v_new, k_pages, v_pages, block_table, ctx_len, o, lse,
+                        status, workspace, stream=None) -> None:
+    import torch
+    bf, f32, i32 = torch.bfloat16, torch.float32, torch.int32
+    s = shape
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
+    pool = (s.n_pages, s.Hkv, 64, s.D)
+    rc = load_library().peagle_draft_decode(
+        s.c(), _ptr(q_new, "q_new", bf, (s.C, s.K, s.Hq, s.D)), _ptr(k_new, "k_new", bf, (s.C, s.K, s.Hkv, s.D)),
+        _ptr(v_new, "v_new", bf, (s.C, s.K, s.Hkv, s.D)), _ptr(k_pages, "k_pages", bf, pool),
+        _ptr(v_pages, "v_pages", bf, pool), _ptr(block_table, "block_table", i32, (s.C, s.max_pages)),
+        _ptr(ctx_len, "ctx_len", i32, (s.C,)), _ptr(o, "o", bf, (s.C, s.K, s.Hq, s.D)),
+        _ptr(lse, "lse", f32, (s.C, s.Hq, s.K)), _ptr(status, "status", i32, (s.C,)),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_draft_decode")
 
 
 def peagle_measure_mfma_ceiling(stream=None) -> float:

@@ -312,6 +312,88 @@ extern "C" int peagle_attn_step_rope_profiled(const peagle_tilemap_t* tm, const 
   return timer.collect(profile->ms, profile->launches) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }
 
+namespace {
+
+int check_decode(const peagle_decode_shape_t* s) {
+  if (!s) return PEAGLE_ENULL;
+  if (s->C < 1 || s->K < 1 || s->Hq < 1 || s->Hkv < 1 || s->n_pages < 1 || s->max_pages < 1) return PEAGLE_EINVAL;
+  if (s->Hq % s->Hkv != 0) return PEAGLE_EINVAL;
+  if (!(s->scale > 0.f) || !std::isfinite(s->scale)) return PEAGLE_EINVAL;
+  if (s->D != 64 && s->D != 128) return PEAGLE_EUNSUPPORTED;
+  if ((int64_t)s->K * (s->Hq / s->Hkv) > peagle::kRowsPerTile || s->K > peagle::kKeysPerTile) return PEAGLE_EUNSUPPORTED;
+  if (s->C > 65535 || s->Hkv > 65535) return PEAGLE_EUNSUPPORTED;  // grid dimensions
+  return PEAGLE_OK;
+}
+
+// Pieces each request's context is cut into: enough workgroups to cover the chip a few times over,
+// but at least four pages per piece so that the partial records stay small next to the cache read.
+int decode_splits(const peagle_decode_shape_t* s) {
+  const int64_t want = (1024 + (int64_t)s->C * s->Hkv - 1) / ((int64_t)s->C * s->Hkv);
+  const int64_t most = (s->max_pages + 3) / 4;
+  int64_t n = want < most ? want : most;
+  if (n > 64) n = 64;
+  return (int)(n < 1 ? 1 : n);
+}
+
+struct DecodeWs {
+  size_t o_off, ml_off, total;
+  int rows_pad, n_splits;
+};
+DecodeWs decode_ws(const peagle_decode_shape_t* s) {
+  DecodeWs w;
+  w.n_splits = decode_splits(s);
+  w.rows_pad = (s->K * (s->Hq / s->Hkv) + 31) / 32 * 32;
+  const size_t recs = (size_t)s->C * s->Hkv * w.n_splits;
+  w.o_off = 0;
+  w.ml_off = align256(recs * w.rows_pad * s->D * sizeof(float));
+  w.total = w.ml_off + align256(recs * 3 * w.rows_pad * sizeof(float));
+  return w;
+}
+
+}  // namespace
+
+extern "C" int32_t peagle_draft_decode_splits(const peagle_decode_shape_t* shape) {
+  return check_decode(shape) == PEAGLE_OK ? decode_splits(shape) : -1;
+}
+
+extern "C" size_t peagle_draft_decode_workspace_bytes(const peagle_decode_shape_t* shape) {
+  return check_decode(shape) == PEAGLE_OK ? decode_ws(shape).total : 0;
+}
+
+extern "C" int peagle_draft_decode(const peagle_decode_shape_t* shape, const void* q_new, const void* k_new,
+                                   const void* v_new, const void* k_pages, const void* v_pages,
+                                   const int32_t* block_table, const int32_t* ctx_len, void* o, float* lse,
+                                   int32_t* status, void* workspace, size_t ws_bytes, void* stream) {
+  const int rc = check_decode(shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q_new || !k_new || !v_new || !k_pages || !v_pages || !block_table || !ctx_len || !o || !lse) return PEAGLE_ENULL;
+  const DecodeWs w = decode_ws(shape);
+  if (!workspace || ws_bytes < w.total) return PEAGLE_EWORKSPACE;
+  peagle::DecodeParams p{};
+  p.q_new = (const __bf16*)q_new;
+  p.k_new = (const __bf16*)k_new;
+  p.v_new = (const __bf16*)v_new;
+  p.k_pages = (const __bf16*)k_pages;
+  p.v_pages = (const __bf16*)v_pages;
+  p.block_table = block_table;
+  p.ctx_len = ctx_len;
+  p.o = (__bf16*)o;
+  p.lse = lse;
+  p.status = status;
+  p.part_o = (float*)((char*)workspace + w.o_off);
+  p.part_ml = (float*)((char*)workspace + w.ml_off);
+  p.C = shape->C;
+  p.K = shape->K;
+  p.Hq = shape->Hq;
+  p.Hkv = shape->Hkv;
+  p.n_pages = shape->n_pages;
+  p.max_pages = shape->max_pages;
+  p.n_splits = w.n_splits;
+  p.rows_pad = w.rows_pad;
+  p.c_log2 = shape->scale * 1.4426950408889634f;
+  return peagle::launch_draft_decode(p, shape->D, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+}
+
 extern "C" int peagle_measure_mfma_ceiling(void* stream, float* tflops) {
   if (!tflops) return PEAGLE_ENULL;
   *tflops = 0.f;

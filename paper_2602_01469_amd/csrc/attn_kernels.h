@@ -50,6 +50,26 @@ struct BwdParams {
                             // are turned back to the unrotated inputs' frame before they are stored
 };
 
+// Inference-side drafting step (Sec. 2 of the paper: all K draft positions in one forward pass): the K
+// rows of each request against its paged KV cache plus the K new keys.
+struct DecodeParams {
+  const __bf16* q_new;         // [C, K, Hq, D]
+  const __bf16* k_new;         // [C, K, Hkv, D]
+  const __bf16* v_new;
+  const __bf16* k_pages;       // [n_pages, Hkv, 64, D]
+  const __bf16* v_pages;
+  const int32_t* block_table;  // [C, max_pages] page of each 64-token block of a request's context
+  const int32_t* ctx_len;      // [C] cached tokens per request
+  __bf16* o;                   // [C, K, Hq, D]
+  float* lse;                  // [C, Hq, K]
+  int32_t* status;             // [C] or null: 1 if the request's block table or length was out of range
+  float* part_o;               // workspace [C, Hkv, n_splits, rows_pad, D]: unnormalised partial outputs
+  float* part_ml;              // workspace [C, Hkv, n_splits, 3, rows_pad]: reference max (log2), row sum, flag
+  int C, K, Hq, Hkv, n_pages, max_pages, n_splits, rows_pad;
+  float c_log2;
+};
+hipError_t launch_draft_decode(const DecodeParams& p, int D, hipStream_t stream);
+
 // Optional per-kernel timing: an event pair is recorded around every launch on the launch stream.
 enum KernelKind { kKindFwd = 0, kKindDq = 1, kKindDkDv = 2, kKindReduce = 3, kKindRope = 4, kNumKinds = 5 };
 struct KernelTimer {

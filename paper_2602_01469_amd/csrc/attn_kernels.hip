@@ -1027,6 +1027,182 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* src, __bf16
   }
 }
 
+// =====================================================================================
+// Inference-side drafting step: the K new rows of a request (depth 0 = next-token position, depths
+// 1..K-1 = multi-token positions, all of the anchor that follows the cached context) are the last
+// anchor's rows of the parallel-prediction mask: every cached key is visible, and the new key of
+// depth e is visible to the rows of depth >= e.  One workgroup per (context split, KV head,
+// request); its waves own 32 rows each of the K x (Hq/Hkv) query rows that share the KV head
+// (row = depth * group + head), loop over the split's 64-token pages with the forward's tile
+// routine, and leave an unnormalised partial (reference max, row sum, O) for the combine kernel.
+// The work is bound by reading the cache once; the matrix cores only keep the arithmetic off
+// the critical path.
+// =====================================================================================
+template <int D>
+__global__ __launch_bounds__(256) void draft_decode_kernel(DecodeParams p) {
+  constexpr int kTileBytes = kKeysPerTile * D * 2;
+  constexpr int kBlocks = kTileBytes / 1024;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const int nw = blockDim.x >> 6;
+  const int split = blockIdx.x, kvh = blockIdx.y, c = blockIdx.z;
+  const int group = p.Hq / p.Hkv;
+  const int n_rows = p.K * group;
+
+  // context of this request, clamped to what the block table can describe
+  int n_ctx = p.ctx_len[c];
+  bool bad = n_ctx < 0 || n_ctx > p.max_pages * kKeysPerTile;
+  n_ctx = n_ctx < 0 ? 0 : (n_ctx > p.max_pages * kKeysPerTile ? p.max_pages * kKeysPerTile : n_ctx);
+  const int n_pg = (n_ctx + kKeysPerTile - 1) / kKeysPerTile;
+  const int per = (n_pg + p.n_splits - 1) / p.n_splits;
+  const int p0 = split * per < n_pg ? split * per : n_pg;
+  const int p1 = p0 + per < n_pg ? p0 + per : n_pg;
+  const int n_tiles = (p1 - p0) + (split == 0 ? 1 : 0);  // split 0 also takes the new keys
+
+  const int r = wave * 32 + ln;  // query row of this lane (shared with lane ^ 32)
+  const bool row_ok = r < n_rows;
+  const int depth = row_ok ? r / group : 0, head = kvh * group + (row_ok ? r - depth * group : 0);
+  bf16x8 qf[1][D / 16];
+  {
+    const __bf16* qrow = p.q_new + (((size_t)c * p.K + depth) * p.Hq + head) * D + g * 8;
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) qf[0][st] = as_frag(ld16(qrow + st * 16));
+  }
+
+  // Source of tile `i` for the direct-to-LDS copy.  Rows of a tile that hold no key (tail of the
+  // last page, rows past the K new keys, a page id out of range) are filled from the request's
+  // first new key, which is always present and finite user data: their probabilities are masked
+  // to zero, and zero times a finite value adds nothing.
+  const __bf16* k_fill = p.k_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
+  const __bf16* v_fill = p.v_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
+  const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
+  auto copy_tile = [&](int i, int buf) {
+    const bool is_new = i >= p1 - p0;
+    int page = 0, valid = p.K;
+    if (!is_new) {
+      page = p.block_table[(size_t)c * p.max_pages + p0 + i];
+      valid = n_ctx - (p0 + i) * kKeysPerTile;
+      valid = valid > kKeysPerTile ? kKeysPerTile : valid;
+      if (page < 0 || page >= p.n_pages) {
+        bad = true;
+        valid = 0;
+      }
+    }
+    for (int blk = wave; blk < kBlocks; blk += nw) {
+      const int row = blk * (512 / D) + row_in_blk;
+      const int chunk = (phys ^ swz<D>(row)) << 3;
+      const __bf16 *ks, *vs;
+      if (row >= valid) {
+        ks = k_fill + chunk;
+        vs = v_fill + chunk;
+      } else if (is_new) {
+        ks = k_fill + (size_t)row * p.Hkv * D + chunk;
+        vs = v_fill + (size_t)row * p.Hkv * D + chunk;
+      } else {
+        const size_t off = (((size_t)page * p.Hkv + kvh) * kKeysPerTile + row) * D + chunk;
+        ks = p.k_pages + off;
+        vs = p.v_pages + off;
+      }
+      dma16(ks, lds[buf][0] + blk * 1024);
+      dma16(vs, lds[buf][1] + blk * 1024);
+    }
+    return valid;
+  };
+
+  f32x16 o[1][D / 32];
+  float m[1] = {kNegInit}, lsum[1] = {0.f};
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
+  const NatOff<D> no = nat_offsets<D>(lane);
+  const TrOff<D> to = tr_offsets<D>(lane);
+
+  int valid_cur = 0;
+  if (n_tiles > 0) valid_cur = copy_tile(0, 0);
+  dma_publish();
+  for (int i = 0; i < n_tiles; ++i) {
+    const int buf = i & 1;
+    int valid_nxt = 0;
+    if (i + 1 < n_tiles) valid_nxt = copy_tile(i + 1, buf ^ 1);
+    const bool is_new = i >= p1 - p0;
+    if (!is_new && valid_cur == kKeysPerTile) {
+      const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+      fwd_tile<D, 1, false, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+    } else {
+      // keys [0, n) of the tile are visible: n = the page's valid tokens, or depth + 1 of the new keys
+      const int n = is_new ? depth + 1 : valid_cur;
+      const uint64_t bits = n >= 64 ? ~0ull : ((1ull << n) - 1);
+      const uint32_t mw[2] = {(uint32_t)bits >> (4 * g), (uint32_t)(bits >> 32) >> (4 * g)};
+      fwd_tile<D, 1, true, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
+    }
+    dma_publish();
+    valid_cur = valid_nxt;
+  }
+
+  // partial record of this split: lane <-> row, registers <-> d = db*32 + 8*q4 + 4g + j
+  const float l_tot = sum_halves(lsum[0]);
+  const size_t rec = ((size_t)c * p.Hkv + kvh) * p.n_splits + split;
+  if (r < p.rows_pad) {
+    float* po = p.part_o + (rec * p.rows_pad + r) * D;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 a;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = o[0][db][4 * q4 + j];
+        *reinterpret_cast<f32x4*>(po + db * 32 + 8 * q4 + 4 * g) = a;
+      }
+    if (g == 0) {
+      float* ml = p.part_ml + rec * 3 * p.rows_pad;
+      ml[r] = m[0];
+      ml[p.rows_pad + r] = l_tot;
+      ml[2 * p.rows_pad + r] = bad ? 1.f : 0.f;
+    }
+  }
+}
+
+// Merges the splits of a request's rows: M = max m_s, L = sum l_s 2^(m_s - M), O = sum O_s 2^(m_s - M) / L.
+// One thread per (request, KV head, row, 4 features).
+template <int D>
+__global__ __launch_bounds__(256) void draft_decode_combine_kernel(DecodeParams p) {
+  const int group = p.Hq / p.Hkv;
+  const int n_rows = p.K * group;
+  const size_t n = (size_t)p.C * p.Hkv * n_rows * (D / 4);
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+    const int c4 = (int)(idx % (D / 4));
+    size_t rem = idx / (D / 4);
+    const int r = (int)(rem % n_rows);
+    rem /= n_rows;
+    const int kvh = (int)(rem % p.Hkv);
+    const int c = (int)(rem / p.Hkv);
+    const size_t rec0 = ((size_t)c * p.Hkv + kvh) * p.n_splits;
+    float M = kNegInit;
+    for (int s = 0; s < p.n_splits; ++s) M = __builtin_fmaxf(M, p.part_ml[(rec0 + s) * 3 * p.rows_pad + r]);
+    float L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < p.n_splits; ++s) {
+      const float* ml = p.part_ml + (rec0 + s) * 3 * p.rows_pad;
+      const float w = exp2_fast(ml[r] - M);
+      L = __builtin_fmaf(ml[p.rows_pad + r], w, L);
+      acc += *reinterpret_cast<const f32x4*>(p.part_o + ((rec0 + s) * p.rows_pad + r) * D + c4 * 4) * w;
+    }
+    const float inv = 1.0f / L;
+    const int depth = r / group, head = kvh * group + (r - depth * group);
+    u32x2 w2;
+    w2[0] = pack_bf16(acc[0] * inv, acc[1] * inv);
+    w2[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
+    *reinterpret_cast<u32x2*>(p.o + (((size_t)c * p.K + depth) * p.Hq + head) * D + c4 * 4) = w2;
+    if (c4 == 0) p.lse[((size_t)c * p.Hq + head) * p.K + depth] = (M + __builtin_log2f(L)) * kLn2;
+    if (p.status && c4 == 0 && r == 0 && kvh == 0) {  // one writer per request: any workgroup of it that met a bad entry
+      float flag = 0.f;
+      for (int w = 0; w < p.Hkv * p.n_splits; ++w)
+        flag = __builtin_fmaxf(flag, p.part_ml[(((size_t)c * p.Hkv * p.n_splits) + w) * 3 * p.rows_pad + 2 * p.rows_pad]);
+      p.status[c] = flag != 0.f ? 1 : 0;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------- launchers
 
 // Pure MFMA issue loop (no memory traffic): four independent accumulator chains per wave,
@@ -1202,6 +1378,20 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
     }
   }
   return hipSuccess;
+}
+
+hipError_t launch_draft_decode(const DecodeParams& p, int D, hipStream_t stream) {
+  const dim3 grid((unsigned)p.n_splits, (unsigned)p.Hkv, (unsigned)p.C), block((unsigned)(p.rows_pad / 32 * 64));
+  if (D == 64) hipLaunchKernelGGL((draft_decode_kernel<64>), grid, block, 0, stream, p);
+  else hipLaunchKernelGGL((draft_decode_kernel<128>), grid, block, 0, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t n = (size_t)p.C * p.Hkv * p.K * (p.Hq / p.Hkv) * (D / 4);
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  if (D == 64) hipLaunchKernelGGL((draft_decode_combine_kernel<64>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL((draft_decode_combine_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
 }
 
 hipError_t launch_cast_bf16(const float* src, void* dst, size_t n, hipStream_t stream) {

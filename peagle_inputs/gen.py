@@ -133,3 +133,45 @@ def useful_pairs_sampled(depth_count) -> int:
     n = np.asarray(depth_count, dtype=np.int64)
     i = np.arange(len(n), dtype=np.int64)
     return int((n * (i + 1) + n * (n - 1) // 2).sum())
+
+
+PAGE_TOKENS = 64
+
+
+def make_decode_inputs(ctx_lens, K: int, Hq: int, Hkv: int, D: int, seed: int, spare_pages: int = 3,
+                       value_scale: float = 1.0):
+    """Inputs of one inference-side drafting step for C = len(ctx_lens) requests (the serving setting of the
+    paper: K = 3, 5, 7 draft positions, concurrency 2-4).  Returns bf16 bit patterns:
+
+      q_new [C, K, Hq, D], k_new / v_new [C, K, Hkv, D];
+      k_ctx / v_ctx: per request, [n_c, Hkv, D] (what the oracle reads);
+      k_pages / v_pages [n_pages, Hkv, 64, D], block_table [C, max_pages] int32, ctx_len [C] int32
+      (what the HIP path reads: the same context tokens scattered over a shuffled page pool; unused
+      table entries are -1 and the unused tail of every last page holds NaN bit patterns, as
+      uninitialised cache memory might).
+    """
+    rng = np.random.default_rng(seed)
+    C = len(ctx_lens)
+    draw = lambda shape: f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(value_scale))
+    q_new, k_new, v_new = draw((C, K, Hq, D)), draw((C, K, Hkv, D)), draw((C, K, Hkv, D))
+    k_ctx = [draw((int(n), Hkv, D)) for n in ctx_lens]
+    v_ctx = [draw((int(n), Hkv, D)) for n in ctx_lens]
+    pages_of = [(int(n) + PAGE_TOKENS - 1) // PAGE_TOKENS for n in ctx_lens]
+    max_pages = max(1, max(pages_of))
+    n_pages = max(1, sum(pages_of) + spare_pages)
+    perm = rng.permutation(n_pages)
+    k_pages = np.full((n_pages, Hkv, PAGE_TOKENS, D), 0x7FC0, dtype=np.uint16)   # bf16 NaN
+    v_pages = np.full((n_pages, Hkv, PAGE_TOKENS, D), 0x7FC0, dtype=np.uint16)
+    block_table = np.full((C, max_pages), -1, dtype=np.int32)
+    nxt = 0
+    for c, n in enumerate(ctx_lens):
+        for b in range(pages_of[c]):
+            page = int(perm[nxt])
+            nxt += 1
+            block_table[c, b] = page
+            lo, hi = b * PAGE_TOKENS, min(int(n), (b + 1) * PAGE_TOKENS)
+            k_pages[page, :, :hi - lo] = k_ctx[c][lo:hi].transpose(1, 0, 2)
+            v_pages[page, :, :hi - lo] = v_ctx[c][lo:hi].transpose(1, 0, 2)
+    return {"q_new": q_new, "k_new": k_new, "v_new": v_new, "k_ctx": k_ctx, "v_ctx": v_ctx, "k_pages": k_pages,
+            "v_pages": v_pages, "block_table": block_table, "ctx_len": np.asarray(ctx_lens, dtype=np.int32),
+            "n_pages": n_pages, "max_pages": max_pages}

@@ -547,3 +547,44 @@ def test_rope_entry_points_validate_before_launch():
     assert step(ws=pe.peagle_workspace_bytes(tm, ok)) == -6      # the plain workspace is too small
     assert step(seg=(2, 1)) == -1
     assert step() == -8
+
+
+# ----------------------------------------------------------------------------- inference-side drafting: host side
+
+def test_draft_decode_validates_before_launch():
+    lib = pe.load_library()
+    one = C.c_void_p(16)  # never dereferenced: validation fails first
+
+    def call(shape, q=one, ws=one, ws_bytes=1 << 40):
+        return lib.peagle_draft_decode(shape.c(), q, one, one, one, one, one, one, one, one, None, ws, ws_bytes, None)
+
+    ok = pe.DecodeShape(4, 7, 64, 8, 64, 100, 20)
+    assert call(pe.DecodeShape(0, 7, 64, 8, 64, 100, 20)) == -1
+    assert call(pe.DecodeShape(4, 7, 64, 6, 64, 100, 20)) == -1          # Hq % Hkv
+    assert call(pe.DecodeShape(4, 7, 64, 8, 96, 100, 20)) == -5          # head_dim
+    assert call(pe.DecodeShape(4, 7, 64, 2, 64, 100, 20)) == -5          # K * group > 128 rows
+    assert call(pe.DecodeShape(4, 7, 64, 8, 64, 100, 20, scale=0.0)) == -1
+    assert call(pe.DecodeShape(4, 7, 64, 8, 64, 0, 20)) == -1
+    assert call(ok, q=None) == -2
+    assert call(ok, ws=None) == -6
+    assert call(ok, ws_bytes=pe.peagle_draft_decode_workspace_bytes(ok) - 1) == -6
+    assert lib.peagle_draft_decode_workspace_bytes(pe.DecodeShape(4, 7, 64, 8, 96, 100, 20).c()) == 0
+    assert pe.peagle_draft_decode_splits(pe.DecodeShape(4, 7, 64, 8, 96, 100, 20)) == -1
+    # split count: at least four pages per piece, never more than 64 pieces, at least one
+    assert pe.peagle_draft_decode_splits(ok) == 5
+    assert pe.peagle_draft_decode_splits(pe.DecodeShape(1, 3, 8, 8, 64, 10, 1)) == 1
+    assert pe.peagle_draft_decode_splits(pe.DecodeShape(2, 3, 8, 1, 64, 5000, 4000)) == 64
+    assert pe.peagle_draft_decode_splits(pe.DecodeShape(512, 3, 8, 8, 64, 5000, 4000)) == 1
+
+
+def test_decode_input_generator_scatters_the_context_over_pages():
+    from peagle_inputs import PAGE_TOKENS, make_decode_inputs
+    inp = make_decode_inputs([0, 1, 64, 65, 200], K=3, Hq=4, Hkv=2, D=64, seed=9)
+    assert PAGE_TOKENS == 64 and inp["max_pages"] == 4 and inp["n_pages"] == 0 + 1 + 1 + 2 + 4 + 3
+    used = inp["block_table"][inp["block_table"] >= 0]
+    assert len(set(used.tolist())) == len(used) == 8                     # every block has a page of its own
+    for c, n in enumerate(inp["ctx_len"]):
+        for t in range(int(n)):
+            page = inp["block_table"][c, t // 64]
+            assert np.array_equal(inp["k_pages"][page, :, t % 64], inp["k_ctx"][c][t])
+            assert np.array_equal(inp["v_pages"][page, :, t % 64], inp["v_ctx"][c][t])
