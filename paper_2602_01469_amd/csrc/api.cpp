@@ -331,7 +331,7 @@ int decode_splits(const peagle_decode_shape_t* s) {
   const int64_t want = (1024 + (int64_t)s->C * s->Hkv - 1) / ((int64_t)s->C * s->Hkv);
   const int64_t most = (s->max_pages + 3) / 4;
   int64_t n = want < most ? want : most;
-  if (n > 64) n = 64;
+  if (n > 32) n = 32;
   return (int)(n < 1 ? 1 : n);
 }
 

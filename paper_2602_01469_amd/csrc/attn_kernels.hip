@@ -1039,13 +1039,17 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* src, __bf16
 // the critical path.
 // =====================================================================================
 template <int D>
-__global__ __launch_bounds__(256) void draft_decode_kernel(DecodeParams p) {
+__global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   constexpr int kBlocks = kTileBytes / 1024;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
 
+  // The last wave of the workgroup only copies (global -> LDS), the others only compute.  The wait for
+  // a copy is counted per wave, so the computing waves never wait on one and the copy of tile i+1 is in
+  // flight for the whole of tile i's arithmetic; one workgroup barrier per tile hands buffers over.
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
-  const int nw = blockDim.x >> 6;
+  const int n_compute = (blockDim.x >> 6) - 1;
+  const bool producer = wave == n_compute;
   const int split = blockIdx.x, kvh = blockIdx.y, c = blockIdx.z;
   const int group = p.Hq / p.Hkv;
   const int n_rows = p.K * group;
@@ -1060,6 +1064,59 @@ __global__ __launch_bounds__(256) void draft_decode_kernel(DecodeParams p) {
   const int p1 = p0 + per < n_pg ? p0 + per : n_pg;
   const int n_tiles = (p1 - p0) + (split == 0 ? 1 : 0);  // split 0 also takes the new keys
 
+  // Tile i of this split: a cache page (keys [0, valid) of it exist) or, last in split 0, the K new keys.
+  // A page id outside the pool makes the tile empty and flags the request.
+  auto tile_info = [&](int i, int& page, bool& is_new) {
+    is_new = i >= p1 - p0;
+    page = 0;
+    if (is_new) return p.K;
+    page = p.block_table[(size_t)c * p.max_pages + p0 + i];
+    int valid = n_ctx - (p0 + i) * kKeysPerTile;
+    valid = valid > kKeysPerTile ? kKeysPerTile : valid;
+    if (page < 0 || page >= p.n_pages) {
+      bad = true;
+      valid = 0;
+    }
+    return valid;
+  };
+
+  if (producer) {
+    // Rows of a tile that hold no key (tail of the last page, rows past the K new keys, an empty tile)
+    // are filled from the request's first new key, which is always present and finite user data: their
+    // probabilities are masked to zero, and zero times a finite value adds nothing.
+    const __bf16* k_fill = p.k_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
+    const __bf16* v_fill = p.v_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
+    const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
+    for (int i = 0; i < n_tiles; ++i) {
+      int page;
+      bool is_new;
+      const int valid = tile_info(i, page, is_new);
+      const int buf = i & 1;
+#pragma unroll 4
+      for (int blk = 0; blk < kBlocks; ++blk) {
+        const int row = blk * (512 / D) + row_in_blk;
+        const int chunk = (phys ^ swz<D>(row)) << 3;
+        const __bf16 *ks, *vs;
+        if (row >= valid) {
+          ks = k_fill + chunk;
+          vs = v_fill + chunk;
+        } else if (is_new) {
+          ks = k_fill + (size_t)row * p.Hkv * D + chunk;
+          vs = v_fill + (size_t)row * p.Hkv * D + chunk;
+        } else {
+          const size_t off = (((size_t)page * p.Hkv + kvh) * kKeysPerTile + row) * D + chunk;
+          ks = p.k_pages + off;
+          vs = p.v_pages + off;
+        }
+        dma16(ks, lds[buf][0] + blk * 1024);
+        dma16(vs, lds[buf][1] + blk * 1024);
+      }
+      dma_publish();  // tile i has landed; the computing waves are done with tile i-1, whose buffer is next
+    }
+    if (n_tiles == 0) __syncthreads();
+    return;  // barriers executed: max(n_tiles, 1), the same as the computing waves below
+  }
+
   const int r = wave * 32 + ln;  // query row of this lane (shared with lane ^ 32)
   const bool row_ok = r < n_rows;
   const int depth = row_ok ? r / group : 0, head = kvh * group + (row_ok ? r - depth * group : 0);
@@ -1069,47 +1126,6 @@ __global__ __launch_bounds__(256) void draft_decode_kernel(DecodeParams p) {
 #pragma unroll
     for (int st = 0; st < D / 16; ++st) qf[0][st] = as_frag(ld16(qrow + st * 16));
   }
-
-  // Source of tile `i` for the direct-to-LDS copy.  Rows of a tile that hold no key (tail of the
-  // last page, rows past the K new keys, a page id out of range) are filled from the request's
-  // first new key, which is always present and finite user data: their probabilities are masked
-  // to zero, and zero times a finite value adds nothing.
-  const __bf16* k_fill = p.k_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
-  const __bf16* v_fill = p.v_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
-  const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
-  auto copy_tile = [&](int i, int buf) {
-    const bool is_new = i >= p1 - p0;
-    int page = 0, valid = p.K;
-    if (!is_new) {
-      page = p.block_table[(size_t)c * p.max_pages + p0 + i];
-      valid = n_ctx - (p0 + i) * kKeysPerTile;
-      valid = valid > kKeysPerTile ? kKeysPerTile : valid;
-      if (page < 0 || page >= p.n_pages) {
-        bad = true;
-        valid = 0;
-      }
-    }
-    for (int blk = wave; blk < kBlocks; blk += nw) {
-      const int row = blk * (512 / D) + row_in_blk;
-      const int chunk = (phys ^ swz<D>(row)) << 3;
-      const __bf16 *ks, *vs;
-      if (row >= valid) {
-        ks = k_fill + chunk;
-        vs = v_fill + chunk;
-      } else if (is_new) {
-        ks = k_fill + (size_t)row * p.Hkv * D + chunk;
-        vs = v_fill + (size_t)row * p.Hkv * D + chunk;
-      } else {
-        const size_t off = (((size_t)page * p.Hkv + kvh) * kKeysPerTile + row) * D + chunk;
-        ks = p.k_pages + off;
-        vs = p.v_pages + off;
-      }
-      dma16(ks, lds[buf][0] + blk * 1024);
-      dma16(vs, lds[buf][1] + blk * 1024);
-    }
-    return valid;
-  };
-
   f32x16 o[1][D / 32];
   float m[1] = {kNegInit}, lsum[1] = {0.f};
 #pragma unroll
@@ -1117,26 +1133,23 @@ __global__ __launch_bounds__(256) void draft_decode_kernel(DecodeParams p) {
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
 
-  int valid_cur = 0;
-  if (n_tiles > 0) valid_cur = copy_tile(0, 0);
-  dma_publish();
+  __syncthreads();  // tile 0 has landed (or there is none)
   for (int i = 0; i < n_tiles; ++i) {
     const int buf = i & 1;
-    int valid_nxt = 0;
-    if (i + 1 < n_tiles) valid_nxt = copy_tile(i + 1, buf ^ 1);
-    const bool is_new = i >= p1 - p0;
-    if (!is_new && valid_cur == kKeysPerTile) {
+    int page;
+    bool is_new;
+    const int valid = tile_info(i, page, is_new);
+    if (!is_new && valid == kKeysPerTile) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       fwd_tile<D, 1, false, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
     } else {
       // keys [0, n) of the tile are visible: n = the page's valid tokens, or depth + 1 of the new keys
-      const int n = is_new ? depth + 1 : valid_cur;
+      const int n = is_new ? depth + 1 : valid;
       const uint64_t bits = n >= 64 ? ~0ull : ((1ull << n) - 1);
       const uint32_t mw[2] = {(uint32_t)bits >> (4 * g), (uint32_t)(bits >> 32) >> (4 * g)};
       fwd_tile<D, 1, true, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
     }
-    dma_publish();
-    valid_cur = valid_nxt;
+    if (i + 1 < n_tiles) __syncthreads();  // tile i+1 has landed, and tile i's buffer may be refilled
   }
 
   // partial record of this split: lane <-> row, registers <-> d = db*32 + 8*q4 + 4g + j
@@ -1163,9 +1176,12 @@ __global__ __launch_bounds__(256) void draft_decode_kernel(DecodeParams p) {
 }
 
 // Merges the splits of a request's rows: M = max m_s, L = sum l_s 2^(m_s - M), O = sum O_s 2^(m_s - M) / L.
-// One thread per (request, KV head, row, 4 features).
+// One thread per (request, KV head, row, 4 features).  The loads of a batch of splits are issued
+// together (the loops are unrolled in batches with clamped indices): a thread's time is a few memory
+// round trips, not one per split.  Block 0 also sets the per-request status words, a wave per request.
 template <int D>
 __global__ __launch_bounds__(256) void draft_decode_combine_kernel(DecodeParams p) {
+  constexpr int kBatch = 8;
   const int group = p.Hq / p.Hkv;
   const int n_rows = p.K * group;
   const size_t n = (size_t)p.C * p.Hkv * n_rows * (D / 4);
@@ -1177,15 +1193,37 @@ __global__ __launch_bounds__(256) void draft_decode_combine_kernel(DecodeParams 
     const int kvh = (int)(rem % p.Hkv);
     const int c = (int)(rem / p.Hkv);
     const size_t rec0 = ((size_t)c * p.Hkv + kvh) * p.n_splits;
+    const float* ml0 = p.part_ml + rec0 * 3 * p.rows_pad + r;
+    const float* o0 = p.part_o + (rec0 * p.rows_pad + r) * D + c4 * 4;
     float M = kNegInit;
-    for (int s = 0; s < p.n_splits; ++s) M = __builtin_fmaxf(M, p.part_ml[(rec0 + s) * 3 * p.rows_pad + r]);
+    for (int s0 = 0; s0 < p.n_splits; s0 += kBatch) {
+      float mv[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int s = s0 + j < p.n_splits ? s0 + j : p.n_splits - 1;
+        mv[j] = ml0[(size_t)s * 3 * p.rows_pad];
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) M = __builtin_fmaxf(M, mv[j]);
+    }
     float L = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < p.n_splits; ++s) {
-      const float* ml = p.part_ml + (rec0 + s) * 3 * p.rows_pad;
-      const float w = exp2_fast(ml[r] - M);
-      L = __builtin_fmaf(ml[p.rows_pad + r], w, L);
-      acc += *reinterpret_cast<const f32x4*>(p.part_o + ((rec0 + s) * p.rows_pad + r) * D + c4 * 4) * w;
+    for (int s0 = 0; s0 < p.n_splits; s0 += kBatch) {
+      float mv[kBatch], lv[kBatch];
+      f32x4 ov[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int s = s0 + j < p.n_splits ? s0 + j : p.n_splits - 1;
+        mv[j] = ml0[(size_t)s * 3 * p.rows_pad];
+        lv[j] = ml0[(size_t)s * 3 * p.rows_pad + p.rows_pad];
+        ov[j] = *reinterpret_cast<const f32x4*>(o0 + (size_t)s * p.rows_pad * D);
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const float w = s0 + j < p.n_splits ? exp2_fast(mv[j] - M) : 0.f;
+        L = __builtin_fmaf(lv[j], w, L);
+        acc += ov[j] * w;
+      }
     }
     const float inv = 1.0f / L;
     const int depth = r / group, head = kvh * group + (r - depth * group);
@@ -1194,11 +1232,17 @@ __global__ __launch_bounds__(256) void draft_decode_combine_kernel(DecodeParams 
     w2[1] = pack_bf16(acc[2] * inv, acc[3] * inv);
     *reinterpret_cast<u32x2*>(p.o + (((size_t)c * p.K + depth) * p.Hq + head) * D + c4 * 4) = w2;
     if (c4 == 0) p.lse[((size_t)c * p.Hq + head) * p.K + depth] = (M + __builtin_log2f(L)) * kLn2;
-    if (p.status && c4 == 0 && r == 0 && kvh == 0) {  // one writer per request: any workgroup of it that met a bad entry
-      float flag = 0.f;
-      for (int w = 0; w < p.Hkv * p.n_splits; ++w)
-        flag = __builtin_fmaxf(flag, p.part_ml[(((size_t)c * p.Hkv * p.n_splits) + w) * 3 * p.rows_pad + 2 * p.rows_pad]);
-      p.status[c] = flag != 0.f ? 1 : 0;
+  }
+  if (p.status && blockIdx.x == 0) {
+    // a request is flagged if any of its workgroups met a bad block-table entry or length
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nwv = blockDim.x >> 6;
+    const int per_req = p.Hkv * p.n_splits;
+    for (int c = wave; c < p.C; c += nwv) {
+      bool any = false;
+      for (int w = lane; w < per_req; w += 64)
+        any |= p.part_ml[((size_t)c * per_req + w) * 3 * p.rows_pad + 2 * p.rows_pad] != 0.f;
+      const bool flagged = __builtin_amdgcn_ballot_w64(any) != 0;
+      if (lane == 0) p.status[c] = flagged ? 1 : 0;
     }
   }
 }
@@ -1381,7 +1425,8 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
 }
 
 hipError_t launch_draft_decode(const DecodeParams& p, int D, hipStream_t stream) {
-  const dim3 grid((unsigned)p.n_splits, (unsigned)p.Hkv, (unsigned)p.C), block((unsigned)(p.rows_pad / 32 * 64));
+  // one computing wave per 32 query rows, plus the wave that copies
+  const dim3 grid((unsigned)p.n_splits, (unsigned)p.Hkv, (unsigned)p.C), block((unsigned)((p.rows_pad / 32 + 1) * 64));
   if (D == 64) hipLaunchKernelGGL((draft_decode_kernel<64>), grid, block, 0, stream, p);
   else hipLaunchKernelGGL((draft_decode_kernel<128>), grid, block, 0, stream, p);
   hipError_t e = hipGetLastError();

@@ -107,3 +107,27 @@ def test_draft_decode_flags_a_block_table_that_points_outside_the_pool():
     ro, rl = _oracle(inp, 0, r.shape.scale)
     assert rel_l2(o[0], ro) <= FWD_REL and max_abs(lse[0], rl) <= LSE_ABS
     assert np.isfinite(lse[1]).all()
+
+
+def test_draft_decode_replays_from_a_hip_graph():
+    """The call allocates nothing and clears nothing with a memset, so a serving loop can capture it: every
+    replay (with new queries written between replays) must equal the eager result bit for bit."""
+    print("case decode graph replay", flush=True)
+    inp = make_decode_inputs((1500, 70, 640), 5, 16, 2, 64, 1120)
+    r = DecodeRun(inp, 5, 16, 2, 64)
+    r.run()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pe.peagle_draft_decode(r.shape, r.q, r.k, r.v, r.kp, r.vp, r.bt, r.cl, r.o, r.lse, r.status, r.ws,
+                               torch.cuda.current_stream())
+    for rep in range(3):
+        r.q.copy_(to_dev_bf16(make_decode_inputs((1500, 70, 640), 5, 16, 2, 64, 1130 + rep)["q_new"]))
+        r.o.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        o_graph, lse_graph = r.o.clone(), r.lse.clone()
+        o_eager, lse_eager, _ = r.run()
+        assert np.array_equal(bf16_to_f64(o_graph), o_eager), rep
+        assert np.array_equal(lse_graph.double().cpu().numpy(), lse_eager), rep

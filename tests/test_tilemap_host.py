@@ -570,10 +570,10 @@ def test_draft_decode_validates_before_launch():
     assert call(ok, ws_bytes=pe.peagle_draft_decode_workspace_bytes(ok) - 1) == -6
     assert lib.peagle_draft_decode_workspace_bytes(pe.DecodeShape(4, 7, 64, 8, 96, 100, 20).c()) == 0
     assert pe.peagle_draft_decode_splits(pe.DecodeShape(4, 7, 64, 8, 96, 100, 20)) == -1
-    # split count: at least four pages per piece, never more than 64 pieces, at least one
+    # split count: at least four pages per piece, never more than 32 pieces, at least one
     assert pe.peagle_draft_decode_splits(ok) == 5
     assert pe.peagle_draft_decode_splits(pe.DecodeShape(1, 3, 8, 8, 64, 10, 1)) == 1
-    assert pe.peagle_draft_decode_splits(pe.DecodeShape(2, 3, 8, 1, 64, 5000, 4000)) == 64
+    assert pe.peagle_draft_decode_splits(pe.DecodeShape(2, 3, 8, 1, 64, 5000, 4000)) == 32
     assert pe.peagle_draft_decode_splits(pe.DecodeShape(512, 3, 8, 8, 64, 5000, 4000)) == 1
 
 
