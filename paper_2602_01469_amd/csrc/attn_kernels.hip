@@ -23,6 +23,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kRescaleThreshold = 8.0f;  // log2 units: the running reference max lags by at most 2^8
 constexpr float kNegInit = -1.0e30f;
+// Bits of a 32-key mask word (already shifted right by 4g) that belong to the keys a lane holds in the
+// C layout of a transposed score block: keys 8*(i/4) + 4g + i%4, i = 0..15.
+constexpr uint32_t kLaneKeyBits = 0x0f0f0f0fu;
 
 // Token (row of the [T, H, D] tensors) of key `row` of key tile `kt`; false if that key does not
 // exist in a length-L problem.
@@ -192,6 +195,11 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
   dma4(ok ? (const void*)(base + (size_t)h * T + t.stat_tok) : tm.zeros, reinterpret_cast<char*>(lds_stat + half * 64));
 }
 
+// Does any row of the wave see a key of the 32-key block whose (shifted) mask word each lane holds?
+__device__ __forceinline__ bool wave_sees_block(uint32_t mw) {
+  return __builtin_amdgcn_ballot_w64((mw & kLaneKeyBits) != 0) != 0;
+}
+
 // Bit `pos` of w selects x, otherwise -inf.
 __device__ __forceinline__ float mask_sel(float x, uint32_t w, int pos) {
   return ((w >> pos) & 1u) ? x : -__builtin_inff();
@@ -245,12 +253,12 @@ __device__ __forceinline__ void softmax_block(f32x16& s, uint32_t mw, float c, f
 // (row tile, NH query heads of one KV group); wave w owns rows [32w, 32w+32) of the tile.
 // K/V tiles are staged once in LDS per workgroup and serve all NH heads.
 // =====================================================================================
-template <int D, int NH, bool MASKED, bool SAFE>
+template <int D, int NH, bool MASKED, bool SAFE, int KB0 = 0, int KB1 = 2>
 __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds, const NatOff<D>& no, const TrOff<D>& to,
                                          const bf16x8 (&qf)[NH][D / 16], f32x16 (&o)[NH][D / 32], float (&m)[NH],
                                          float (&lsum)[NH], const uint32_t (&mw)[2], float c) {
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
+  for (int kb = KB0; kb < KB1; ++kb) {  // the tile's 32-key blocks [KB0, KB1)
     // S^T block: 32 keys x 32 rows, lane <-> row, registers <-> keys 8*(i/4) + 4g + i%4
     f32x16 s[NH];
 #pragma unroll
@@ -405,13 +413,13 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
 // Backward, part 1: Delta = rowsum(dO * O) and dQ = scale * dS K, row-tile owned (same
 // decomposition as the forward).  Writes Delta [Hq, T] for part 2.
 // =====================================================================================
-template <int D, int NH, bool MASKED>
+template <int D, int NH, bool MASKED, int KB0 = 0, int KB1 = 2>
 __device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, const NatOff<D>& no, const TrOff<D>& to,
                                         const bf16x8 (&qf)[NH][D / 16], const bf16x8 (&dof)[NH][D / 16],
                                         f32x16 (&dq)[NH][D / 32], const float (&lse2)[NH], const float (&delta)[NH],
                                         const uint32_t (&mw)[2], float c) {
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
+  for (int kb = KB0; kb < KB1; ++kb) {
     f32x16 s[NH], dp[NH];
 #pragma unroll
     for (int hh = 0; hh < NH; ++hh) {
@@ -538,7 +546,15 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     } else {
       const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)cur.mask_id * kRowsPerTile + r) * 2);
       const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
-      dq_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
+      // A 32-key block that none of the wave's 32 rows can see contributes exact zeros and is left out:
+      // half of a row tile's chain keys are deeper than a given wave's rows, and the second half of a
+      // diagonal depth-0 tile is often in the future of the whole row tile.
+      // (The forward does not do this: at two heads per workgroup it has no registers to spare, and a
+      // second code path there spills.)
+      const bool see0 = wave_sees_block(mw[0]), see1 = wave_sees_block(mw[1]);
+      if (see0 && see1) dq_tile<D, NH, true>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
+      else if (see0) dq_tile<D, NH, true, 0, 1>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
+      else if (see1) dq_tile<D, NH, true, 1, 2>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     }
     dma_publish();
     cur = nxt;
