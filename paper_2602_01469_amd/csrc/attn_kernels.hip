@@ -182,7 +182,7 @@ __device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base,
   for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
     const bool ok = t.tok[i] >= 0;
     const size_t off = ((size_t)(ok ? t.tok[i] : 0) * Hq + h) * D + rl.chunk[i];
-    dma16(ok ? (const void*)(base + off) : tm.zeros, lds_tile + (i * NW + wave) * 1024);
+    dma16_untracked(ok ? (const void*)(base + off) : tm.zeros, lds_tile + (i * NW + wave) * 1024);
   }
 }
 
@@ -192,7 +192,8 @@ template <int D, int NW>
 __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base, int T, int h, const DeviceTileMap& tm,
                                              const RowTokens<D, NW>& t, int half) {
   const bool ok = t.stat_tok >= 0;
-  dma4(ok ? (const void*)(base + (size_t)h * T + t.stat_tok) : tm.zeros, reinterpret_cast<char*>(lds_stat + half * 64));
+  dma4_untracked(ok ? (const void*)(base + (size_t)h * T + t.stat_tok) : tm.zeros,
+                 reinterpret_cast<char*>(lds_stat + half * 64));
 }
 
 // Does any row of the wave see a key of the 32-key block whose (shifted) mask word each lane holds?

@@ -126,6 +126,26 @@ __device__ __forceinline__ void dma4(const void* gsrc, char* lds_wave_base) {
                                    PEAGLE_LDS_PTR(void, lds_wave_base), 4, 0, 0);
 }
 
+// The same two copies issued through an assembly statement.  The compiler counts a copy made with the
+// builtin as an outstanding memory access of unknown LDS destination and makes the wave wait for ALL of
+// them before its next LDS read, whichever buffer that read touches; a kernel that issues the next
+// tile's copy and then computes on the current one so stalls for the copy's whole latency unless another
+// workgroup fills the gap.  Issued this way the copy is invisible to that bookkeeping (the hardware
+// counter still counts it, so the compiler's own waits can only become longer, never too short), and the
+// caller alone orders it: nothing may read or overwrite the destination before dma_publish().  M0 carries
+// the LDS address, as it does for the builtin; it is declared clobbered.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // "clobber list contains reserved registers: m0": intended, see above
+__device__ __forceinline__ void dma16_untracked(const void* gsrc, char* lds_wave_base) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)PEAGLE_LDS_PTR(char, lds_wave_base));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gsrc), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4_untracked(const void* gsrc, char* lds_wave_base) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)PEAGLE_LDS_PTR(char, lds_wave_base));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(gsrc), "s"(lds_addr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 // Wait until every global -> LDS copy this wave has issued has landed (vmcnt(0)), then
 // synchronise the workgroup: after it, all waves may read what any wave copied, and the buffers
 // read before it may be overwritten.  The wait is explicit because a workgroup barrier by itself
