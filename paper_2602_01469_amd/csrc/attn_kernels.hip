@@ -90,14 +90,15 @@ __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __b
   constexpr int kBlocks = kKeysPerTile * D * 2 / 1024;
   static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
   const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
+  const uint32_t kd = lds_scalar_addr(k_lds + wave * 1024), vd = lds_scalar_addr(v_lds + wave * 1024);
   if (kt < tm.n_d0 && (kt + 1) * kKeysPerTile <= L) {
 #pragma unroll
     for (int i = 0; i < kBlocks / NW; ++i) {
       const int blk = i * NW + wave;
       const int row = blk * (512 / D) + row_in_blk;
       const size_t off = ((size_t)(kt * kKeysPerTile + row) * Hkv + kvh) * D + ((phys ^ swz<D>(row)) << 3);
-      dma16(kbase + off, k_lds + blk * 1024);
-      dma16(vbase + off, v_lds + blk * 1024);
+      dma16_untracked(kbase + off, kd + i * NW * 1024);
+      dma16_untracked(vbase + off, vd + i * NW * 1024);
     }
   } else {
 #pragma unroll
@@ -107,8 +108,8 @@ __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __b
       int tok;
       const bool ok = key_token(tm, kt, row, L, tok);
       const size_t off = ((size_t)(ok ? tok : 0) * Hkv + kvh) * D + ((phys ^ swz<D>(row)) << 3);
-      dma16(ok ? (const void*)(kbase + off) : tm.zeros, k_lds + blk * 1024);
-      dma16(ok ? (const void*)(vbase + off) : tm.zeros, v_lds + blk * 1024);
+      dma16_untracked(ok ? (const void*)(kbase + off) : tm.zeros, kd + i * NW * 1024);
+      dma16_untracked(ok ? (const void*)(vbase + off) : tm.zeros, vd + i * NW * 1024);
     }
   }
 }
@@ -178,11 +179,12 @@ __device__ __forceinline__ RowTokens<D, NW> row_tokens(const DeviceTileMap& tm, 
 template <int D, int NW>
 __device__ __forceinline__ void dma_row_tile(char* lds_tile, const __bf16* base, int Hq, int h, const DeviceTileMap& tm,
                                              const RowDmaLane<D, NW>& rl, const RowTokens<D, NW>& t, int wave) {
+  const uint32_t dst = lds_scalar_addr(lds_tile + wave * 1024);
 #pragma unroll
   for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
     const bool ok = t.tok[i] >= 0;
     const size_t off = ((size_t)(ok ? t.tok[i] : 0) * Hq + h) * D + rl.chunk[i];
-    dma16_untracked(ok ? (const void*)(base + off) : tm.zeros, lds_tile + (i * NW + wave) * 1024);
+    dma16_untracked(ok ? (const void*)(base + off) : tm.zeros, dst + i * NW * 1024);
   }
 }
 
@@ -193,7 +195,7 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
                                              const RowTokens<D, NW>& t, int half) {
   const bool ok = t.stat_tok >= 0;
   dma4_untracked(ok ? (const void*)(base + (size_t)h * T + t.stat_tok) : tm.zeros,
-                 reinterpret_cast<char*>(lds_stat + half * 64));
+                 lds_scalar_addr(reinterpret_cast<const char*>(lds_stat + half * 64)));
 }
 
 // Does any row of the wave see a key of the 32-key block whose (shifted) mask word each lane holds?

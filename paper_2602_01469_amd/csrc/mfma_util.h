@@ -133,15 +133,17 @@ __device__ __forceinline__ void dma4(const void* gsrc, char* lds_wave_base) {
 // workgroup fills the gap.  Issued this way the copy is invisible to that bookkeeping (the hardware
 // counter still counts it, so the compiler's own waits can only become longer, never too short), and the
 // caller alone orders it: nothing may read or overwrite the destination before dma_publish().  M0 carries
-// the LDS address, as it does for the builtin; it is declared clobbered.
+// the LDS address, as it does for the builtin; it is declared clobbered.  The address is passed as a
+// scalar: lds_scalar_addr() of a wave-uniform pointer, plus wave-uniform offsets.
+__device__ __forceinline__ uint32_t lds_scalar_addr(const char* lds_ptr) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)PEAGLE_LDS_PTR(char, lds_ptr));
+}
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // "clobber list contains reserved registers: m0": intended, see above
-__device__ __forceinline__ void dma16_untracked(const void* gsrc, char* lds_wave_base) {
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)PEAGLE_LDS_PTR(char, lds_wave_base));
+__device__ __forceinline__ void dma16_untracked(const void* gsrc, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gsrc), "s"(lds_addr) : "memory", "m0");
 }
-__device__ __forceinline__ void dma4_untracked(const void* gsrc, char* lds_wave_base) {
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)PEAGLE_LDS_PTR(char, lds_wave_base));
+__device__ __forceinline__ void dma4_untracked(const void* gsrc, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(gsrc), "s"(lds_addr) : "memory", "m0");
 }
 #pragma clang diagnostic pop
