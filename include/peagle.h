@@ -308,8 +308,9 @@ int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_s
  *
  * The cache is paged: page = PEAGLE_PAGE_TOKENS (64) consecutive tokens of one request, all KV heads.
  *
- *   shape        C requests, K new positions each, Hq / Hkv heads (Hq % Hkv == 0, K * Hq/Hkv <= 128),
- *                D in {64, 128}, scale > 0, n_pages pages in the pools, max_pages block-table columns
+ *   shape        C requests (<= 65535), K new positions each (<= 64), Hq / Hkv heads (Hq % Hkv == 0,
+ *                K * Hq/Hkv <= 128), D in {64, 128}, scale > 0, n_pages pages in the pools, max_pages
+ *                block-table columns (<= 2^24); anything else: EINVAL / EUNSUPPORTED before any launch
  *   q_new        device, bf16 [C, K, Hq, D]          k_new, v_new  device, bf16 [C, K, Hkv, D]
  *   k_pages, v_pages   device, bf16 [n_pages, Hkv, 64, D]  (the tail of a request's last page may hold
  *                anything: it is never used in arithmetic)

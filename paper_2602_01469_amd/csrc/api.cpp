@@ -322,6 +322,7 @@ int check_decode(const peagle_decode_shape_t* s) {
   if (s->D != 64 && s->D != 128) return PEAGLE_EUNSUPPORTED;
   if ((int64_t)s->K * (s->Hq / s->Hkv) > peagle::kRowsPerTile || s->K > peagle::kKeysPerTile) return PEAGLE_EUNSUPPORTED;
   if (s->C > 65535 || s->Hkv > 65535) return PEAGLE_EUNSUPPORTED;  // grid dimensions
+  if (s->max_pages > (1 << 24)) return PEAGLE_EUNSUPPORTED;          // 64 * max_pages tokens must fit an int
   return PEAGLE_OK;
 }
 

@@ -565,6 +565,8 @@ def test_draft_decode_validates_before_launch():
     assert call(pe.DecodeShape(4, 7, 64, 2, 64, 100, 20)) == -5          # K * group > 128 rows
     assert call(pe.DecodeShape(4, 7, 64, 8, 64, 100, 20, scale=0.0)) == -1
     assert call(pe.DecodeShape(4, 7, 64, 8, 64, 0, 20)) == -1
+    assert call(pe.DecodeShape(4, 7, 64, 8, 64, 100, (1 << 24) + 1)) == -5     # context length would overflow
+    assert call(pe.DecodeShape(70000, 7, 64, 8, 64, 100, 20)) == -5            # more requests than a grid dimension
     assert call(ok, q=None) == -2
     assert call(ok, ws=None) == -6
     assert call(ok, ws_bytes=pe.peagle_draft_decode_workspace_bytes(ok) - 1) == -6
