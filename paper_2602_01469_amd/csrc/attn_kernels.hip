@@ -1057,15 +1057,19 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* src, __bf16
 // The work is bound by reading the cache once; the matrix cores only keep the arithmetic off
 // the critical path.
 // =====================================================================================
-template <int D>
+template <int D, int kRing>
 __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   constexpr int kBlocks = kTileBytes / 1024;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
+  // kRing LDS buffers of one tile (K and V) each: two, or four at D = 64 when a workgroup has many tiles
+  constexpr int kCopiesPerTile = 2 * kBlocks;
+  static_assert((kRing - 2) * kCopiesPerTile <= 63, "the copies in flight behind a tile must fit the hardware's counter");
+  __shared__ __attribute__((aligned(16))) char lds[kRing][2][kTileBytes];  // [buffer][K|V]
 
   // The last wave of the workgroup only copies (global -> LDS), the others only compute.  The wait for
-  // a copy is counted per wave, so the computing waves never wait on one and the copy of tile i+1 is in
-  // flight for the whole of tile i's arithmetic; one workgroup barrier per tile hands buffers over.
+  // a copy is counted per wave and in issue order, so the copying wave keeps kRing - 1 tiles in flight
+  // and waits for the oldest alone, and the computing waves never wait on a copy.  One workgroup barrier
+  // per tile hands the buffers over.
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
   const int n_compute = (blockDim.x >> 6) - 1;
   const bool producer = wave == n_compute;
@@ -1089,7 +1093,10 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
     is_new = i >= p1 - p0;
     page = 0;
     if (is_new) return p.K;
-    page = p.block_table[(size_t)c * p.max_pages + p0 + i];
+    // read through the scalar (constant) path: a vector load here would make the copying wave wait for
+    // every copy it has in flight before it could use the page id
+    typedef const int32_t __attribute__((address_space(4))) * ConstTable;
+    page = ((ConstTable)(uintptr_t)p.block_table)[(size_t)c * p.max_pages + p0 + i];
     int valid = n_ctx - (p0 + i) * kKeysPerTile;
     valid = valid > kKeysPerTile ? kKeysPerTile : valid;
     if (page < 0 || page >= p.n_pages) {
@@ -1106,11 +1113,12 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
     const __bf16* k_fill = p.k_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
     const __bf16* v_fill = p.v_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
     const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
-    for (int i = 0; i < n_tiles; ++i) {
+    auto copy_tile = [&](int i) {
       int page;
       bool is_new;
       const int valid = tile_info(i, page, is_new);
-      const int buf = i & 1;
+      // (untracked copies: a tracked one would make every workgroup barrier below wait for all of them)
+      const uint32_t kdst = lds_scalar_addr(lds[i % kRing][0]), vdst = lds_scalar_addr(lds[i % kRing][1]);
 #pragma unroll 4
       for (int blk = 0; blk < kBlocks; ++blk) {
         const int row = blk * (512 / D) + row_in_blk;
@@ -1127,10 +1135,22 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
           ks = p.k_pages + off;
           vs = p.v_pages + off;
         }
-        dma16(ks, lds[buf][0] + blk * 1024);
-        dma16(vs, lds[buf][1] + blk * 1024);
+        dma16_untracked(ks, kdst + blk * 1024);
+        dma16_untracked(vs, vdst + blk * 1024);
       }
-      dma_publish();  // tile i has landed; the computing waves are done with tile i-1, whose buffer is next
+    };
+    int issued = 0;
+    for (; issued < n_tiles && issued < kRing - 1; ++issued) copy_tile(issued);
+    for (int i = 0; i < n_tiles; ++i) {
+      // Tile i must have landed; the `later` tiles issued behind it may still be in flight.  Copies
+      // complete in issue order, so waiting until at most later * kCopiesPerTile accesses are outstanding
+      // is enough (anything else this wave may have in flight only makes the wait longer).
+      const int later = issued - 1 - i;  // 0 .. kRing - 2
+      if (later >= 2) wait_outstanding<kRing >= 4 ? 2 * kCopiesPerTile : 0>();
+      else if (later == 1) wait_outstanding<kCopiesPerTile>();
+      else wait_outstanding<0>();
+      __syncthreads();  // tile i is published; the computing waves are done with tile i-1 ...
+      if (issued < n_tiles) copy_tile(issued++);  // ... whose buffer takes tile i + kRing - 1
     }
     if (n_tiles == 0) __syncthreads();
     return;  // barriers executed: max(n_tiles, 1), the same as the computing waves below
@@ -1152,9 +1172,10 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
   const NatOff<D> no = nat_offsets<D>(lane);
   const TrOff<D> to = tr_offsets<D>(lane);
 
-  __syncthreads();  // tile 0 has landed (or there is none)
+  if (n_tiles == 0) __syncthreads();
   for (int i = 0; i < n_tiles; ++i) {
-    const int buf = i & 1;
+    __syncthreads();  // tile i has landed
+    const int buf = i % kRing;
     int page;
     bool is_new;
     const int valid = tile_info(i, page, is_new);
@@ -1168,7 +1189,6 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
       const uint32_t mw[2] = {(uint32_t)bits >> (4 * g), (uint32_t)(bits >> 32) >> (4 * g)};
       fwd_tile<D, 1, true, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
     }
-    if (i + 1 < n_tiles) __syncthreads();  // tile i+1 has landed, and tile i's buffer may be refilled
   }
 
   // partial record of this split: lane <-> row, registers <-> d = db*32 + 8*q4 + 4g + j
@@ -1446,8 +1466,16 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
 hipError_t launch_draft_decode(const DecodeParams& p, int D, hipStream_t stream) {
   // one computing wave per 32 query rows, plus the wave that copies
   const dim3 grid((unsigned)p.n_splits, (unsigned)p.Hkv, (unsigned)p.C), block((unsigned)((p.rows_pad / 32 + 1) * 64));
-  if (D == 64) hipLaunchKernelGGL((draft_decode_kernel<64>), grid, block, 0, stream, p);
-  else hipLaunchKernelGGL((draft_decode_kernel<128>), grid, block, 0, stream, p);
+  // Long splits keep three tiles in flight per workgroup (4.4 against 4.1 TB/s on a batch that fills the
+  // memory system); short ones - the serving shapes - are a microsecond faster with two buffers, which
+  // let more workgroups share a CU.  D = 128 tiles are twice the size: two buffers.
+  const bool deep = D == 64 && (p.max_pages + p.n_splits - 1) / p.n_splits > 16;
+  if (D == 64) {
+    if (deep) hipLaunchKernelGGL((draft_decode_kernel<64, 4>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((draft_decode_kernel<64, 2>), grid, block, 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((draft_decode_kernel<128, 2>), grid, block, 0, stream, p);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t n = (size_t)p.C * p.Hkv * p.K * (p.Hq / p.Hkv) * (D / 4);

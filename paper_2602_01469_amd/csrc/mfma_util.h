@@ -158,6 +158,15 @@ __device__ __forceinline__ void dma_publish() {
   __syncthreads();
 }
 
+// Wait until at most N of this wave's vector-memory accesses are outstanding (they complete in issue
+// order, so this waits for all but the N youngest).  Like dma_publish() it is an assembly statement with a
+// memory clobber: nothing moves across it.
+template <int N>
+__device__ __forceinline__ void wait_outstanding() {
+  static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   bf16x2 p;
   p[0] = (__bf16)a;
