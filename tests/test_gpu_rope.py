@@ -247,3 +247,42 @@ def test_rope_full_size_c3_sampled_rows():
     dof = bf16_bits_to_f64(dob)
     rhs = dof.sum(axis=0).reshape(cfg.Hkv, grp, cfg.D).sum(axis=1)
     assert np.abs(got["dV"].sum(axis=0) - rhs).max() <= 2e-3 * np.abs(dof).sum(axis=0).reshape(cfg.Hkv, grp, cfg.D).sum(axis=1).max()
+
+
+def test_rope_step_replays_from_a_hip_graph():
+    """The rotary step records kernel launches only (two more than the plain step): three replays, with new
+    inputs written and the program synchronising between them, each bit-identical to the eager result."""
+    L, K, Hq, Hkv, D = 640, 8, 8, 2, 64
+    bounds = [0, 256, 640]
+    print(f"case rope graph replay: L={L} K={K} bounds={bounds}", flush=True)
+    T = L * K
+    tm = pe.peagle_build_tilemap(L, K, bounds, device=0)
+
+    def bits(seed):
+        return (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1), rand_bits((T, Hkv, D), seed + 2),
+                rand_bits((T, Hq, D), seed + 3))
+
+    r = attach_rope(Run(tm, L, K, Hq, Hkv, D, *bits(2100)), BASE)
+    r.step_rope(0, 2)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pe.peagle_attn_step_partitioned_rope(tm, r.shape, 0, 2, r.q, r.k, r.v, r.do, r.rope_table, r.o, r.lse, r.dq,
+                                             r.dk, r.dv, None, None, r.ws, torch.cuda.current_stream())
+    for rep in range(3):
+        qb, kb, vb, dob = bits(2200 + 10 * rep)
+        for dst, src in ((r.q, qb), (r.k, kb), (r.v, vb), (r.do, dob)):
+            dst.copy_(to_dev_bf16(src))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {n: t.clone() for n, t in (("o", r.o), ("lse", r.lse), ("dq", r.dq), ("dk", r.dk), ("dv", r.dv))}
+        for t in (r.o, r.dq):
+            t.fill_(float("nan"))
+        r.step_rope(0, 2)
+        torch.cuda.synchronize()
+        for n, t in (("o", r.o), ("lse", r.lse), ("dq", r.dq), ("dk", r.dk), ("dv", r.dv)):
+            assert torch.equal(got[n], t), (rep, n)
+    ref = _oracle_rope(qb, kb, vb, dob, L, K, r.shape.scale, bounds)
+    _check_against_oracle(r.results(), ref, "rope graph replay", lse_abs=LSE_ABS_ROPE)
