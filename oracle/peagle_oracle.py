@@ -46,7 +46,9 @@ per-sequence masks rebuilt from the dependency rules, outputs against each seque
 against library autograd.  Rotary embedding (Sec. 2): the D = 2 case against complex multiplication,
 a hand-computed D = 4 vector, norm and inverse identities, position ids against the rows the worked
 example of Sec. 3.2 names by (position, depth), invariance of the whole step under a common shift
-of all positions, and finite differences of the loss with respect to the unrotated Q and K.
+of all positions, and finite differences of the loss with respect to the unrotated Q and K; the
+first-layer form with one shared key / value vector for all multi-token positions by finite differences
+with respect to those vectors and by the K = 1 case.
 Inference-side drafting: against the rows of the last anchor of the training-time problem (mask rebuilt
 from the dependency rules), a library attention routine with an explicit mask, and the zero-query closed
 form.  No function here is "parity unpinned".
@@ -76,6 +78,7 @@ __all__ = [
     "rope_angles",
     "rope_rotate",
     "attn_step_rope",
+    "attn_step_rope_shared",
     "draft_decode",
 ]
 
@@ -430,6 +433,25 @@ def attn_step_rope(q, k, v, do, L: int, K: int, scale: float, seg_bounds: Sequen
     r["dQ"] = rope_rotate(r["dQ"], pos, base, inverse=True)
     r["dK"] = rope_rotate(r["dK"], pos, base, inverse=True)
     return r
+
+
+def attn_step_rope_shared(q, k0, k_shared, v0, v_shared, do, L: int, K: int, scale: float, seg_bounds: Sequence[int],
+                          base: float, tokens: Optional[Tuple[np.ndarray, ...]] = None) -> Dict[str, np.ndarray]:
+    """The step as the first drafter layer sees it (Sec. 2): every multi-token position (depth >= 1) is fed
+    the same input - the shared hidden state and the mask-token embedding - so before the rotation all
+    their keys are one vector per KV head, k_shared [Hkv, D], and all their values one vector v_shared;
+    only the depth-0 positions (the first L stored tokens) have keys and values of their own, k0 / v0
+    [L, Hkv, D].  Builds the full K and V, runs :func:`attn_step_rope`, and returns O, LSE, dQ as there,
+    dK0 / dV0 for the depth-0 rows, and dK_shared / dV_shared: the sums over all chain positions (for the
+    keys: of the gradients turned back to the unrotated frame)."""
+    T = q.shape[0]
+    Hkv, D = k_shared.shape
+    assert k0.shape == (L, Hkv, D) and v0.shape == (L, Hkv, D) and v_shared.shape == (Hkv, D)
+    k = np.concatenate([k0, np.broadcast_to(k_shared, (T - L, Hkv, D))], axis=0)
+    v = np.concatenate([v0, np.broadcast_to(v_shared, (T - L, Hkv, D))], axis=0)
+    r = attn_step_rope(q, k, v, do, L, K, scale, seg_bounds, base, tokens=tokens)
+    return {"O": r["O"], "LSE": r["LSE"], "dQ": r["dQ"], "dK0": r["dK"][:L], "dV0": r["dV"][:L],
+            "dK_shared": r["dK"][L:].sum(axis=0), "dV_shared": r["dV"][L:].sum(axis=0)}
 
 
 # --------------------------------------------------------------------------------------

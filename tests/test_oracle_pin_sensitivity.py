@@ -45,6 +45,8 @@ MUTATIONS = [
      [("test_position_ids_follow_the_rows_named_in_the_paper_example", ())]),
     ("positions do not restart per packed sequence", "return ta - first[ts] + td", "return ta + td",
      [("test_position_ids_follow_the_rows_named_in_the_paper_example", ())]),
+    ("shared-vector gradient summed over every stored position", 'r["dK"][L:].sum(axis=0), "dV_shared"', 'r["dK"].sum(axis=0), "dV_shared"',
+     [("test_shared_chain_vectors_gradients_against_finite_differences", ())]),
     ("drafting rows see every new key", "M[d, n + e] = visible(n, d, n, e)", "M[d, n + e] = True",
      [("test_draft_decode_against_library_attention_and_closed_forms", ())]),
 ]

@@ -674,3 +674,41 @@ def test_draft_decode_against_library_attention_and_closed_forms():
     O1, LSE1 = orc.draft_decode(qn, kn, vn, kc[:0], vc[:0], 0.25)
     np.testing.assert_allclose(O1[0, 0], vn[0, 0], rtol=0, atol=1e-12)
     np.testing.assert_allclose(LSE1[0, 0], 0.25 * qn[0, 0] @ kn[0, 0], rtol=0, atol=1e-12)
+
+
+def test_shared_chain_vectors_gradients_against_finite_differences():
+    """First-layer form (Sec. 2): one key / value vector for all multi-token positions.  Gradients with
+    respect to those vectors by central differences of the loss through the plain forward."""
+    L, K, Hq, Hkv, D = 5, 3, 2, 1, 4
+    rng = np.random.default_rng(51)
+    T = L * K
+    q, do = rng.standard_normal((T, Hq, D)), rng.standard_normal((T, Hq, D))
+    k0, v0 = rng.standard_normal((L, Hkv, D)), rng.standard_normal((L, Hkv, D))
+    ks, vs = rng.standard_normal((Hkv, D)), rng.standard_normal((Hkv, D))
+    base, scale = 50.0, 0.45
+    r = orc.attn_step_rope_shared(q, k0, ks, v0, vs, do, L, K, scale, [0, 2, 5], base)
+
+    def loss(k0_, ks_, v0_, vs_):
+        pos = orc.position_ids(L, K)
+        k = np.concatenate([k0_] + [ks_[None]] * (T - L))
+        v = np.concatenate([v0_] + [vs_[None]] * (T - L))
+        O, _ = orc.attn_forward(orc.rope_rotate(q, pos, base), orc.rope_rotate(k, pos, base), v, L, K, scale)
+        return float((O * do).sum())
+
+    eps = 1e-6
+    for d in range(D):
+        e = np.zeros_like(ks)
+        e[0, d] = eps
+        fd = (loss(k0, ks + e, v0, vs) - loss(k0, ks - e, v0, vs)) / (2 * eps)
+        assert abs(fd - r["dK_shared"][0, d]) < 1e-7 * max(1.0, abs(fd))
+        fd = (loss(k0, ks, v0, vs + e) - loss(k0, ks, v0, vs - e)) / (2 * eps)
+        assert abs(fd - r["dV_shared"][0, d]) < 1e-7 * max(1.0, abs(fd))
+        e0 = np.zeros_like(k0)
+        e0[3, 0, d] = eps
+        fd = (loss(k0 + e0, ks, v0, vs) - loss(k0 - e0, ks, v0, vs)) / (2 * eps)
+        assert abs(fd - r["dK0"][3, 0, d]) < 1e-7 * max(1.0, abs(fd))
+        fd = (loss(k0, ks, v0 + e0, vs) - loss(k0, ks, v0 - e0, vs)) / (2 * eps)
+        assert abs(fd - r["dV0"][3, 0, d]) < 1e-7 * max(1.0, abs(fd))
+    # K = 1: there is no multi-token position, so the shared vectors receive no gradient
+    r1 = orc.attn_step_rope_shared(q[:L], k0, ks, v0, vs, do[:L], L, 1, scale, [0, L], base)
+    assert np.array_equal(r1["dK_shared"], np.zeros((Hkv, D))) and np.array_equal(r1["dV_shared"], np.zeros((Hkv, D)))
