@@ -299,6 +299,32 @@ int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_s
                                       void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * The rotary step as the first drafter layer sees it.  Every multi-token position is fed the same
+ * input - the shared hidden state and the mask-token embedding (Sec. 2) - so before the rotation the
+ * keys of all positions of depth >= 1 are one vector per KV head, and their values one vector; only
+ * the depth-0 positions, the first L stored tokens of any map, have keys and values of their own.
+ * The caller passes those and the two shared vectors instead of [T, Hkv, D] tensors, and gets the
+ * gradients in the same form.  All S segments run (in order, dK/dV accumulated across them).
+ *
+ *   q, d_o, o, dq   device, bf16 [T, Hq, D] as in peagle_attn_step_partitioned_rope; lse fp32 [Hq, T]
+ *   k0, v0          device, bf16 [L, Hkv, D]: unrotated keys / values of the depth-0 positions
+ *   k_shared, v_shared   device, bf16 [Hkv, D]: the unrotated key / value of every other position
+ *   dk0, dv0        device, fp32 [L, Hkv, D] (out)
+ *   dk_shared, dv_shared   device, fp32 [Hkv, D] (out): sums over all positions of depth >= 1 (for the
+ *                   keys, of the gradients turned back to the unrotated frame); deterministic
+ *   workspace       device, >= peagle_rope_shared_workspace_bytes(): besides the rotary workspace it holds
+ *                   the expanded V and fp32 dK / dV over all T tokens
+ * The keys are expanded and rotated in one pass (each chain row reads the shared vector, not HBM rows
+ * of its own), the values expanded by a copy; the attention kernels are those of the rotary step.
+ */
+size_t peagle_rope_shared_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape);
+int peagle_attn_step_rope_shared(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const void* q,
+                                 const void* k0, const void* k_shared, const void* v0, const void* v_shared,
+                                 const void* d_o, const float* rope_table, int32_t n_pos, void* o, float* lse,
+                                 void* dq, float* dk0, float* dv0, float* dk_shared, float* dv_shared,
+                                 void* workspace, size_t ws_bytes, void* stream);
+
+/*
  * Inference-side parallel drafting (Sec. 2: the drafter produces all K draft tokens in a single
  * forward pass; the serving experiments run K = 3, 5, 7 at concurrency 2-4).  One drafting step adds K
  * positions after a request's cached context of n tokens: the next-token position (depth 0) and K-1

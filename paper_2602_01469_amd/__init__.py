@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     peagle_attn_step_partitioned_rope,
     peagle_attn_step_profiled,
     peagle_attn_step_rope_profiled,
+    peagle_attn_step_rope_shared,
+    peagle_rope_shared_workspace_bytes,
     peagle_rope_position_ids,
     peagle_rope_positions,
     peagle_rope_rotate,

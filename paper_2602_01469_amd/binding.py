@@ -43,6 +43,7 @@ EXPORTS = [
     "peagle_tilemap_rebuild", "peagle_tilemap_tokens",
     "peagle_rope_positions", "peagle_rope_position_ids", "peagle_rope_table", "peagle_rope_rotate", "peagle_rope_workspace_bytes",
     "peagle_attn_step_partitioned_rope", "peagle_attn_step_rope_profiled",
+    "peagle_rope_shared_workspace_bytes", "peagle_attn_step_rope_shared",
     "peagle_draft_decode_splits", "peagle_draft_decode_workspace_bytes", "peagle_draft_decode",
     "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
@@ -117,6 +118,11 @@ def load_library():
     lib.peagle_attn_step_rope_profiled.argtypes = [vp, C.POINTER(_ShapeC), i32, i32, vp, vp, vp, vp, vp, i32, vp, vp,
                                                    vp, vp, vp, vp, sz, vp, C.POINTER(_ProfileC)]
     lib.peagle_attn_step_rope_profiled.restype = C.c_int
+    lib.peagle_rope_shared_workspace_bytes.argtypes = [vp, C.POINTER(_ShapeC)]
+    lib.peagle_rope_shared_workspace_bytes.restype = sz
+    lib.peagle_attn_step_rope_shared.argtypes = [vp, C.POINTER(_ShapeC), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp,
+                                                 vp, vp, vp, vp, sz, vp]
+    lib.peagle_attn_step_rope_shared.restype = C.c_int
     lib.peagle_draft_decode_splits.argtypes = [C.POINTER(_DecodeShapeC)]
     lib.peagle_draft_decode_splits.restype = i32
     lib.peagle_draft_decode_workspace_bytes.argtypes = [C.POINTER(_DecodeShapeC)]
@@ -456,6 +462,33 @@ def peagle_attn_step_rope_profiled(tm: TileMap, shape: Shape, seg_begin: int, se
     if rc != 0:
         raise PeagleError(rc, "peagle_attn_step_rope_profiled")
     return {name: (float(prof.ms[i]), int(prof.launches[i])) for i, name in enumerate(KERNEL_KINDS)}
+
+
+def peagle_rope_shared_workspace_bytes(tm: TileMap, shape: Shape) -> int:
+    n = int(load_library().peagle_rope_shared_workspace_bytes(tm.handle, shape.c()))
+    if n == 0:
+        raise PeagleError(-3, "peagle_rope_shared_workspace_bytes")
+    return n
+
+
+def peagle_attn_step_rope_shared(tm: TileMap, shape: Shape, q, k0, k_shared, v0, v_shared, d_o, rope_table, o, lse, dq,
+                                 dk0, dv0, dk_shared, dv_shared, workspace, stream=None) -> None:
+    import torch
+    bf, f32 = torch.bfloat16, torch.float32
+    T = tm.tokens(shape.L)
+    qs, k0s, kss = (T, shape.Hq, shape.D), (shape.L, shape.Hkv, shape.D), (shape.Hkv, shape.D)
+    n_pos = rope_table.shape[0]
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace: expected a contiguous uint8 GPU tensor")
+    rc = load_library().peagle_attn_step_rope_shared(
+        tm.handle, shape.c(), _ptr(q, "q", bf, qs), _ptr(k0, "k0", bf, k0s), _ptr(k_shared, "k_shared", bf, kss),
+        _ptr(v0, "v0", bf, k0s), _ptr(v_shared, "v_shared", bf, kss), _ptr(d_o, "d_o", bf, qs),
+        _ptr(rope_table, "rope_table", f32, (n_pos, 2, shape.D // 2)), n_pos, _ptr(o, "o", bf, qs),
+        _ptr(lse, "lse", f32, (shape.Hq, T)), _ptr(dq, "dq", bf, qs), _ptr(dk0, "dk0", f32, k0s),
+        _ptr(dv0, "dv0", f32, k0s), _ptr(dk_shared, "dk_shared", f32, kss), _ptr(dv_shared, "dv_shared", f32, kss),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_attn_step_rope_shared")
 
 
 class DecodeShape:

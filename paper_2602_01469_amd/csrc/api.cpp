@@ -168,7 +168,7 @@ static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, in
                      const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
                      float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes,
                      void* stream, peagle::KernelTimer* timer, const float* rope_table = nullptr,
-                     int32_t rope_n_pos = 0) {
+                     int32_t rope_n_pos = 0, bool inputs_rotated = false) {
   int rc = check_shape(tm, shape);
   if (rc != PEAGLE_OK) return rc;
   if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
@@ -178,7 +178,7 @@ static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, in
   if (rope_table && rope_n_pos < rope_positions(tm, shape->L)) return PEAGLE_ESHAPE;
   if (tm->device < 0) return PEAGLE_ENODEVICE;
   hipStream_t st = (hipStream_t)stream;
-  if (rope_table) {
+  if (rope_table && !inputs_rotated) {
     // Q and K arrive unrotated: the attention runs on rotated copies kept behind the workspace
     const RopeWs rw = rope_ws(tm, shape);
     void* q_rot = (char*)workspace + rw.q_off;
@@ -292,6 +292,73 @@ extern "C" int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, con
   if (!rope_table) return PEAGLE_ENULL;
   return step_impl(tm, shape, seg_begin, seg_end, q, k, v, d_o, o, lse, dq, dk_acc, dv_acc, dk_bf16, dv_bf16,
                    workspace, ws_bytes, stream, nullptr, rope_table, n_pos);
+}
+
+namespace {
+
+// Workspace of the first-layer form: the rotary workspace, the expanded V, fp32 dK / dV over all tokens,
+// and the partial sums of the shared-vector gradients.
+struct SharedWs {
+  size_t v_off, dk_off, dv_off, part_off, total;
+};
+SharedWs shared_ws(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
+  SharedWs w;
+  const size_t T = tokens_of(tm, s), cols = (size_t)s->Hkv * s->D;
+  w.v_off = rope_ws(tm, s).total;
+  w.dk_off = w.v_off + align256(T * cols * 2);
+  w.dv_off = w.dk_off + align256(T * cols * sizeof(float));
+  w.part_off = w.dv_off + align256(T * cols * sizeof(float));
+  w.total = w.part_off + align256((size_t)2 * peagle::kSharedGradBlocks * cols * sizeof(float));
+  return w;
+}
+
+}  // namespace
+
+extern "C" size_t peagle_rope_shared_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape) {
+  if (check_shape(tm, shape) != PEAGLE_OK) return 0;
+  return shared_ws(tm, shape).total;
+}
+
+extern "C" int peagle_attn_step_rope_shared(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const void* q,
+                                            const void* k0, const void* k_shared, const void* v0,
+                                            const void* v_shared, const void* d_o, const float* rope_table,
+                                            int32_t n_pos, void* o, float* lse, void* dq, float* dk0, float* dv0,
+                                            float* dk_shared, float* dv_shared, void* workspace, size_t ws_bytes,
+                                            void* stream) {
+  int rc = check_shape(tm, shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q || !k0 || !k_shared || !v0 || !v_shared || !d_o || !rope_table || !o || !lse || !dq || !dk0 || !dv0 ||
+      !dk_shared || !dv_shared)
+    return PEAGLE_ENULL;
+  if (n_pos < rope_positions(tm, shape->L)) return PEAGLE_ESHAPE;
+  const SharedWs sw = shared_ws(tm, shape);
+  if (!workspace || ws_bytes < sw.total) return PEAGLE_EWORKSPACE;
+  if (tm->device < 0) return PEAGLE_ENODEVICE;
+  hipStream_t st = (hipStream_t)stream;
+  const RopeWs rw = rope_ws(tm, shape);
+  const int T = (int)tokens_of(tm, shape), L0 = shape->L;  // the depth-0 positions are the first L stored tokens
+  char* ws = (char*)workspace;
+  void* q_rot = ws + rw.q_off;
+  void* k_rot = ws + rw.k_off;
+  void* v_full = ws + sw.v_off;
+  float* dk_acc = (float*)(ws + sw.dk_off);
+  float* dv_acc = (float*)(ws + sw.dv_off);
+  if (peagle::launch_rope_rotate(q, q_rot, shape->Hq, T, shape->D, tm->dview, shape->L, rope_table, false, st) !=
+      hipSuccess)
+    return PEAGLE_EHIP;
+  if (peagle::launch_expand_shared(k0, k_shared, k_rot, shape->Hkv, T, L0, shape->D, tm->dview, shape->L, rope_table,
+                                   st) != hipSuccess)
+    return PEAGLE_EHIP;
+  if (peagle::launch_expand_shared(v0, v_shared, v_full, shape->Hkv, T, L0, shape->D, tm->dview, shape->L, nullptr,
+                                   st) != hipSuccess)
+    return PEAGLE_EHIP;
+  rc = step_impl(tm, shape, 0, tm->S, q_rot, k_rot, v_full, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr, workspace,
+                 ws_bytes, stream, nullptr, rope_table, n_pos, /*inputs_rotated=*/true);
+  if (rc != PEAGLE_OK) return rc;
+  return peagle::launch_shared_grads(dk_acc, dv_acc, (float*)(ws + sw.part_off), peagle::kSharedGradBlocks, dk0, dv0,
+                                     dk_shared, dv_shared, T, L0, shape->Hkv * shape->D, st) == hipSuccess
+             ? PEAGLE_OK
+             : PEAGLE_EHIP;
 }
 
 extern "C" int peagle_attn_step_rope_profiled(const peagle_tilemap_t* tm, const peagle_shape_t* shape,

@@ -93,6 +93,14 @@ hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStrea
 // Rotary embedding: table [n_pos][2][D/2] of cosines and sines; rotation of a bf16 [T, H, D] tensor
 // by each token's position (inverse: the transpose).
 hipError_t launch_rope_table(double base, int D, int n_pos, float* table, hipStream_t stream);
+// First-layer form: expansion of (own depth-0 rows, one shared vector for every later token) into a full
+// [T, H, D] tensor, rotated when a table is given; and the reduction of the chain rows' gradients.
+hipError_t launch_expand_shared(const void* x0, const void* x_shared, void* out, int H, int T, int L0, int D,
+                                const DeviceTileMap& tm, int L, const float* table_or_null, hipStream_t stream);
+constexpr int kSharedGradBlocks = 256;
+hipError_t launch_shared_grads(const float* acc_k, const float* acc_v, float* partial, int n_partial_blocks, float* dk0,
+                               float* dv0, float* dk_shared, float* dv_shared, int T, int L0, int cols,
+                               hipStream_t stream);
 hipError_t launch_rope_rotate(const void* x, void* out, int H, int T, int D, const DeviceTileMap& tm, int L,
                               const float* table, bool inverse, hipStream_t stream, KernelTimer* timer = nullptr);
 

@@ -61,6 +61,79 @@ __global__ __launch_bounds__(256) void rope_rotate_kernel(const __bf16* x, __bf1
   }
 }
 
+// First drafter layer (Sec. 2: every multi-token position is fed the shared hidden state and the mask-token
+// embedding): tokens [0, L0) - the depth-0 positions - have rows of their own in x0 [L0, H, D], every later
+// token reads the one vector x_shared [H, D].  ROTATE: turn each row by its token's position (keys);
+// otherwise plain copies (values).
+template <int D, bool ROTATE>
+__global__ __launch_bounds__(256) void expand_shared_kernel(const __bf16* x0, const __bf16* x_shared, __bf16* out, int H,
+                                                            int T, int L0, DeviceTileMap tm, int L, const float* table) {
+  constexpr int kChunks = D / 16;
+  const size_t n = (size_t)T * H * kChunks;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+    const int c = (int)(idx % kChunks);
+    const size_t th = idx / kChunks;  // token * H + head
+    const int tok = (int)(th / H), h = (int)(th - (size_t)tok * H);
+    const __bf16* src = (tok < L0 ? x0 + th * D : x_shared + (size_t)h * D) + c * 8;
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(src);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(src + D / 2);
+    __bf16* dst = out + th * D + c * 8;
+    if (!ROTATE) {
+      *reinterpret_cast<bf16x8*>(dst) = a;
+      *reinterpret_cast<bf16x8*>(dst + D / 2) = b;
+      continue;
+    }
+    const float* row = table + (size_t)token_position(tm, tok, L) * D + c * 8;
+    u32x4 wa, wb;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      f32x4 lo, hi;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lo[j] = (float)a[4 * q + j];
+        hi[j] = (float)b[4 * q + j];
+      }
+      rope_turn4<false>(lo, hi, *reinterpret_cast<const f32x4*>(row + 4 * q),
+                        *reinterpret_cast<const f32x4*>(row + D / 2 + 4 * q));
+      wa[2 * q] = pack_bf16(lo[0], lo[1]);
+      wa[2 * q + 1] = pack_bf16(lo[2], lo[3]);
+      wb[2 * q] = pack_bf16(hi[0], hi[1]);
+      wb[2 * q + 1] = pack_bf16(hi[2], hi[3]);
+    }
+    *reinterpret_cast<u32x4*>(dst) = wa;
+    *reinterpret_cast<u32x4*>(dst + D / 2) = wb;
+  }
+}
+
+// Gradients of the shared vectors: column sums of the chain tokens' rows [L0, T) of acc [T, cols] (fp32),
+// in two deterministic stages.  Stage 1: block b sums the tokens L0 + b, L0 + b + nblk, ... into
+// partial[b][cols]; stage 2 (one block) sums the partials.  The same two launches also copy the depth-0
+// rows [0, L0) to their own output (stage 1, by all blocks).  gridDim.y selects dK or dV.
+__global__ __launch_bounds__(256) void shared_grad_stage1(const float* acc_k, const float* acc_v, float* partial,
+                                                          float* out0_k, float* out0_v, int T, int L0, int cols) {
+  const float* acc = blockIdx.y ? acc_v : acc_k;
+  float* out0 = blockIdx.y ? out0_v : out0_k;
+  const int nblk = gridDim.x, b = blockIdx.x;
+  for (int c4 = threadIdx.x; c4 < cols / 4; c4 += blockDim.x) {
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int t = L0 + b; t < T; t += nblk) sum += *reinterpret_cast<const f32x4*>(acc + (size_t)t * cols + c4 * 4);
+    *reinterpret_cast<f32x4*>(partial + ((size_t)blockIdx.y * nblk + b) * cols + c4 * 4) = sum;
+    for (int t = b; t < L0; t += nblk)
+      *reinterpret_cast<f32x4*>(out0 + (size_t)t * cols + c4 * 4) =
+          *reinterpret_cast<const f32x4*>(acc + (size_t)t * cols + c4 * 4);
+  }
+}
+__global__ __launch_bounds__(256) void shared_grad_stage2(const float* partial, float* out_k, float* out_v, int nblk,
+                                                          int cols) {
+  float* out = blockIdx.y ? out_v : out_k;
+  for (int c4 = threadIdx.x; c4 < cols / 4; c4 += blockDim.x) {
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < nblk; ++b)
+      sum += *reinterpret_cast<const f32x4*>(partial + ((size_t)blockIdx.y * nblk + b) * cols + c4 * 4);
+    *reinterpret_cast<f32x4*>(out + c4 * 4) = sum;
+  }
+}
+
 inline unsigned grid_for(size_t n) {
   size_t blocks = (n + 255) / 256;
   if (blocks > 256 * 32) blocks = 256 * 32;
@@ -93,6 +166,35 @@ hipError_t launch_rope_rotate(const void* x, void* out, int H, int T, int D, con
   hipError_t e = hipGetLastError();
   if (timer && begin == hipSuccess) begin = timer->end(stream);
   return e != hipSuccess ? e : begin;
+}
+
+hipError_t launch_expand_shared(const void* x0, const void* x_shared, void* out, int H, int T, int L0, int D,
+                                const DeviceTileMap& tm, int L, const float* table, hipStream_t stream) {
+  const size_t n = (size_t)T * H * (D / 16);
+  if (n == 0) return hipSuccess;
+  const dim3 grid(grid_for(n)), block(256);
+  const __bf16 *a = (const __bf16*)x0, *b = (const __bf16*)x_shared;
+  __bf16* o = (__bf16*)out;
+  if (D == 64) {
+    if (table) hipLaunchKernelGGL((expand_shared_kernel<64, true>), grid, block, 0, stream, a, b, o, H, T, L0, tm, L, table);
+    else hipLaunchKernelGGL((expand_shared_kernel<64, false>), grid, block, 0, stream, a, b, o, H, T, L0, tm, L, table);
+  } else {
+    if (table) hipLaunchKernelGGL((expand_shared_kernel<128, true>), grid, block, 0, stream, a, b, o, H, T, L0, tm, L, table);
+    else hipLaunchKernelGGL((expand_shared_kernel<128, false>), grid, block, 0, stream, a, b, o, H, T, L0, tm, L, table);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_shared_grads(const float* acc_k, const float* acc_v, float* partial, int n_partial_blocks, float* dk0,
+                               float* dv0, float* dk_shared, float* dv_shared, int T, int L0, int cols,
+                               hipStream_t stream) {
+  hipLaunchKernelGGL(shared_grad_stage1, dim3((unsigned)n_partial_blocks, 2), dim3(256), 0, stream, acc_k, acc_v, partial,
+                     dk0, dv0, T, L0, cols);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(shared_grad_stage2, dim3(1, 2), dim3(256), 0, stream, partial, dk_shared, dv_shared,
+                     n_partial_blocks, cols);
+  return hipGetLastError();
 }
 
 }  // namespace peagle

@@ -286,3 +286,71 @@ def test_rope_step_replays_from_a_hip_graph():
             assert torch.equal(got[n], t), (rep, n)
     ref = _oracle_rope(qb, kb, vb, dob, L, K, r.shape.scale, bounds)
     _check_against_oracle(r.results(), ref, "rope graph replay", lse_abs=LSE_ABS_ROPE)
+
+
+SHARED_CASES = [
+    # name, seq_lens, K, Hq, Hkv, D, retention, seed, bounds, dense map?
+    ("dense_segments", (256,), 8, 4, 2, 64, None, 3000, [0, 64, 128, 256], True),
+    ("dense_d128", (200,), 4, 4, 2, 128, None, 3010, [0, 96, 200], True),
+    ("dense_k1_no_chain", (300,), 1, 2, 2, 64, None, 3020, None, True),
+    ("sampled", (300,), 8, 4, 2, 64, 0.7, 3030, [0, 100, 300], False),
+    ("packed", (100, 37, 64, 1, 90), 8, 4, 1, 64, 0.8, 3040, None, False),
+]
+
+
+@pytest.mark.parametrize("name,seq_lens,K,Hq,Hkv,D,ret,seed,bounds,dense", SHARED_CASES, ids=[c[0] for c in SHARED_CASES])
+def test_rope_step_with_shared_chain_vectors_matches_oracle(name, seq_lens, K, Hq, Hkv, D, ret, seed, bounds, dense):
+    """First-layer form (Sec. 2): depth-0 keys / values of their own, one shared vector for every other position."""
+    print(f"case rope shared {name}: seq_lens={seq_lens} K={K} Hq={Hq} Hkv={Hkv} D={D} r={ret} bounds={bounds}", flush=True)
+    L = sum(seq_lens)
+    if dense:
+        tm = pe.peagle_build_tilemap(L, K, bounds, device=0)
+        tokens = None
+    else:
+        count = None if ret is None else cod_depth_counts(L, K, ret, seed)
+        tm = pe.peagle_build_tilemap_packed(seq_lens, K, count, bounds, device=0)
+        tokens = orc.packed_tokens(seq_lens, K, count)
+    T = tm.tokens(L)
+    qb, dob = rand_bits((T, Hq, D), seed), rand_bits((T, Hq, D), seed + 1)
+    k0b, v0b = rand_bits((L, Hkv, D), seed + 2), rand_bits((L, Hkv, D), seed + 3)
+    ksb, vsb = rand_bits((Hkv, D), seed + 4), rand_bits((Hkv, D), seed + 5)
+    shape = pe.Shape(L, K, Hq, Hkv, D)
+    n_pos = pe.peagle_rope_positions(tm, L)
+    table = torch.empty((n_pos, 2, D // 2), dtype=torch.float32, device="cuda")
+    pe.peagle_rope_table(BASE, D, n_pos, table)
+    dev = {n: to_dev_bf16(x) for n, x in (("q", qb), ("do", dob), ("k0", k0b), ("v0", v0b), ("ks", ksb), ("vs", vsb))}
+    nan = float("nan")
+    o = torch.full((T, Hq, D), nan, dtype=torch.bfloat16, device="cuda")
+    dq = torch.full((T, Hq, D), nan, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((Hq, T), nan, dtype=torch.float32, device="cuda")
+    dk0 = torch.full((L, Hkv, D), nan, dtype=torch.float32, device="cuda")
+    dv0 = torch.full((L, Hkv, D), nan, dtype=torch.float32, device="cuda")
+    dks = torch.full((Hkv, D), nan, dtype=torch.float32, device="cuda")
+    dvs = torch.full((Hkv, D), nan, dtype=torch.float32, device="cuda")
+    ws = torch.empty(pe.peagle_rope_shared_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+    for rep in range(2):        # the second call reuses the workspace: identical bits
+        pe.peagle_attn_step_rope_shared(tm, shape, dev["q"], dev["k0"], dev["ks"], dev["v0"], dev["vs"], dev["do"], table, o,
+                                        lse, dq, dk0, dv0, dks, dvs, ws)
+        torch.cuda.synchronize()
+        got = {"O": bf16_to_f64(o), "LSE": lse.double().cpu().numpy(), "dQ": bf16_to_f64(dq),
+               "dK0": dk0.double().cpu().numpy(), "dV0": dv0.double().cpu().numpy(),
+               "dK_shared": dks.double().cpu().numpy(), "dV_shared": dvs.double().cpu().numpy()}
+        if rep == 0:
+            first = got
+    for n in got:
+        assert np.array_equal(first[n], got[n]), n
+    f = bf16_bits_to_f64
+    ob = bounds if bounds is not None else [0, L]
+    ref = orc.attn_step_rope_shared(f(qb), f(k0b), f(ksb), f(v0b), f(vsb), f(dob), L, K, shape.scale, ob, BASE,
+                                    tokens=tokens)
+    assert not any(np.isnan(got[n]).any() for n in got)
+    assert rel_l2(got["O"], ref["O"]) <= FWD_REL
+    _check_o_abs(got["O"], ref["O"], name)
+    assert max_abs(got["LSE"], ref["LSE"]) <= LSE_ABS_ROPE
+    for n in ("dQ", "dK0", "dV0"):
+        assert rel_l2(got[n], ref[n]) <= GRAD_REL, n
+    if K > 1:
+        for n in ("dK_shared", "dV_shared"):
+            assert rel_l2(got[n], ref[n]) <= GRAD_REL, n
+    else:
+        assert not got["dK_shared"].any() and not got["dV_shared"].any()

@@ -590,3 +590,20 @@ def test_decode_input_generator_scatters_the_context_over_pages():
             page = inp["block_table"][c, t // 64]
             assert np.array_equal(inp["k_pages"][page, :, t % 64], inp["k_ctx"][c][t])
             assert np.array_equal(inp["v_pages"][page, :, t % 64], inp["v_ctx"][c][t])
+
+
+def test_rope_shared_entry_point_validates_before_launch():
+    lib = pe.load_library()
+    tm = pe.peagle_build_tilemap(256, 8, [0, 128, 256], device=-1)
+    one = C.c_void_p(16)
+    ok = pe.Shape(256, 8, 4, 2, 64)
+
+    def call(k_shared=one, n_pos=263, ws=1 << 40):
+        return lib.peagle_attn_step_rope_shared(tm.handle, ok.c(), one, one, k_shared, one, one, one, one, n_pos, one, one,
+                                                one, one, one, one, one, one, ws, None)
+    assert call(k_shared=None) == -2
+    assert call(n_pos=262) == -3
+    assert call(ws=pe.peagle_rope_workspace_bytes(tm, ok)) == -6       # the rotary workspace alone is too small
+    assert call() == -8
+    need = pe.peagle_rope_shared_workspace_bytes(tm, ok)
+    assert need >= pe.peagle_rope_workspace_bytes(tm, ok) + 256 * 8 * 2 * 64 * (2 + 4 + 4)
