@@ -323,6 +323,19 @@ def rope(args) -> int:
 
     ms_plain = timed(plain) if not args.partitioned_only else None
     ms = timed(roped)
+    # the first-layer form: depth-0 keys / values of their own, one shared vector for every other position
+    ms_shared = None
+    if not args.partitioned_only:
+        k0, v0 = k[:cfg.L].contiguous(), v[:cfg.L].contiguous()
+        ks, vs = k[cfg.L].contiguous(), v[cfg.L].contiguous()
+        dk0, dv0 = torch.empty((cfg.L, cfg.Hkv, cfg.D), dtype=torch.float32, device="cuda"), None
+        dv0 = torch.empty_like(dk0)
+        dks = torch.empty((cfg.Hkv, cfg.D), dtype=torch.float32, device="cuda")
+        dvs = torch.empty_like(dks)
+        ws2 = torch.empty(pe.peagle_rope_shared_workspace_bytes(tm, shape), dtype=torch.uint8, device="cuda")
+        ms_shared = timed(lambda: pe.peagle_attn_step_rope_shared(tm, shape, q, k0, ks, v0, vs, do, table, o, lse, dq, dk0,
+                                                                  dv0, dks, dvs, ws2, stream))
+        del ws2
     flops = useful_flops(cfg.L, cfg.K, cfg.Hq, cfg.D)
     out = {
         "metric": "effective masked-attn TFLOP/s fwd+bwd (useful FLOPs), rotary embedding of Q and K inside the step",
@@ -331,6 +344,7 @@ def rope(args) -> int:
         "config": {"workload": f"{cfg.name} with rotary embedding (base {args.rope:g}): L={cfg.L} K={cfg.K} Hq={cfg.Hq} "
                                f"Hkv={cfg.Hkv} D={cfg.D}, {S} segments, seed {cfg.seed}"},
         "plain_ms_per_step": ms_plain, "rope_overhead": None if ms_plain is None else ms / ms_plain,
+        "shared_chain_vectors_ms_per_step": ms_shared,
         "rope_table_ms": table_ms, "rope_positions": n_pos,
         "finite": bool(torch.isfinite(dk).all().item() and torch.isfinite(dv).all().item())}
     if not args.partitioned_only:
