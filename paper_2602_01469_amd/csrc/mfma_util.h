@@ -111,30 +111,23 @@ __device__ __forceinline__ bf16x8 frag_tr(const char* tile, const TrOff<D>& t, i
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// Asynchronous global -> LDS copy, 16 bytes per lane (global_load_lds_dwordx4): lane l's bytes
-// land at lds_wave_base + 16*l, so one call fills 1 KiB of LDS per wave; lds_wave_base must be
-// wave-uniform.  Completion is tracked by vmcnt of the issuing wave only: use dma_publish() to
-// make the data visible to the other waves.
-__device__ __forceinline__ void dma16(const void* gsrc, char* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
-                                   PEAGLE_LDS_PTR(void, lds_wave_base), 16, 0, 0);
-}
-
-// Same, 4 bytes per lane (global_load_lds_dword): lane l's dword lands at lds_wave_base + 4*l.
-__device__ __forceinline__ void dma4(const void* gsrc, char* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
-                                   PEAGLE_LDS_PTR(void, lds_wave_base), 4, 0, 0);
-}
-
-// The same two copies issued through an assembly statement.  The compiler counts a copy made with the
-// builtin as an outstanding memory access of unknown LDS destination and makes the wave wait for ALL of
-// them before its next LDS read, whichever buffer that read touches; a kernel that issues the next
-// tile's copy and then computes on the current one so stalls for the copy's whole latency unless another
-// workgroup fills the gap.  Issued this way the copy is invisible to that bookkeeping (the hardware
-// counter still counts it, so the compiler's own waits can only become longer, never too short), and the
-// caller alone orders it: nothing may read or overwrite the destination before dma_publish().  M0 carries
-// the LDS address, as it does for the builtin; it is declared clobbered.  The address is passed as a
-// scalar: lds_scalar_addr() of a wave-uniform pointer, plus wave-uniform offsets.
+// Asynchronous global -> LDS copies.  dma16_untracked: 16 bytes per lane (global_load_lds_dwordx4), lane
+// l's bytes land at lds_addr + 16*l, so one call fills 1 KiB of LDS per wave; dma4_untracked: 4 bytes per
+// lane (global_load_lds_dword), lane l's dword lands at lds_addr + 4*l.  lds_addr is a scalar:
+// lds_scalar_addr() of a wave-uniform pointer, plus wave-uniform offsets (so that no vector instruction
+// is spent on it).  Completion is counted by vmcnt of the issuing wave only: dma_publish() makes the
+// data visible to the other waves.
+//
+// The instruction is issued through an assembly statement rather than the compiler's builtin, hence
+// "untracked".  The compiler counts a copy made with the builtin as an outstanding memory access of
+// unknown LDS destination and makes the wave wait for ALL of them before its next LDS read, whichever
+// buffer that read touches (and before every workgroup barrier with its fence); a kernel that issues the
+// next tile's copy and then computes on the current one so stalls for the copy's whole latency unless
+// another workgroup fills the gap.  Issued this way the copy is invisible to that bookkeeping (the
+// hardware counter still counts it, so the compiler's own waits can only become longer, never too
+// short), and the caller alone orders it: nothing may read or overwrite the destination before
+// dma_publish() / wait_outstanding().  M0 carries the LDS address, as it would for the builtin; it is
+// declared clobbered, and no kernel here mixes the two forms.
 __device__ __forceinline__ uint32_t lds_scalar_addr(const char* lds_ptr) {
   return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)PEAGLE_LDS_PTR(char, lds_ptr));
 }
