@@ -1065,6 +1065,8 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
   constexpr int kCopiesPerTile = 2 * kBlocks;
   static_assert((kRing - 2) * kCopiesPerTile <= 63, "the copies in flight behind a tile must fit the hardware's counter");
   __shared__ __attribute__((aligned(16))) char lds[kRing][2][kTileBytes];  // [buffer][K|V]
+  __shared__ int tile_keys[kRing];  // keys present in the tile of each buffer (0 .. 64), set by the copying wave
+  __shared__ int table_bad;         // the copying wave met a page id outside the pool
 
   // The last wave of the workgroup only copies (global -> LDS), the others only compute.  The wait for
   // a copy is counted per wave and in issue order, so the copying wave keeps kRing - 1 tiles in flight
@@ -1087,23 +1089,14 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
   const int p1 = p0 + per < n_pg ? p0 + per : n_pg;
   const int n_tiles = (p1 - p0) + (split == 0 ? 1 : 0);  // split 0 also takes the new keys
 
-  // Tile i of this split: a cache page (keys [0, valid) of it exist) or, last in split 0, the K new keys.
-  // A page id outside the pool makes the tile empty and flags the request.
-  auto tile_info = [&](int i, int& page, bool& is_new) {
-    is_new = i >= p1 - p0;
-    page = 0;
-    if (is_new) return p.K;
-    // read through the scalar (constant) path: a vector load here would make the copying wave wait for
-    // every copy it has in flight before it could use the page id
-    typedef const int32_t __attribute__((address_space(4))) * ConstTable;
-    page = ((ConstTable)(uintptr_t)p.block_table)[(size_t)c * p.max_pages + p0 + i];
-    int valid = n_ctx - (p0 + i) * kKeysPerTile;
-    valid = valid > kKeysPerTile ? kKeysPerTile : valid;
-    if (page < 0 || page >= p.n_pages) {
-      bad = true;
-      valid = 0;
-    }
-    return valid;
+  // Tile i of this split is a cache page or, last in split 0, the K new keys.  Only the copying wave
+  // reads the block table - through the scalar (constant) path, because a vector load would be ordered
+  // behind its copies and using the result would wait for all of them, and one tile ahead of its use,
+  // so that the load's latency is off the path; it tells the computing waves how many keys each tile
+  // holds through tile_keys[] (a page id outside the pool makes the tile empty and flags the request).
+  typedef const int32_t __attribute__((address_space(4))) * ConstTable;
+  auto page_of = [&](int i) {
+    return i < p1 - p0 ? ((ConstTable)(uintptr_t)p.block_table)[(size_t)c * p.max_pages + p0 + i] : 0;
   };
 
   if (producer) {
@@ -1113,10 +1106,21 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
     const __bf16* k_fill = p.k_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
     const __bf16* v_fill = p.v_new + ((size_t)c * p.K * p.Hkv + kvh) * D;
     const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
+    int page_next = page_of(0);
     auto copy_tile = [&](int i) {
-      int page;
-      bool is_new;
-      const int valid = tile_info(i, page, is_new);
+      const int page = page_next;
+      page_next = page_of(i + 1);
+      const bool is_new = i >= p1 - p0;
+      int valid = p.K;
+      if (!is_new) {
+        valid = n_ctx - (p0 + i) * kKeysPerTile;
+        valid = valid > kKeysPerTile ? kKeysPerTile : valid;
+        if (page < 0 || page >= p.n_pages) {
+          bad = true;
+          valid = 0;
+        }
+      }
+      if (lane == 0) tile_keys[i % kRing] = valid;
       // (untracked copies: a tracked one would make every workgroup barrier below wait for all of them)
       const uint32_t kdst = lds_scalar_addr(lds[i % kRing][0]), vdst = lds_scalar_addr(lds[i % kRing][1]);
 #pragma unroll 4
@@ -1149,10 +1153,14 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
       if (later >= 2) wait_outstanding<kRing >= 4 ? 2 * kCopiesPerTile : 0>();
       else if (later == 1) wait_outstanding<kCopiesPerTile>();
       else wait_outstanding<0>();
+      if (i == n_tiles - 1 && lane == 0) table_bad = bad ? 1 : 0;  // every tile has been looked up by now
       __syncthreads();  // tile i is published; the computing waves are done with tile i-1 ...
       if (issued < n_tiles) copy_tile(issued++);  // ... whose buffer takes tile i + kRing - 1
     }
-    if (n_tiles == 0) __syncthreads();
+    if (n_tiles == 0) {
+      if (lane == 0) table_bad = 0;
+      __syncthreads();
+    }
     return;  // barriers executed: max(n_tiles, 1), the same as the computing waves below
   }
 
@@ -1176,9 +1184,8 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
   for (int i = 0; i < n_tiles; ++i) {
     __syncthreads();  // tile i has landed
     const int buf = i % kRing;
-    int page;
-    bool is_new;
-    const int valid = tile_info(i, page, is_new);
+    const bool is_new = i >= p1 - p0;
+    const int valid = __builtin_amdgcn_readfirstlane(tile_keys[buf]);
     if (!is_new && valid == kKeysPerTile) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       fwd_tile<D, 1, false, true>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
@@ -1209,7 +1216,7 @@ __global__ __launch_bounds__(320) void draft_decode_kernel(DecodeParams p) {
       float* ml = p.part_ml + rec * 3 * p.rows_pad;
       ml[r] = m[0];
       ml[p.rows_pad + r] = l_tot;
-      ml[2 * p.rows_pad + r] = bad ? 1.f : 0.f;
+      ml[2 * p.rows_pad + r] = (bad || table_bad != 0) ? 1.f : 0.f;  // (table_bad: written before the last barrier)
     }
   }
 }
