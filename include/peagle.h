@@ -5,7 +5,7 @@
  * expanded sequence of Sec. 3 of the paper: a sequence of L tokens becomes T = L*K positions,
  * one per (anchor i in [0,L), prediction depth d in [0,K)); depth 0 is the ordinary next-token
  * position, depths 1..K-1 carry the shared hidden state.  The parallel-prediction mask
- * (Sec. 3, PARD paragraph: a depth-d row sees depths <= d only; Sec. 3.2 "Challenge 2":
+ * (Sec. 3, PARD paragraph: a depth-d row sees depths <= d only; Sec. 3.2, Challenge 2:
  * position p at depth d depends on position p-1 at depth d-1) reads, in anchor coordinates:
  *
  *     row (i,d) sees key (j,e)   iff   (e == 0 and j <= i)  or  (j == i and 1 <= e <= d).
@@ -144,7 +144,7 @@ int peagle_attn_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* shape, int
 /*
  * Attention backward for the same rows: Delta = rowsum(dO * O), P = exp(S - LSE), dV = P^T dO,
  * dP = dO V^T, dS = P * (dP - Delta), dQ = scale * dS K, dK = scale * dS^T Q, with dK/dV summed
- * over the query heads of a KV group ("separate forward-backward pass" per segment, Sec. 3.2).
+ * over the query heads of a KV group (each segment runs as a forward-backward pass of its own, Sec. 3.2).
  *
  *   o, d_o     device, bf16 [T, Hq, D]   (O from peagle_attn_fwd, upstream gradient)
  *   lse        device, fp32 [Hq, T]

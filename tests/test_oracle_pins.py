@@ -553,8 +553,8 @@ def test_rope_is_an_isometry_with_the_transpose_as_inverse():
 
 
 def test_position_ids_follow_the_rows_named_in_the_paper_example():
-    # Sec. 3.2 names rows by (position, depth): "position 8 at depth 2 depends on position 7 at depth 1",
-    # i.e. both belong to anchor 6; stored tokens of the worked example carry those positions.
+    # Sec. 3.2 names rows by (position, depth); in its worked dependency example the row (position 8, depth 2)
+    # hangs on the row (position 7, depth 1): both belong to anchor 6, and the stored tokens carry those positions.
     count, d = _paper_example_depth_counts()
     ta, td = orc.cod_tokens(count)
     pos = orc.position_ids(len(count), d["K"], tokens=(ta, td))
