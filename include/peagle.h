@@ -364,6 +364,24 @@ int peagle_draft_decode(const peagle_decode_shape_t* shape, const void* q_new, c
                         const void* k_pages, const void* v_pages, const int32_t* block_table, const int32_t* ctx_len,
                         void* o, float* lse, int32_t* status, void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * The same drafting step for callers that cannot allocate or hand over device memory for scratch:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The partial
+ * records live in an array inside the loaded library (PEAGLE_STATIC_SCRATCH_BYTES per GPU, held until
+ * the process ends) instead of a caller workspace; every other argument is as in peagle_draft_decode
+ * and the results are bit-identical to it.  Shapes whose records need more than that
+ * (peagle_draft_decode_workspace_bytes() > PEAGLE_STATIC_SCRATCH_BYTES) are rejected with
+ * PEAGLE_EWORKSPACE before any launch.  The call allocates and frees nothing.  All calls on one GPU
+ * share that GPU's array: calls that overlap there (two streams, two threads) race; calls on one
+ * stream are ordered and safe.  The array keeps the previous call's records; the kernels overwrite
+ * every record they later read, so nothing needs clearing.
+ */
+#define PEAGLE_STATIC_SCRATCH_BYTES (32u << 20)
+int peagle_draft_decode_static(const peagle_decode_shape_t* shape, const void* q_new, const void* k_new,
+                               const void* v_new, const void* k_pages, const void* v_pages,
+                               const int32_t* block_table, const int32_t* ctx_len, void* o, float* lse,
+                               int32_t* status, void* stream);
+
 /* Kernel kinds reported by peagle_attn_step_profiled. */
 #define PEAGLE_KERNEL_FWD 0      /* forward (O, LSE) */
 #define PEAGLE_KERNEL_DQ 1       /* Delta and dQ */

@@ -32,6 +32,7 @@ from .binding import (  # noqa: F401
     peagle_device_info,
     peagle_draft_decode,
     peagle_draft_decode_splits,
+    peagle_draft_decode_static,
     peagle_draft_decode_workspace_bytes,
     peagle_strerror,
     peagle_workspace_bytes,

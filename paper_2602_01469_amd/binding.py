@@ -45,6 +45,7 @@ EXPORTS = [
     "peagle_attn_step_partitioned_rope", "peagle_attn_step_rope_profiled",
     "peagle_rope_shared_workspace_bytes", "peagle_attn_step_rope_shared",
     "peagle_draft_decode_splits", "peagle_draft_decode_workspace_bytes", "peagle_draft_decode",
+    "peagle_draft_decode_static",
     "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
 ]
 
@@ -129,6 +130,8 @@ def load_library():
     lib.peagle_draft_decode_workspace_bytes.restype = sz
     lib.peagle_draft_decode.argtypes = [C.POINTER(_DecodeShapeC), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.peagle_draft_decode.restype = C.c_int
+    lib.peagle_draft_decode_static.argtypes = [C.POINTER(_DecodeShapeC), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.peagle_draft_decode_static.restype = C.c_int
     lib.peagle_measure_mfma_ceiling.argtypes = [vp, C.POINTER(C.c_float)]
     lib.peagle_measure_mfma_ceiling.restype = C.c_int
     lib.peagle_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
@@ -532,6 +535,22 @@ def peagle_draft_decode(shape: DecodeShape, q_new, k_new, v_new, k_pages, v_page
         C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream))
     if rc != 0:
         raise PeagleError(rc, "peagle_draft_decode")
+
+
+def peagle_draft_decode_static(shape: DecodeShape, q_new, k_new, v_new, k_pages, v_pages, block_table, ctx_len, o, lse,
+                               status, stream=None) -> None:
+    import torch
+    bf, f32, i32 = torch.bfloat16, torch.float32, torch.int32
+    s = shape
+    pool = (s.n_pages, s.Hkv, 64, s.D)
+    rc = load_library().peagle_draft_decode_static(
+        s.c(), _ptr(q_new, "q_new", bf, (s.C, s.K, s.Hq, s.D)), _ptr(k_new, "k_new", bf, (s.C, s.K, s.Hkv, s.D)),
+        _ptr(v_new, "v_new", bf, (s.C, s.K, s.Hkv, s.D)), _ptr(k_pages, "k_pages", bf, pool),
+        _ptr(v_pages, "v_pages", bf, pool), _ptr(block_table, "block_table", i32, (s.C, s.max_pages)),
+        _ptr(ctx_len, "ctx_len", i32, (s.C,)), _ptr(o, "o", bf, (s.C, s.K, s.Hq, s.D)),
+        _ptr(lse, "lse", f32, (s.C, s.Hq, s.K)), _ptr(status, "status", i32, (s.C,)), _stream_ptr(stream))
+    if rc != 0:
+        raise PeagleError(rc, "peagle_draft_decode_static")
 
 
 def peagle_measure_mfma_ceiling(stream=None) -> float:

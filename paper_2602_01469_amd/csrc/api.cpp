@@ -2,6 +2,7 @@
 // paper: one forward+backward pass per segment, dK/dV accumulated across segments in fp32).
 #include <climits>
 #include <cmath>
+#include <mutex>
 
 #include "attn_kernels.h"
 #include "peagle.h"
@@ -428,15 +429,11 @@ extern "C" size_t peagle_draft_decode_workspace_bytes(const peagle_decode_shape_
   return check_decode(shape) == PEAGLE_OK ? decode_ws(shape).total : 0;
 }
 
-extern "C" int peagle_draft_decode(const peagle_decode_shape_t* shape, const void* q_new, const void* k_new,
-                                   const void* v_new, const void* k_pages, const void* v_pages,
-                                   const int32_t* block_table, const int32_t* ctx_len, void* o, float* lse,
-                                   int32_t* status, void* workspace, size_t ws_bytes, void* stream) {
-  const int rc = check_decode(shape);
-  if (rc != PEAGLE_OK) return rc;
-  if (!q_new || !k_new || !v_new || !k_pages || !v_pages || !block_table || !ctx_len || !o || !lse) return PEAGLE_ENULL;
-  const DecodeWs w = decode_ws(shape);
-  if (!workspace || ws_bytes < w.total) return PEAGLE_EWORKSPACE;
+namespace {
+
+int decode_impl(const peagle_decode_shape_t* shape, const DecodeWs& w, const void* q_new, const void* k_new,
+                const void* v_new, const void* k_pages, const void* v_pages, const int32_t* block_table,
+                const int32_t* ctx_len, void* o, float* lse, int32_t* status, void* workspace, void* stream) {
   peagle::DecodeParams p{};
   p.q_new = (const __bf16*)q_new;
   p.k_new = (const __bf16*)k_new;
@@ -460,6 +457,64 @@ extern "C" int peagle_draft_decode(const peagle_decode_shape_t* shape, const voi
   p.rows_pad = w.rows_pad;
   p.c_log2 = shape->scale * 1.4426950408889634f;
   return peagle::launch_draft_decode(p, shape->D, (hipStream_t)stream) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+}
+
+}  // namespace
+
+extern "C" int peagle_draft_decode(const peagle_decode_shape_t* shape, const void* q_new, const void* k_new,
+                                   const void* v_new, const void* k_pages, const void* v_pages,
+                                   const int32_t* block_table, const int32_t* ctx_len, void* o, float* lse,
+                                   int32_t* status, void* workspace, size_t ws_bytes, void* stream) {
+  const int rc = check_decode(shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q_new || !k_new || !v_new || !k_pages || !v_pages || !block_table || !ctx_len || !o || !lse) return PEAGLE_ENULL;
+  const DecodeWs w = decode_ws(shape);
+  if (!workspace || ws_bytes < w.total) return PEAGLE_EWORKSPACE;
+  return decode_impl(shape, w, q_new, k_new, v_new, k_pages, v_pages, block_table, ctx_len, o, lse, status, workspace,
+                     stream);
+}
+
+// Partial records of peagle_draft_decode_static: one array per GPU, held by the loaded library until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the device address
+// it yields (one per device, looked up once with that device current) is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[PEAGLE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return PEAGLE_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return PEAGLE_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PEAGLE_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PEAGLE_OK;
+}
+
+}  // namespace
+
+extern "C" int peagle_draft_decode_static(const peagle_decode_shape_t* shape, const void* q_new, const void* k_new,
+                                          const void* v_new, const void* k_pages, const void* v_pages,
+                                          const int32_t* block_table, const int32_t* ctx_len, void* o, float* lse,
+                                          int32_t* status, void* stream) {
+  const int rc = check_decode(shape);
+  if (rc != PEAGLE_OK) return rc;
+  if (!q_new || !k_new || !v_new || !k_pages || !v_pages || !block_table || !ctx_len || !o || !lse) return PEAGLE_ENULL;
+  const DecodeWs w = decode_ws(shape);
+  if (w.total > (size_t)PEAGLE_STATIC_SCRATCH_BYTES) return PEAGLE_EWORKSPACE;
+  void* ws = nullptr;
+  const int src = static_scratch(&ws);
+  if (src != PEAGLE_OK) return src;
+  // Every partial record the merge reads is written by this call's first launch: nothing has to start at zero.
+  return decode_impl(shape, w, q_new, k_new, v_new, k_pages, v_pages, block_table, ctx_len, o, lse, status, ws, stream);
 }
 
 extern "C" int peagle_measure_mfma_ceiling(void* stream, float* tflops) {

@@ -579,6 +579,23 @@ def test_draft_decode_validates_before_launch():
     assert pe.peagle_draft_decode_splits(pe.DecodeShape(512, 3, 8, 8, 64, 5000, 4000)) == 1
 
 
+def test_draft_decode_static_validates_before_launch():
+    """The entry point with the library's own scratch array: same checks, and shapes whose partial records
+    exceed the array are refused with the workspace error."""
+    lib = pe.load_library()
+    one = C.c_void_p(16)  # never dereferenced: validation fails first
+
+    def call(shape, q=one):
+        return lib.peagle_draft_decode_static(shape.c(), q, one, one, one, one, one, one, one, one, None, None)
+
+    assert call(pe.DecodeShape(0, 7, 64, 8, 64, 100, 20)) == -1
+    assert call(pe.DecodeShape(4, 7, 64, 8, 96, 100, 20)) == -5
+    assert call(pe.DecodeShape(4, 7, 64, 8, 64, 100, 20), q=None) == -2
+    big = pe.DecodeShape(4096, 7, 64, 8, 64, 8, 1)
+    assert pe.peagle_draft_decode_workspace_bytes(big) > 32 << 20
+    assert call(big) == -6
+
+
 def test_decode_input_generator_scatters_the_context_over_pages():
     from peagle_inputs import PAGE_TOKENS, make_decode_inputs
     inp = make_decode_inputs([0, 1, 64, 65, 200], K=3, Hq=4, Hkv=2, D=64, seed=9)
