@@ -102,6 +102,7 @@ BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
   p.s_lo = sr.s_lo;
   p.s_hi = sr.s_hi;
   p.cropped = sr.cropped;
+  p.fast_rows = (size_t)p.T * s->Hq * s->D * 2 < ((size_t)1 << 32) ? 1 : 0;
   p.chain_accumulate = chain_accumulate;
   p.c_log2 = s->scale * 1.4426950408889634f;
   p.scale = s->scale;

@@ -44,6 +44,7 @@ struct BwdParams {
   int d0_tile_lo;
   int clip_rows;        // filled by the launcher: [rt_lo, rt_hi) covers only part of the segments s_lo..s_hi
   int d0_split, d0_step;  // filled by the launcher: depth-0 pairs are dealt in passes, [0, d0_split) then d0_step at a time
+  int fast_rows;        // Q-shaped tensors and the [Hq, T] statistics span less than 4 GiB: row copies may use 32-bit offsets
   int chain_accumulate; // chain keys: add to dk_acc/dv_acc instead of overwriting
   float c_log2, scale;
   const float* rope_table;  // null, or [positions][2][D/2] cosines and sines: q and k are rotated copies, and dQ / dK

@@ -92,13 +92,16 @@ __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __b
   const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
   const uint32_t kd = lds_scalar_addr(k_lds + wave * 1024), vd = lds_scalar_addr(v_lds + wave * 1024);
   if (kt < tm.n_d0 && (kt + 1) * kKeysPerTile <= L) {
+    // A whole tile of depth-0 keys: the rows a lane copies are NW * 512/D apart (a multiple of the swizzle
+    // period), so its byte offset from each copy's first row is one value, the same for every tile, and the
+    // rest of the address is wave-uniform.
+    const int row0 = wave * (512 / D) + row_in_blk;
+    const uint32_t voff = (uint32_t)((row0 * Hkv) * D + ((phys ^ swz<D>(row0)) << 3)) * 2u;
 #pragma unroll
     for (int i = 0; i < kBlocks / NW; ++i) {
-      const int blk = i * NW + wave;
-      const int row = blk * (512 / D) + row_in_blk;
-      const size_t off = ((size_t)(kt * kKeysPerTile + row) * Hkv + kvh) * D + ((phys ^ swz<D>(row)) << 3);
-      dma16_untracked(kbase + off, kd + i * NW * 1024);
-      dma16_untracked(vbase + off, vd + i * NW * 1024);
+      const size_t first = ((size_t)(kt * kKeysPerTile + i * NW * (512 / D)) * Hkv + kvh) * D;
+      dma16_untracked(uniform_ptr(kbase + first), voff, kd + i * NW * 1024);
+      dma16_untracked(uniform_ptr(vbase + first), voff, vd + i * NW * 1024);
     }
   } else {
 #pragma unroll
@@ -128,9 +131,13 @@ struct RowDmaLane {
   int row[kPer];     // row of the tile (index into a sampled map's row list)
   int chunk[kPer];   // element offset of the logical 16-byte chunk this lane fetches
   int stat_tok0, stat_a, stat_row;  // same for the row whose per-row statistic this lane copies (waves 0..3)
+  // Dense maps, row tiles whose 128 rows all exist: byte offset of each copy's source from the head's row of the
+  // tile's first anchor, ((d*L + a) * Hq) * D * 2 + 2 * chunk (and 4 * (d*L + a) for the statistic) - the same
+  // for every row tile and head, so a copy needs only a new scalar base.
+  uint32_t fast_off[kPer], fast_stat_off;
 };
 template <int D, int NW>
-__device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& tm, int L, int wave, int lane) {
+__device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& tm, int L, int wave, int lane, int Hq = 0) {
   RowDmaLane<D, NW> r;
   const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
 #pragma unroll
@@ -142,6 +149,7 @@ __device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& t
     r.a[i] = d < tm.K ? a : (1 << 30);
     r.row[i] = row;
     r.chunk[i] = (phys ^ swz<D>(row)) << 3;
+    r.fast_off[i] = (uint32_t)r.tok0[i] * (uint32_t)(Hq * D * 2) + (uint32_t)(r.chunk[i] * 2);
   }
   const int srow = (wave & 1) * 64 + lane;
   const int A = tm.row_tok ? 1 : tm.A;
@@ -149,6 +157,7 @@ __device__ __forceinline__ RowDmaLane<D, NW> row_dma_lane(const DeviceTileMap& t
   r.stat_tok0 = sd * L + sa;
   r.stat_a = sd < tm.K ? sa : (1 << 30);
   r.stat_row = srow;
+  r.fast_stat_off = (uint32_t)r.stat_tok0 * 4u;
   return r;
 }
 // Tokens of the rows this lane copies for one row tile (-1: the row does not exist).  For a dense map
@@ -196,6 +205,20 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
   const bool ok = t.stat_tok >= 0;
   dma4_untracked(ok ? (const void*)(base + (size_t)h * T + t.stat_tok) : tm.zeros,
                  lds_scalar_addr(reinterpret_cast<const char*>(lds_stat + half * 64)));
+}
+
+// The same two copies for a row tile of a dense map whose 128 rows all exist (see RowDmaLane::fast_off):
+// `row0` = the head's row of the tile's first anchor at depth 0 (wave-uniform).
+template <int D, int NW>
+__device__ __forceinline__ void dma_row_tile_fast(char* lds_tile, const __bf16* row0, const RowDmaLane<D, NW>& rl, int wave) {
+  const uint32_t dst = lds_scalar_addr(lds_tile + wave * 1024);
+  const __bf16* base = uniform_ptr(row0);
+#pragma unroll
+  for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) dma16_untracked(base, rl.fast_off[i], dst + i * NW * 1024);
+}
+template <int D, int NW>
+__device__ __forceinline__ void dma_row_stat_fast(float* lds_stat, const float* stat0, const RowDmaLane<D, NW>& rl, int half) {
+  dma4_untracked(uniform_ptr(stat0), rl.fast_stat_off, lds_scalar_addr(reinterpret_cast<const char*>(lds_stat + half * 64)));
 }
 
 // Does any row of the wave see a key of the 32-key block whose (shifted) mask word each lane holds?
@@ -614,89 +637,151 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
 // (128 keys) of one KV head in registers and loops over the row tiles that see the first of
 // them (clipped to the segment) for the query heads [h_lo, h_hi) assigned to it; the second
 // tile's list is a suffix of the first's, so its waves idle on the few leading row tiles.
-// Wave w owns key block w%4 (32 keys) and row part w/4 of each row tile (RH parts); the parts'
-// dK^T / dV^T are summed through LDS at the end.
+// Wave w owns key block w (32 keys) and all 128 rows of each row tile.
 //   depth-0 key tiles: one query head per workgroup, result to the per-head partial buffer;
 //   chain key tiles:   all heads of the KV group, result straight to dk_acc / dv_acc.
 // =====================================================================================
-// MODE 0: every element visible; 1: bitmask; 2: every element visible except for lanes whose key
+// ---- one row tile (128 rows of one query head) against the wave's 32 keys, as one software pipeline ----
+// MODE 0: every element visible; 1: key-major bitmask; 2: every element visible except for lanes whose key
 // belongs to another sequence of a packed batch (lane_off = true): those lanes contribute nothing.
-template <int D, int RB, int MODE>
-__device__ __forceinline__ void dkdv_tile(const char* q_lds, const char* do_lds, const float* nlse_lds,
-                                          const float* ndelta_lds, const NatOff<D>& no, const TrOff<D>& to,
-                                          const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
-                                          f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], int row_base, int g, int ln,
-                                          const uint32_t* mrow, float c, bool lane_off = false) {
-  constexpr bool MASKED = MODE == 1;
+//
+// On this chip a wave that issues a matrix instruction and then independent vector instructions runs the
+// vector work in the shadow of the matrix pipe (about four plain vector instructions per
+// v_mfma_f32_32x32x16_bf16 cost nothing), whereas matrix and vector phases that follow one another - in the
+// same wave or in two waves of one SIMD - take the sum of their times.  The row tile's four 32-row units
+// are therefore staggered: while the vector unit turns the scores of unit u into P and dS, the matrix
+// pipe runs dV / dK of unit u-1 and S / dP of unit u+1.  The 8 groups of D/8 matrix instructions are
+//   S,dP(0) | S,dP(1) | dV,dK(0) | S,dP(2) | dV,dK(1) | S,dP(3) | dV,dK(2) | dV,dK(3)
+// and the vector work of units 0..3 rides on groups 1 | 2,3 | 4,5 | 6.  Every matrix instruction is
+// followed by its share of vector instructions and a scheduling fence, so the interleaving written here
+// is the one the hardware sees; operand fragments are fetched from LDS kPipeAhead instructions ahead.
+struct PipeGroup {
+  int kind;   // 0: S and dP of `unit`; 1: dV and dK of `unit`
+  int unit;   // 32-row block of the row tile
+  int vunit;  // unit whose vector work rides on this group (-1: none)
+  int e0, e1; // ... and which of its 16 score registers
+};
+constexpr PipeGroup kPipeGroups[8] = {{0, 0, -1, 0, 0}, {0, 1, 0, 0, 16}, {1, 0, 1, 0, 8},  {0, 2, 1, 8, 16},
+                                      {1, 1, 2, 0, 8},  {0, 3, 2, 8, 16}, {1, 2, 3, 0, 16}, {1, 3, -1, 0, 0}};
+constexpr int kPipeAhead = 2;
+
+template <int D>
+struct DkdvPipe {
+  f32x16 sc[2], dpc[2];        // S and dP accumulators of the units in flight (unit & 1)
+  u32x4 pb[2][2], dsb[2][2];   // P and dS of a unit as bf16 B operands, per 16-row step
+  bf16x8 ring[kPipeAhead];     // A operands on their way from LDS
+};
+
+// A operand of matrix instruction j of a group: S / dP read natural fragments (even j: Q, odd j: dO),
+// dV / dK transposed ones (even j: dO^T, odd j: Q^T; j/2 = 16-row step * D/32 + feature block).
+template <int D, int KIND>
+__device__ __forceinline__ bf16x8 pipe_frag(const char* q_lds, const char* do_lds, const NatOff<D>& no,
+                                            const TrOff<D>& to, int r0, int j) {
+  if (KIND == 0) return *reinterpret_cast<const bf16x8*>(((j & 1) ? do_lds : q_lds) + no.off[j >> 1] + r0 * (2 * D));
+  const int idx = j >> 1, db = idx % (D / 32), tt = idx / (D / 32);
+  return frag_tr<D>((j & 1) ? q_lds : do_lds, to, r0 + tt * 16, db);
+}
+
+// -lse/scale and -Delta of the unit's rows, straight into the accumulators S and dP start from (C layout).
+template <int MODE>
+__device__ __forceinline__ void pipe_row_terms(f32x16& s, f32x16& dp, const float* nlse_lds, const float* ndelta_lds,
+                                               int r0, int g, bool lane_off) {
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int r0 = row_base + rb * 32;  // multiple of 32
-    // S = Q K^T - lse/scale and dP - Delta = dO V^T - Delta: lane <-> key, registers <-> rows
-    // r0 + 8*(i/4) + 4g + i%4.  The per-row terms are the initial accumulator values, read
-    // from LDS in exactly the C layout, so they cost no vector instruction.
-    f32x16 s, dp;
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const f32x4 l4 = *reinterpret_cast<const f32x4*>(nlse_lds + r0 + 8 * q4 + 4 * g);
+    const f32x4 d4 = *reinterpret_cast<const f32x4*>(ndelta_lds + r0 + 8 * q4 + 4 * g);
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(nlse_lds + r0 + 8 * q4 + 4 * g);
-      const f32x4 d4 = *reinterpret_cast<const f32x4*>(ndelta_lds + r0 + 8 * q4 + 4 * g);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        s[4 * q4 + j] = MODE == 2 && lane_off ? -__builtin_inff() : l4[j];
-        dp[4 * q4 + j] = d4[j];
-      }
+    for (int j = 0; j < 4; ++j) {
+      s[4 * q4 + j] = MODE == 2 && lane_off ? -__builtin_inff() : l4[j];
+      dp[4 * q4 + j] = d4[j];
     }
-#pragma unroll
-    for (int st = 0; st < D / 16; ++st) {
-      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(q_lds + no.off[st] + r0 * (2 * D));
-      const bf16x8 ad = *reinterpret_cast<const bf16x8*>(do_lds + no.off[st] + r0 * (2 * D));
-      s = mfma32(aq, kf[st], s);
-      dp = mfma32(ad, vf[st], dp);
-    }
-    if (MASKED) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const uint32_t w = mrow[(r0 + 8 * (i / 4) + 4 * g + (i % 4)) * 2];
-        s[i] = mask_sel(s[i], w, ln);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float pr = exp2_fast(s[i] * c);
-      s[i] = pr;
-      dp[i] *= pr;
-    }
-    bf16x8 pb[2], dsb[2];
-    pb[0] = pack8(s, 0);
-    pb[1] = pack8(s, 1);
-    dsb[0] = pack8(dp, 0);
-    dsb[1] = pack8(dp, 1);
-    // dV^T += dO^T P, dK^T += Q^T dS : A operands transposed from LDS (lane <-> d, contraction over rows)
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 adt = frag_tr<D>(do_lds, to, r0 + t * 16, db);
-        const bf16x8 aqt = frag_tr<D>(q_lds, to, r0 + t * 16, db);
-        dv[db] = mfma32(adt, pb[t], dv[db]);
-        dk[db] = mfma32(aqt, dsb[t], dk[db]);
-      }
   }
+}
+
+template <int D, int MODE, int G>
+__device__ __forceinline__ void dkdv_pipe_group(DkdvPipe<D>& P, const char* q_lds, const char* do_lds,
+                                                const float* nlse_lds, const float* ndelta_lds, const NatOff<D>& no,
+                                                const TrOff<D>& to, const bf16x8 (&kf)[D / 16],
+                                                const bf16x8 (&vf)[D / 16], f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32],
+                                                int g, float c, bool lane_off, const u32x4& cm) {
+  constexpr int NG = D / 8;  // matrix instructions per group
+  constexpr PipeGroup gd = kPipeGroups[G];
+  constexpr PipeGroup gn = kPipeGroups[G + 1 < 8 ? G + 1 : 7];
+  constexpr int u = gd.unit & 1, vu = gd.vunit & 1;
+  if (G + 1 < 8 && gn.kind == 0)  // the next group starts S / dP of a unit: fetch its per-row terms now
+    pipe_row_terms<MODE>(P.sc[gn.unit & 1], P.dpc[gn.unit & 1], nlse_lds, ndelta_lds, gn.unit * 32, g, lane_off);
+#pragma unroll
+  for (int j = 0; j < NG; ++j) {
+    const int slot = (G * NG + j) % kPipeAhead;  // the instruction kPipeAhead later takes the slot this one frees
+    const bf16x8 a = P.ring[slot];
+    if (gd.kind == 0) {
+      if (j & 1) P.dpc[u] = mfma32(a, vf[j >> 1], P.dpc[u]);
+      else P.sc[u] = mfma32(a, kf[j >> 1], P.sc[u]);
+    } else {
+      const int idx = j >> 1, db = idx % (D / 32), tt = idx / (D / 32);
+      if (j & 1) dk[db] = mfma32(a, __builtin_bit_cast(bf16x8, P.dsb[u][tt]), dk[db]);
+      else dv[db] = mfma32(a, __builtin_bit_cast(bf16x8, P.pb[u][tt]), dv[db]);
+    }
+    if (j + kPipeAhead < NG)
+      P.ring[slot] = pipe_frag<D, gd.kind>(q_lds, do_lds, no, to, gd.unit * 32, j + kPipeAhead);
+    else if (G + 1 < 8)
+      P.ring[slot] = pipe_frag<D, gn.kind>(q_lds, do_lds, no, to, gn.unit * 32, j + kPipeAhead - NG);
+    if (gd.vunit >= 0) {
+      const int n = gd.e1 - gd.e0;
+#pragma unroll
+      for (int i = gd.e0 + n * j / NG; i < gd.e0 + n * (j + 1) / NG; ++i) {
+        float pr = exp2_fast(P.sc[vu][i] * c);
+        if (MODE == 1) {  // the lane's key-major mask word of this unit: bit of row 8*(i/4) + 4g + i%4
+          const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)(cm[gd.vunit & 3] >> (4 * g)), 8 * (i / 4) + (i % 4), 1);
+          pr = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, pr) & keep);
+        }
+        P.sc[vu][i] = pr;
+        P.dpc[vu][i] *= pr;
+        if (i & 1) {
+          P.pb[vu][i >> 3][(i & 7) >> 1] = pack_bf16(P.sc[vu][i - 1], P.sc[vu][i]);
+          P.dsb[vu][i >> 3][(i & 7) >> 1] = pack_bf16(P.dpc[vu][i - 1], P.dpc[vu][i]);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+template <int D, int MODE>
+__device__ __forceinline__ void dkdv_rowtile_pipelined(const char* q_lds, const char* do_lds, const float* nlse_lds,
+                                                       const float* ndelta_lds, const NatOff<D>& no, const TrOff<D>& to,
+                                                       const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
+                                                       f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], int g, float c,
+                                                       bool lane_off = false, const u32x4 cm = u32x4{0, 0, 0, 0}) {
+  DkdvPipe<D> P;
+  pipe_row_terms<MODE>(P.sc[0], P.dpc[0], nlse_lds, ndelta_lds, 0, g, lane_off);
+#pragma unroll
+  for (int j = 0; j < kPipeAhead; ++j) P.ring[j] = pipe_frag<D, 0>(q_lds, do_lds, no, to, 0, j);
+#define PEAGLE_PIPE_GROUP(G) \
+  dkdv_pipe_group<D, MODE, G>(P, q_lds, do_lds, nlse_lds, ndelta_lds, no, to, kf, vf, dk, dv, g, c, lane_off, cm)
+  PEAGLE_PIPE_GROUP(0);
+  PEAGLE_PIPE_GROUP(1);
+  PEAGLE_PIPE_GROUP(2);
+  PEAGLE_PIPE_GROUP(3);
+  PEAGLE_PIPE_GROUP(4);
+  PEAGLE_PIPE_GROUP(5);
+  PEAGLE_PIPE_GROUP(6);
+  PEAGLE_PIPE_GROUP(7);
+#undef PEAGLE_PIPE_GROUP
 }
 
 // LISTED: the map names rows by explicit token lists (sampled / packed maps); their tokens are then
 // fetched an iteration before the copy that uses them.  A dense map computes them when it issues
 // the copy and carries no token registers.
-template <int D, int RH, bool LISTED>
-__global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_kernel(BwdParams p) {
-  constexpr int RB = 4 / RH;  // 32-row blocks per wave per row tile
+template <int D, bool LISTED>
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p) {
   constexpr int kTileBytes = kRowsPerTile * D * 2;
   constexpr int kBufBytes = 2 * kTileBytes + 2 * kRowsPerTile * 4;  // Q | dO | lse2 | delta
-  constexpr int kRedBytes = (RH - 1) * 4 * 64 * 2 * (D / 32) * 16 * 4;  // [part][key block][lane][dk|dv regs]
-  constexpr int kLdsBytes = 2 * kBufBytes > kRedBytes ? 2 * kBufBytes : kRedBytes;
+  constexpr int kLdsBytes = 2 * kBufBytes;
   __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
-  const int kblk = wave & 3, part = wave >> 2;
+  const int kblk = wave;  // 32-key block of the pair owned by this wave
   const DeviceTileMap& tm = p.tm;
   const int group = p.Hq / p.Hkv;
 
@@ -795,15 +880,28 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
 
   // Q / dO row tiles and their per-row terms (-lse/scale, -Delta, prepared by the dQ kernel) go
   // straight from global memory into the LDS buffer that the next iteration reads.
-  const RowDmaLane<D, 4 * RH> rl = row_dma_lane<D, 4 * RH>(tm, p.L, wave, lane);
-  using Toks = RowTokens<D, 4 * RH>;
+  const RowDmaLane<D, 4> rl = row_dma_lane<D, 4>(tm, p.L, wave, lane, p.Hq);
+  using Toks = RowTokens<D, 4>;
+  // dense map whose row tiles hold 128 real rows, tensors within reach of a 32-bit offset: copies of whole row
+  // tiles take the short form
+  const bool fast_rows = !LISTED && tm.A * tm.K == kRowsPerTile && p.fast_rows;
+  auto issue_fast = [&](int hh, int rt, int buf) {
+    char* base = lds + buf * kBufBytes;
+    const size_t row0 = ((size_t)rt * tm.A * p.Hq + hh) * D;
+    dma_row_tile_fast<D, 4>(base, p.q + row0, rl, wave);
+    dma_row_tile_fast<D, 4>(base + kTileBytes, p.d_o + row0, rl, wave);
+    float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
+    const size_t s0 = (size_t)hh * p.T + (size_t)rt * tm.A;
+    if (wave < 2) dma_row_stat_fast<D, 4>(stat, p.nlse + s0, rl, wave & 1);
+    else if (wave < 4) dma_row_stat_fast<D, 4>(stat + kRowsPerTile, p.delta + s0, rl, wave & 1);
+  };
   auto issue = [&](int hh, const Toks& t, int buf) {
     char* base = lds + buf * kBufBytes;
-    dma_row_tile<D, 4 * RH>(base, p.q, p.Hq, hh, tm, rl, t, wave);
-    dma_row_tile<D, 4 * RH>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rl, t, wave);
+    dma_row_tile<D, 4>(base, p.q, p.Hq, hh, tm, rl, t, wave);
+    dma_row_tile<D, 4>(base + kTileBytes, p.d_o, p.Hq, hh, tm, rl, t, wave);
     float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
-    if (wave < 2) dma_row_stat<D, 4 * RH>(stat, p.nlse, p.T, hh, tm, t, wave & 1);
-    else if (wave < 4) dma_row_stat<D, 4 * RH>(stat + kRowsPerTile, p.delta, p.T, hh, tm, t, wave & 1);
+    if (wave < 2) dma_row_stat<D, 4>(stat, p.nlse, p.T, hh, tm, t, wave & 1);
+    else if (wave < 4) dma_row_stat<D, 4>(stat + kRowsPerTile, p.delta, p.T, hh, tm, t, wave & 1);
   };
   // Iteration `it` handles row tile ei = it % n_row_tiles of head h_lo + it / n_row_tiles.  The
   // pipeline runs three deep: the list entry of iteration it+3 is fetched now and moved to scalar
@@ -837,7 +935,7 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
   int rt_n = 0, rt_a = 0, mask_c = kSkip, mask_n = kSkip;
   Toks tok_n{};
   if (n_iter > 0) {
-    const Toks t0 = row_tokens<D, 4 * RH, LISTED>(tm, rl, take_entry(fetch_row_tile(0)).tile, p.L);
+    const Toks t0 = row_tokens<D, 4, LISTED>(tm, rl, take_entry(fetch_row_tile(0)).tile, p.L);
     issue(h_lo, t0, 0);
     tok_n = t0;
     mask_c = mask_of(0, take_entry(fetch_mask(0)));
@@ -849,7 +947,7 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     step(ei_b, hh_b);
     if (n_iter > 1) {
       rt_n = take_entry(fetch_row_tile(ei_n)).tile;
-      if (LISTED) tok_n = row_tokens<D, 4 * RH, LISTED>(tm, rl, rt_n, p.L);
+      if (LISTED) tok_n = row_tokens<D, 4, LISTED>(tm, rl, rt_n, p.L);
       mask_n = mask_of(ei_n, take_entry(fetch_mask(ei_n)));
     }
     if (n_iter > 2) rt_a = take_entry(fetch_row_tile(ei_a)).tile;
@@ -863,28 +961,28 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     const u32x2 mask_raw = fetch_mask(have2 ? ei_a : 0);
     Toks tok_a = tok_n;
     if (LISTED) {
-      if (have2) tok_a = row_tokens<D, 4 * RH, LISTED>(tm, rl, rt_a, p.L);
+      if (have2) tok_a = row_tokens<D, 4, LISTED>(tm, rl, rt_a, p.L);
       if (it + 1 < n_iter) issue(hh_n, tok_n, buf ^ 1);
     } else {
-      if (it + 1 < n_iter) issue(hh_n, row_tokens<D, 4 * RH, LISTED>(tm, rl, rt_n, p.L), buf ^ 1);
+      if (it + 1 < n_iter) {
+        if (fast_rows && (rt_n + 1) * tm.A <= p.L) issue_fast(hh_n, rt_n, buf ^ 1);
+        else issue(hh_n, row_tokens<D, 4, LISTED>(tm, rl, rt_n, p.L), buf ^ 1);
+      }
     }
     if (mask_c != kSkip) {
       const char* q_lds = lds + buf * kBufBytes;
       const char* do_lds = q_lds + kTileBytes;
       const float* lse_lds = reinterpret_cast<const float*>(q_lds + 2 * kTileBytes);
       const float* delta_lds = lse_lds + kRowsPerTile;
-      const int row_base = part * (kRowsPerTile / RH);
       if (mask_c == -1) {
-        dkdv_tile<D, RB, 0>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
-                            p.c_log2);
+        dkdv_rowtile_pipelined<D, 0>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, g, p.c_log2);
       } else if (mask_c >= 0) {
-        const uint32_t* mrow = tm.masks + (size_t)mask_c * kRowsPerTile * 2 + (kblk & 1);
-        dkdv_tile<D, RB, 1>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, mrow,
-                            p.c_log2);
+        // which of the tile's 128 rows see this lane's key: four words, one per 32-row unit
+        const u32x4 cm = *reinterpret_cast<const u32x4*>(tm.masks_by_key + ((size_t)mask_c * kKeysPerTile + (kblk & 1) * 32 + ln) * 4);
+        dkdv_rowtile_pipelined<D, 1>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, g, p.c_log2, false, cm);
       } else if (LISTED) {  // only packed maps carry such ids
         const bool lane_off = key_anchor < -mask_c - 2;
-        dkdv_tile<D, RB, 2>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, row_base, g, ln, nullptr,
-                            p.c_log2, lane_off);
+        dkdv_rowtile_pipelined<D, 2>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, g, p.c_log2, lane_off);
       }
     }
     dma_publish();
@@ -898,47 +996,8 @@ __global__ __launch_bounds__(256 * RH, (D == 64 && RH == 1 ? 2 : 1)) void dkdv_k
     step(ei_b, hh_b);
   }
 
-  // sum the row parts through LDS (part 0 owns the result), then store from registers:
-  // lane <-> key, registers <-> d = db*32 + 8*q4 + 4g + j
-  if (RH > 1) {
-    f32x4* red = reinterpret_cast<f32x4*>(lds);
-    constexpr int kPerLane = 2 * (D / 32) * 4;  // f32x4 pieces per lane
-    if (part > 0) {
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 a, c;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            a[j] = dk[db][4 * q4 + j];
-            c[j] = dv[db][4 * q4 + j];
-          }
-          const int slot = ((part - 1) * 4 + kblk) * kPerLane;
-          red[(size_t)(slot + db * 8 + q4 * 2 + 0) * 64 + lane] = a;
-          red[(size_t)(slot + db * 8 + q4 * 2 + 1) * 64 + lane] = c;
-        }
-    }
-    __syncthreads();
-    if (part == 0) {
-#pragma unroll
-      for (int pp = 1; pp < RH; ++pp)
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const int slot = ((pp - 1) * 4 + kblk) * kPerLane;
-            const f32x4 a = red[(size_t)(slot + db * 8 + q4 * 2 + 0) * 64 + lane];
-            const f32x4 c = red[(size_t)(slot + db * 8 + q4 * 2 + 1) * 64 + lane];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              dk[db][4 * q4 + j] += a[j];
-              dv[db][4 * q4 + j] += c[j];
-            }
-          }
-    }
-  }
-  if (part == 0 && tile_present) {
+  // store from registers: lane <-> key, registers <-> d = db*32 + 8*q4 + 4g + j
+  if (tile_present) {
     float* dkd;
     float* dvd;
     bool write = true, accumulate = false;
@@ -1445,11 +1504,11 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
       TimedSpan span(timer, kKindDkDv, stream);
       const bool listed = p.tm.row_tok != nullptr;
       if (D == 64) {
-        if (listed) hipLaunchKernelGGL((dkdv_kernel<64, 1, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((dkdv_kernel<64, 1, false>), grid, dim3(256), 0, stream, p);
+        if (listed) hipLaunchKernelGGL((dkdv_kernel<64, true>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((dkdv_kernel<64, false>), grid, dim3(256), 0, stream, p);
       } else {
-        if (listed) hipLaunchKernelGGL((dkdv_kernel<128, 1, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((dkdv_kernel<128, 1, false>), grid, dim3(256), 0, stream, p);
+        if (listed) hipLaunchKernelGGL((dkdv_kernel<128, true>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((dkdv_kernel<128, false>), grid, dim3(256), 0, stream, p);
       }
       hipError_t e = span.finish();
       if (e != hipSuccess) return e;

@@ -139,6 +139,22 @@ __device__ __forceinline__ void dma16_untracked(const void* gsrc, uint32_t lds_a
 __device__ __forceinline__ void dma4_untracked(const void* gsrc, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(gsrc), "s"(lds_addr) : "memory", "m0");
 }
+// The same copies with the global address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset: when the offsets of a lane do not change from tile to tile, a copy costs no vector
+// instruction at all.  The offset is unsigned: the addressed range must lie within 4 GiB of the base.
+__device__ __forceinline__ void dma16_untracked(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4_untracked(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
+}
+// A pointer the compiler can prove wave-uniform (so that it lives in scalar registers).
+template <class T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+  const uint64_t u = (uint64_t)(uintptr_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return reinterpret_cast<const T*>((uintptr_t)(((uint64_t)hi << 32) | lo));
+}
 #pragma clang diagnostic pop
 
 // Wait until every global -> LDS copy this wave has issued has landed (vmcnt(0)), then

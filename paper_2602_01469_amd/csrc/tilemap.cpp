@@ -101,17 +101,18 @@ int upload_map(peagle_tilemap* tm, hipStream_t stream, bool wait) {
   if (tm->device < 0) return PEAGLE_OK;
   int prev = -1;
   if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(tm->device) != hipSuccess) return PEAGLE_EHIP;
-  constexpr int kArrays = 11;
+  constexpr int kArrays = 12;
   static const char kZeros[256] = {0};
   const size_t sz[kArrays] = {tm->row_ptr.size() * sizeof(int32_t), tm->row_entries.size() * sizeof(TileEntry),
                               tm->key_ptr.size() * sizeof(int32_t), tm->key_entries.size() * sizeof(TileEntry),
                               tm->masks.size() * sizeof(uint32_t), tm->key_seg_ptr.size() * sizeof(int32_t),
                               sizeof(kZeros), tm->row_lead.size() * sizeof(int32_t),
                               tm->row_tok.size() * sizeof(int32_t), tm->chain_tok.size() * sizeof(int32_t),
-                              tm->tok_posid.size() * sizeof(int32_t)};
+                              tm->tok_posid.size() * sizeof(int32_t), tm->masks.size() * sizeof(uint32_t)};
   const void* src[kArrays] = {tm->row_ptr.data(), tm->row_entries.data(), tm->key_ptr.data(),
                               tm->key_entries.data(), tm->masks.data(), tm->key_seg_ptr.data(), kZeros,
-                              tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data(), tm->tok_posid.data()};
+                              tm->row_lead.data(), tm->row_tok.data(), tm->chain_tok.data(), tm->tok_posid.data(),
+                              nullptr /* the key-major masks are written into the staging image below */};
   size_t off[kArrays], total = 0;
   for (int i = 0; i < kArrays; ++i) {
     off[i] = total;
@@ -140,7 +141,20 @@ int upload_map(peagle_tilemap* tm, hipStream_t stream, bool wait) {
   }
   if (err == hipSuccess) {
     for (int i = 0; i < kArrays; ++i)
-      if (sz[i]) std::memcpy((char*)tm->staging + off[i], src[i], sz[i]);
+      if (sz[i] && src[i]) std::memcpy((char*)tm->staging + off[i], src[i], sz[i]);
+    // key-major copy of every mask for the dK/dV kernel, whose lanes own keys: word r/32 of key k has bit r%32
+    // set iff row r sees key k
+    uint32_t* mt = (uint32_t*)((char*)tm->staging + off[11]);
+    for (int32_t m = 0; m < tm->n_masks; ++m)
+      for (int k = 0; k < kKeysPerTile; ++k)
+        for (int w = 0; w < kRowsPerTile / 32; ++w) {
+          uint32_t bits = 0;
+          for (int b = 0; b < 32; ++b) {
+            const uint32_t rw = tm->masks[(size_t)m * kMaskWords + (size_t)(w * 32 + b) * kMaskWordsPerRow + k / 32];
+            bits |= ((rw >> (k % 32)) & 1u) << b;
+          }
+          mt[(size_t)m * kMaskWords + (size_t)k * (kRowsPerTile / 32) + w] = bits;
+        }
     err = hipMemcpyAsync(tm->dev_blob, tm->staging, total, hipMemcpyHostToDevice, stream);
   }
   if (err == hipSuccess) err = hipEventRecord((hipEvent_t)tm->copy_done, stream);
@@ -160,6 +174,7 @@ int upload_map(peagle_tilemap* tm, hipStream_t stream, bool wait) {
   tm->dview.row_tok = tm->row_tok.empty() ? nullptr : (const int32_t*)(base + off[8]);
   tm->dview.chain_tok = tm->chain_tok.empty() ? nullptr : (const int32_t*)(base + off[9]);
   tm->dview.tok_posid = tm->tok_posid.empty() ? nullptr : (const int32_t*)(base + off[10]);
+  tm->dview.masks_by_key = (const uint32_t*)(base + off[11]);
   tm->dview.A = tm->A;
   tm->dview.K = tm->K;
   tm->dview.S = tm->S;

@@ -33,7 +33,8 @@ struct DeviceTileMap {
   const int32_t* key_ptr;     // [n_key_tiles + 1]  offsets into key_entries (row tiles ascending)
   const TileEntry* key_entries;
   const int32_t* key_seg_ptr; // [n_key_tiles][S + 1]  offsets into key_entries: where each segment's row tiles start
-  const uint32_t* masks;      // [n_masks][128][2]
+  const uint32_t* masks;      // [n_masks][128][2]: bit k%32 of word k/32 of row r: row r sees key k
+  const uint32_t* masks_by_key;  // [n_masks][64][4]: the same bits key-major (bit r%32 of word r/32 of key k)
   const void* zeros;          // 256 zero bytes: source of rows that do not exist, for direct-to-LDS loads
   const int32_t* row_tok;     // sampled maps only (else null): [n_row_tiles][128] token of each row, -1 = no row
   const int32_t* chain_tok;   // sampled maps only: [n_row_tiles * n_csub][64] token of each chain key, -1 = none
