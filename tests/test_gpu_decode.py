@@ -66,6 +66,11 @@ DECODE = [
     ("mha_k1_plain_decode", (500, 77), 1, 4, 4, 64, 1060),
     ("k7_d128_odd_group", (1000, 257, 5), 7, 9, 3, 128, 1070),
     ("long_context_many_splits", (20000, 4096), 7, 64, 8, 64, 1080),
+    # 16 requests x 8 KV heads -> 8 context pieces; 131 block-table columns -> 17 pages per piece: the variant
+    # with four tile buffers and three copies in flight (more than 16 pages per piece at D = 64).  An odd tail,
+    # an empty request, one-page and page-edge requests and K < 8 in the same batch.
+    ("deep_ring_mixed_batch", (8371, 0, 77, 8257, 1000, 64, 8192, 3, 4097, 129, 0, 6000, 8384, 511, 2048, 65),
+     5, 32, 8, 64, 1090),
 ]
 
 
@@ -79,6 +84,9 @@ def test_draft_decode_matches_oracle(name, ctx_lens, K, Hq, Hkv, D, seed):
     _check(inp, o, lse, r.shape.scale, name)
     o2, lse2, _ = r.run()                                   # same buffers, same workspace: identical bits
     assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+    if name == "deep_ring_mixed_batch":                     # the case exists to reach the four-buffer variant
+        pages_per_piece = -(-r.shape.max_pages // pe.peagle_draft_decode_splits(r.shape))
+        assert D == 64 and pages_per_piece > 16, pages_per_piece
 
 
 def test_draft_decode_large_logits():

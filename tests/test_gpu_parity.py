@@ -25,30 +25,43 @@ def _need_gpu():
         pytest.skip("no GPU")
 
 
-V_MAX = 5.5  # largest |V| drawn by the generators here (N(0,1), up to ~1e8 draws)
+# Share of O elements that may exceed 1e-2 (only where the bf16 formats force it, see _check_o_abs): such
+# elements need |O| >= 2, i.e. a row that puts nearly all its weight on one key whose |V| is at least 2.
+O_OVER_CAP = 2e-5
 
 
-def _check_o_abs(o, ref, what):
-    """|O - ref| <= 1e-2 wherever the bf16 output format allows it.  O is stored in bf16 and the
-    probabilities enter the PV product in bf16 (8-bit significand), so an element carries up to
-    half an output ulp (<= 2^-8 |O|) plus the effect of probability rounding, at worst
-    2^-8 max|V| (two equally weighted keys rounded in opposite directions with opposite V); the
-    check allows half of that worst case.  Where this derived bound is below 1e-2 the fixed
-    bound applies."""
+def _bf16_half_ulp(x):
+    """Half the spacing of bf16 numbers (8-bit significand) at |x|."""
+    return 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -126))) - 8)
+
+
+def _check_o_abs(o, ref, what, extra=0.0):
+    """|O - ref| <= 1e-2 for every element the bf16 formats allow it for, i.e. wherever |ref| < 2.
+
+    O is stored in bf16 and the probabilities enter P V in bf16 (the path's stated arithmetic): an element
+    carries up to half an output ulp plus, when the row's weight sits on few keys, up to 2^-9 |O| from the
+    rounding of those probabilities.  Below |O| = 2 that is at most 2^-8 + 2^-8 = 7.8e-3, inside the fixed
+    bound, which is then applied as it stands.  From |O| = 2 on the two terms alone reach 1.2e-2, so there the
+    bound is half an output ulp + 2^-9 |O| + 2e-3 for everything else; the count of elements above 1e-2 is
+    printed and capped.  ``extra`` widens every bound by a stated, derived amount (operand rounding that the
+    reference does not share: the rotary tests)."""
     err = np.abs(o - ref)
-    bound = np.maximum(FWD_MAX_ABS, np.abs(ref) * 2.0 ** -8 + V_MAX * 2.0 ** -9)
+    forced = _bf16_half_ulp(ref) + np.abs(ref) * 2.0 ** -9 + 2e-3
+    bound = np.where(np.abs(ref) < 2.0, FWD_MAX_ABS, np.maximum(FWD_MAX_ABS, forced)) + extra
     bad = err > bound
     if bad.any():
         w = np.unravel_index(np.argmax(err - bound), err.shape)
         raise AssertionError(f"{what}: {int(bad.sum())} O elements over the bound; worst at {w}: got {o[w]!r} "
                              f"ref {ref[w]!r} err {err[w]:.3e} bound {bound[w]:.3e}; max err {err.max():.3e}")
-    print(f"{what}: O max abs err {err.max():.3e} (over 1e-2: {int((err > FWD_MAX_ABS).sum())} of {err.size})", flush=True)
+    over = int((err > FWD_MAX_ABS + extra).sum())
+    print(f"{what}: O max abs err {err.max():.3e} (over 1e-2: {over} of {err.size}, all at |O| >= 2)", flush=True)
+    assert over <= max(1, int(O_OVER_CAP * err.size)), (what, over, err.size)
 
 
-def _check_against_oracle(got, ref, what="", lse_abs=LSE_ABS):
+def _check_against_oracle(got, ref, what="", lse_abs=LSE_ABS, o_abs_extra=0.0):
     assert not any(np.isnan(got[n]).any() for n in got), what
     assert rel_l2(got["O"], ref["O"]) <= FWD_REL, what
-    _check_o_abs(got["O"], ref["O"], what)
+    _check_o_abs(got["O"], ref["O"], what, o_abs_extra)
     assert max_abs(got["LSE"], ref["LSE"]) <= lse_abs, what
     for n in ("dQ", "dK", "dV"):
         assert rel_l2(got[n], ref[n]) <= GRAD_REL, (what, n)
@@ -125,6 +138,31 @@ def test_small_cases_match_oracle(name, L, K, Hq, Hkv, D, seed, bounds, L_max):
         g4 = r4.results()
         for n in ("dK", "dV"):
             assert rel_l2(g4[n], got[n]) <= PART_REL, n
+
+
+@pytest.mark.parametrize("bounds", [None, [0, 1040, 1500]], ids=["one_pass", "two_segments"])
+def test_dense_segments_longer_than_one_dkdv_launch(bounds):
+    """94 row tiles in one segment (or 65 + 29): the dK/dV launcher cuts a dense segment into launches of at
+    most 64 row tiles, later launches adding to what earlier ones wrote, each followed by its own reduction;
+    every element of every output against the oracle."""
+    L, K, Hq, Hkv, D, seed = 1500, 8, 2, 1, 64, 290
+    print(f"case dense long segments: L={L} K={K} Hq={Hq} Hkv={Hkv} D={D} seed={seed} bounds={bounds}", flush=True)
+    qb, kb, vb, dob = (rand_bits((L * K, H, D), seed + i) for i, H in enumerate((Hq, Hkv, Hkv, Hq)))
+    tm = pe.peagle_build_tilemap(L, K, bounds, device=0)
+    r = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+    r.step(0, 1 if bounds is None else len(bounds) - 1)
+    got = r.results()
+    ref = _oracle(qb, kb, vb, dob, L, K, r.shape.scale)
+    _check_against_oracle(got, ref, f"dense long segments {bounds}")
+    for n in ("dK", "dV"):                      # no key left out or counted twice at a launch boundary
+        assert max_abs(got[n], ref[n]) <= 2e-2 * np.abs(ref[n]).max(), n
+    r.fwd()                                     # the single-segment entry points take the same path
+    r.bwd()
+    whole = r.results()
+    for n in ("O", "LSE", "dQ"):
+        assert np.array_equal(whole[n], got[n]), n
+    for n in ("dK", "dV"):
+        assert rel_l2(got[n], whole[n]) <= PART_REL, n
 
 
 @pytest.mark.parametrize("qscale", [12.0, 40.0])
@@ -288,6 +326,31 @@ def test_full_size_partitioned_configs(name):
         assert np.array_equal(whole[n], got[n]), n
     for n in ("dK", "dV"):
         assert rel_l2(got[n], whole[n]) <= PART_REL, n
+
+
+def test_c3_median_one_whole_kv_group_all_rows():
+    """Config 3 as the benchmark runs it (4 segments), the oracle on one complete KV group - its 8 query heads,
+    all 32,768 rows - so that O, LSE, dQ of every row and dK, dV of every key of the group are compared.  The
+    oracle runs segment by segment as well (its own partitioned form, which holds a segment's rows and keys)."""
+    cfg = CONFIGS["c3_median"]
+    print(f"case {cfg.name}: whole KV group, generating inputs", flush=True)
+    qb, kb, vb, dob = make_inputs(cfg)
+    b = cfg.seg_bounds()
+    tm = pe.peagle_build_tilemap(cfg.L, cfg.K, b, device=0)
+    r = Run(tm, cfg.L, cfg.K, cfg.Hq, cfg.Hkv, cfg.D, qb, kb, vb, dob, cfg.scale)
+    r.step(0, len(b) - 1)
+    got = r.results()
+    g = 2
+    grp = cfg.Hq // cfg.Hkv
+    hs = slice(g * grp, (g + 1) * grp)
+    print(f"case {cfg.name}: oracle on KV head {g} (query heads {g * grp}..{(g + 1) * grp - 1}), all rows", flush=True)
+    q, k, v, do = (bf16_bits_to_f64(x) for x in (qb[:, hs], kb[:, g:g + 1], vb[:, g:g + 1], dob[:, hs]))
+    ref = orc.attn_step_partitioned(q, k, v, do, cfg.L, cfg.K, cfg.scale, b, row_block=2048)
+    sub = {"O": got["O"][:, hs], "LSE": got["LSE"][hs], "dQ": got["dQ"][:, hs], "dK": got["dK"][:, g:g + 1],
+           "dV": got["dV"][:, g:g + 1]}
+    _check_against_oracle(sub, ref, cfg.name + " whole group")
+    for n in ("dK", "dV"):
+        assert max_abs(sub[n], ref[n]) <= 2e-2 * np.abs(ref[n]).max(), n
 
 
 def test_c5_p99_stress_prefix_and_samples():

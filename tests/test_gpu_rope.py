@@ -20,6 +20,11 @@ BASE = 500000.0      # LLaMA 3
 # inputs at scale = 1/sqrt(D).  A row's LSE moves by at most its largest score error; five standard
 # deviations on top of the plain path's bound (2^-8 from the bf16 probabilities):
 LSE_ABS_ROPE = LSE_ABS + 8e-3
+# The same score errors d_j move an output element by sum_j p_j (v_j - O) d_j, standard deviation
+# 1.6e-3 * sqrt(sum_j p_j^2 (v_j - O)^2) <= 1.6e-3 for a row whose weight sits on a few keys of unit-variance V;
+# five standard deviations on top of the plain path's bound.  Every case is also compared at the plain bound with
+# the oracle fed the rotated operands as stored (bf16), which carries no such term.
+O_ABS_ROPE_EXTRA = 8e-3
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -115,7 +120,8 @@ def _oracle_rope_stored(qb, kb, vb, dob, L, K, scale, bounds, tokens=None):
 
 
 def _check_rope(got, qb, kb, vb, dob, L, K, scale, bounds, name, tokens=None):
-    _check_against_oracle(got, _oracle_rope(qb, kb, vb, dob, L, K, scale, bounds, tokens), name, lse_abs=LSE_ABS_ROPE)
+    _check_against_oracle(got, _oracle_rope(qb, kb, vb, dob, L, K, scale, bounds, tokens), name, lse_abs=LSE_ABS_ROPE,
+                          o_abs_extra=O_ABS_ROPE_EXTRA)
     _check_against_oracle(got, _oracle_rope_stored(qb, kb, vb, dob, L, K, scale, bounds, tokens), name + " (stored operands)")
 
 
@@ -234,7 +240,7 @@ def test_rope_full_size_c3_sampled_rows():
     rows = np.concatenate([d * L + anchors for d in range(K)])
     ref = orc.attn_backward(q, k, v, do, L, K, cfg.scale, rows=rows, row_block=256)
     assert rel_l2(got["O"][rows][:, hs], ref["O"]) <= FWD_REL
-    _check_o_abs(got["O"][rows][:, hs], ref["O"], "rope " + cfg.name)
+    _check_o_abs(got["O"][rows][:, hs], ref["O"], "rope " + cfg.name, O_ABS_ROPE_EXTRA)
     assert max_abs(got["LSE"][hs][:, rows], ref["LSE"]) <= LSE_ABS_ROPE
     assert rel_l2(got["dQ"][rows][:, hs], orc.rope_rotate(ref["dQ"], pos[rows], BASE, inverse=True)) <= GRAD_REL
     tail = 40       # keys of the last anchors are seen only by rows of those anchors
@@ -285,7 +291,7 @@ def test_rope_step_replays_from_a_hip_graph():
         for n, t in (("o", r.o), ("lse", r.lse), ("dq", r.dq), ("dk", r.dk), ("dv", r.dv)):
             assert torch.equal(got[n], t), (rep, n)
     ref = _oracle_rope(qb, kb, vb, dob, L, K, r.shape.scale, bounds)
-    _check_against_oracle(r.results(), ref, "rope graph replay", lse_abs=LSE_ABS_ROPE)
+    _check_against_oracle(r.results(), ref, "rope graph replay", lse_abs=LSE_ABS_ROPE, o_abs_extra=O_ABS_ROPE_EXTRA)
 
 
 SHARED_CASES = [
@@ -345,7 +351,7 @@ def test_rope_step_with_shared_chain_vectors_matches_oracle(name, seq_lens, K, H
                                     tokens=tokens)
     assert not any(np.isnan(got[n]).any() for n in got)
     assert rel_l2(got["O"], ref["O"]) <= FWD_REL
-    _check_o_abs(got["O"], ref["O"], name)
+    _check_o_abs(got["O"], ref["O"], name, O_ABS_ROPE_EXTRA)
     assert max_abs(got["LSE"], ref["LSE"]) <= LSE_ABS_ROPE
     for n in ("dQ", "dK0", "dV0"):
         assert rel_l2(got[n], ref[n]) <= GRAD_REL, n
