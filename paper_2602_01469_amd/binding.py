@@ -57,7 +57,8 @@ class _ProfileC(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, _LIB_NAME)
+    """The in-tree build; PEAGLE_ATTN_LIB names another build of the same sources (the host-sanitizer test's)."""
+    return os.environ.get("PEAGLE_ATTN_LIB") or os.path.join(_HERE, _LIB_NAME)
 
 
 def load_library():

@@ -13,13 +13,20 @@ SOURCES = ["tilemap.cpp", "api.cpp", "attn_kernels.hip", "rope_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, sanitize_host_to: str = "") -> str:
+    """Builds the library in-tree.  With `sanitize_host_to`, builds a second library at that path instead whose HOST
+    code (tile-map builder, argument validation, launch drivers) carries AddressSanitizer and
+    UndefinedBehaviorSanitizer; the device code is the same (no sanitizer runs on the GPU)."""
+    out_path = sanitize_host_to or LIB
+    opt = ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer",
+           "-shared-libsan"] if sanitize_host_to else ["-O3"]
     cmd = [
-        HIPCC, "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+        HIPCC, "-x", "hip", "--offload-arch=gfx950", *opt, "-std=c++17", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-fgpu-flush-denormals-to-zero", "-Wno-unused-command-line-argument",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-        "-o", LIB,
+        "-o", out_path,
     ] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
@@ -29,7 +36,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out:
         print(out)
-    return LIB
+    return out_path
 
 
 if __name__ == "__main__":

@@ -6,6 +6,7 @@
 
 #include "attn_kernels.h"
 #include "peagle.h"
+#include "peagle_bench.h"
 #include "tilemap.h"
 
 using peagle::BwdParams;

@@ -32,7 +32,7 @@ def _expanded(tm, L, K, seg, rows):
 
 def test_library_exports_every_declared_symbol():
     lib = pe.load_library()
-    header = open(os.path.join(ROOT, "include", "peagle.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("peagle.h", "peagle_bench.h"))
     declared = set(re.findall(r"\b(peagle_[a-z_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
@@ -207,6 +207,7 @@ def test_compute_entry_points_validate_before_launch():
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_NAME", "libdoes_not_exist.so")
+    monkeypatch.delenv("PEAGLE_ATTN_LIB", raising=False)
     with pytest.raises(ImportError):
         binding.load_library()
 
