@@ -343,25 +343,28 @@ def attn_step_partitioned_sampled(q, k, v, do, depth_count: Sequence[int], K: in
 
 
 def partition_assign(positions: Sequence[Sequence[int]], S: int, L: int) -> Tuple[List[Dict[int, int]], List[List[int]]]:
-    """Segment assignment of Algorithm 1 for (possibly COD-sampled) position sets.
+    """Segment of every kept position (Algorithm 1; Sec. 3.2, Challenge 2) for possibly COD-sampled position sets.
 
-    ``positions[g]`` lists the sequence positions kept at depth g.  Boundaries are
-    B_s = s*L/S.  Depths 0 and 1 are assigned by position (largest s with B_s <= p);
-    a position p at depth g >= 2 inherits the segment of position p-1 at depth g-1;
-    segment s additionally carries the depth-0 positions below B_{s+1}.
+    ``positions[g]`` lists the sequence positions kept at depth g.  The sequence is cut at s*L/S.  What must
+    stay together is a dependency chain: position p at depth g needs position p-1 at depth g-1, and so on
+    down to depth 1, so the chain through (p, g) starts at the depth-1 position p-g+1 and every member goes
+    to the segment in which that head position lies.  Depth-0 positions go by their own position, and
+    segment s also carries, as context, every depth-0 position before the cut that ends it.
 
-    Returns (A, N): A[g] maps position -> segment, N[s] lists cumulative depth-0 positions.
+    Returns (A, N): A[g] maps position -> segment, N[s] lists the cumulative depth-0 positions.
     """
-    Kd = len(positions)
-    B = [s * L / S for s in range(S + 1)]
-    A: List[Dict[int, int]] = [dict() for _ in range(Kd)]
-    for g in range(min(2, Kd)):
+    def segment_holding(position: int) -> int:          # the last cut at or before the position
+        return max(s for s in range(S) if s * L / S <= position)
+
+    kept = [set(ps) for ps in positions]
+    A: List[Dict[int, int]] = [{p: segment_holding(p) for p in ps} for ps in positions[:1]]
+    for g in range(1, len(positions)):
+        A.append({})
         for p in positions[g]:
-            A[g][p] = max(s for s in range(S) if B[s] <= p)
-    for g in range(2, Kd):
-        for p in positions[g]:
-            A[g][p] = A[g - 1][p - 1]
-    N = [[p for p in positions[0] if p < B[s + 1]] for s in range(S)]
+            head = p - (g - 1)                          # the chain's depth-1 member
+            assert all(p - j in kept[g - j] for j in range(1, g)), "a kept position needs the chain below it"
+            A[g][p] = segment_holding(head)
+    N = [[p for p in positions[0] if p < (s + 1) * L / S] for s in range(S)]
     return A, N
 
 

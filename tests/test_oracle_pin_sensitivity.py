@@ -31,7 +31,7 @@ MUTATIONS = [
      [("test_finite_differences", ())]),
     ("segment keys without the cumulative depth-0 context", "n0 = np.arange(0, b_hi)", "n0 = np.arange(b_lo, b_hi)",
      [("test_partitioned_equals_unpartitioned", ([0, 5, 16],))]),
-    ("deeper depths do not inherit their segment", "A[g][p] = A[g - 1][p - 1]", "A[g][p] = max(s for s in range(S) if B[s] <= p)",
+    ("deeper depths do not inherit their segment", "A[g][p] = segment_holding(head)", "A[g][p] = segment_holding(p)",
      [("test_partition_worked_example_from_paper", ())]),
     ("rotation turned the wrong way for gradients", "    if inverse:\n        s = -s\n", "    if inverse:\n        s = s\n",
      [("test_rope_step_gradients_against_finite_differences", ()), ("test_rope_is_an_isometry_with_the_transpose_as_inverse", ())]),
