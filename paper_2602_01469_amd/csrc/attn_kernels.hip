@@ -209,12 +209,18 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
 
 // The same two copies for a row tile of a dense map whose 128 rows all exist (see RowDmaLane::fast_off):
 // `row0` = the head's row of the tile's first anchor at depth 0 (wave-uniform).
+// `step` != 0: the rows a lane copies are NW * 512/D apart, a whole number of depths (A divides that), so copy i
+// reads `step` elements behind copy i-1 for every lane: the step goes into the scalar base and one per-lane
+// offset serves all copies.
 template <int D, int NW>
-__device__ __forceinline__ void dma_row_tile_fast(char* lds_tile, const __bf16* row0, const RowDmaLane<D, NW>& rl, int wave) {
+__device__ __forceinline__ void dma_row_tile_fast(char* lds_tile, const __bf16* row0, const RowDmaLane<D, NW>& rl, int wave,
+                                                  size_t step) {
   const uint32_t dst = lds_scalar_addr(lds_tile + wave * 1024);
-  const __bf16* base = uniform_ptr(row0);
 #pragma unroll
-  for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) dma16_untracked(base, rl.fast_off[i], dst + i * NW * 1024);
+  for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
+    if (step) dma16_untracked(uniform_ptr(row0 + i * step), rl.fast_off[0], dst + i * NW * 1024);
+    else dma16_untracked(uniform_ptr(row0), rl.fast_off[i], dst + i * NW * 1024);
+  }
 }
 template <int D, int NW>
 __device__ __forceinline__ void dma_row_stat_fast(float* lds_stat, const float* stat0, const RowDmaLane<D, NW>& rl, int half) {
@@ -885,11 +891,13 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
   // dense map whose row tiles hold 128 real rows, tensors within reach of a 32-bit offset: copies of whole row
   // tiles take the short form
   const bool fast_rows = !LISTED && tm.A * tm.K == kRowsPerTile && p.fast_rows;
+  constexpr int kRowsApart = 4 * (512 / D);  // between the rows a lane copies
+  const size_t fast_step = kRowsApart % tm.A == 0 ? (size_t)(kRowsApart / tm.A) * p.L * p.Hq * D : 0;
   auto issue_fast = [&](int hh, int rt, int buf) {
     char* base = lds + buf * kBufBytes;
     const size_t row0 = ((size_t)rt * tm.A * p.Hq + hh) * D;
-    dma_row_tile_fast<D, 4>(base, p.q + row0, rl, wave);
-    dma_row_tile_fast<D, 4>(base + kTileBytes, p.d_o + row0, rl, wave);
+    dma_row_tile_fast<D, 4>(base, p.q + row0, rl, wave, fast_step);
+    dma_row_tile_fast<D, 4>(base + kTileBytes, p.d_o + row0, rl, wave, fast_step);
     float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
     const size_t s0 = (size_t)hh * p.T + (size_t)rt * tm.A;
     if (wave < 2) dma_row_stat_fast<D, 4>(stat, p.nlse + s0, rl, wave & 1);
@@ -921,7 +929,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
     return fetch_entry(tm.key_entries, li >= my_skip ? my_lo + li - my_skip : e_lo + li);
   };
   constexpr int kSkip = INT_MIN;
-  auto mask_of = [&](int ei, const TileEntry& en) { return list_pos(ei) >= my_skip ? en.mask_id : kSkip; };
+  auto mask_of = [&](int ei, const TileEntry& en) {  // (wave-uniform: through readfirstlane so that it stays scalar)
+    return list_pos(ei) >= my_skip ? en.mask_id : kSkip;
+  };
   auto step = [&](int& ei, int& hh) {  // advance (ei, hh) by one iteration
     if (++ei == n_row_tiles) {
       ei = 0;
@@ -957,8 +967,6 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
     const bool have2 = it + 2 < n_iter, have3 = it + 3 < n_iter;
-    const u32x2 rt_raw = fetch_row_tile(have3 ? ei_b : 0);
-    const u32x2 mask_raw = fetch_mask(have2 ? ei_a : 0);
     Toks tok_a = tok_n;
     if (LISTED) {
       if (have2) tok_a = row_tokens<D, 4, LISTED>(tm, rl, rt_a, p.L);
@@ -969,6 +977,10 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
         else issue(hh_n, row_tokens<D, 4, LISTED>(tm, rl, rt_n, p.L), buf ^ 1);
       }
     }
+    // (fetched after the copies were issued: anything the copy code has to wait for - a reloaded register -
+    // then finds no list load in flight)
+    const u32x2 rt_raw = fetch_row_tile(have3 ? ei_b : 0);
+    const u32x2 mask_raw = fetch_mask(have2 ? ei_a : 0);
     if (mask_c != kSkip) {
       const char* q_lds = lds + buf * kBufBytes;
       const char* do_lds = q_lds + kTileBytes;
@@ -978,7 +990,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
         dkdv_rowtile_pipelined<D, 0>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, g, p.c_log2);
       } else if (mask_c >= 0) {
         // which of the tile's 128 rows see this lane's key: four words, one per 32-row unit
-        const u32x4 cm = *reinterpret_cast<const u32x4*>(tm.masks_by_key + ((size_t)mask_c * kKeysPerTile + (kblk & 1) * 32 + ln) * 4);
+        // (scalar base + small per-lane offset: no 64-bit per-lane address is kept across the loop)
+        const uint32_t* mbase = uniform_ptr(tm.masks_by_key + (size_t)__builtin_amdgcn_readfirstlane(mask_c) * kMaskWords);
+        const u32x4 cm = *reinterpret_cast<const u32x4*>(mbase + ((kblk & 1) * 32 + ln) * 4);
         dkdv_rowtile_pipelined<D, 1>(q_lds, do_lds, lse_lds, delta_lds, no, to, kf, vf, dk, dv, g, p.c_log2, false, cm);
       } else if (LISTED) {  // only packed maps carry such ids
         const bool lane_off = key_anchor < -mask_c - 2;
