@@ -52,6 +52,15 @@ int peagle_attn_step_rope_profiled(const peagle_tilemap_t* tm, const peagle_shap
 int peagle_measure_mfma_ceiling(void* stream, float* tflops);
 
 /*
+ * Measurement aid: the same loop on pseudo-random operands (roughly uniform in (-2, 2), every significand
+ * bit in use) that change from instruction to instruction.  The matrix cores draw more power on such data
+ * than on the constant small integers of peagle_measure_mfma_ceiling and the chip lowers its clock to stay
+ * inside its power limit: this is the rate the matrix cores sustain on operands like real Q, K, V.
+ * Same arguments, allocation and synchronisation as peagle_measure_mfma_ceiling.
+ */
+int peagle_measure_mfma_ceiling_random(void* stream, float* tflops);
+
+/*
  * Measurement aid: compute-unit count and peak engine clock (kHz) of the current device, as the
  * HIP runtime reports them (both host ints, out).
  */

@@ -46,7 +46,7 @@ EXPORTS = [
     "peagle_rope_shared_workspace_bytes", "peagle_attn_step_rope_shared",
     "peagle_draft_decode_splits", "peagle_draft_decode_workspace_bytes", "peagle_draft_decode",
     "peagle_draft_decode_static",
-    "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_device_info", "peagle_strerror",
+    "peagle_attn_step_profiled", "peagle_measure_mfma_ceiling", "peagle_measure_mfma_ceiling_random", "peagle_device_info", "peagle_strerror",
 ]
 
 KERNEL_KINDS = ("fwd", "dq", "dkdv", "reduce", "rope")
@@ -135,6 +135,8 @@ def load_library():
     lib.peagle_draft_decode_static.restype = C.c_int
     lib.peagle_measure_mfma_ceiling.argtypes = [vp, C.POINTER(C.c_float)]
     lib.peagle_measure_mfma_ceiling.restype = C.c_int
+    lib.peagle_measure_mfma_ceiling_random.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.peagle_measure_mfma_ceiling_random.restype = C.c_int
     lib.peagle_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
     lib.peagle_device_info.restype = C.c_int
     lib.peagle_strerror.argtypes = [C.c_int]
@@ -554,9 +556,11 @@ def peagle_draft_decode_static(shape: DecodeShape, q_new, k_new, v_new, k_pages,
         raise PeagleError(rc, "peagle_draft_decode_static")
 
 
-def peagle_measure_mfma_ceiling(stream=None) -> float:
+def peagle_measure_mfma_ceiling(stream=None, random_operands: bool = False) -> float:
     out = C.c_float(0.0)
-    rc = load_library().peagle_measure_mfma_ceiling(_stream_ptr(stream), C.byref(out))
+    lib = load_library()
+    fn = lib.peagle_measure_mfma_ceiling_random if random_operands else lib.peagle_measure_mfma_ceiling
+    rc = fn(_stream_ptr(stream), C.byref(out))
     if rc != 0:
         raise PeagleError(rc, "peagle_measure_mfma_ceiling")
     return float(out.value)

@@ -522,7 +522,13 @@ extern "C" int peagle_draft_decode_static(const peagle_decode_shape_t* shape, co
 extern "C" int peagle_measure_mfma_ceiling(void* stream, float* tflops) {
   if (!tflops) return PEAGLE_ENULL;
   *tflops = 0.f;
-  return peagle::measure_mfma_ceiling((hipStream_t)stream, tflops) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+  return peagle::measure_mfma_ceiling((hipStream_t)stream, false, tflops) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
+}
+
+extern "C" int peagle_measure_mfma_ceiling_random(void* stream, float* tflops) {
+  if (!tflops) return PEAGLE_ENULL;
+  *tflops = 0.f;
+  return peagle::measure_mfma_ceiling((hipStream_t)stream, true, tflops) == hipSuccess ? PEAGLE_OK : PEAGLE_EHIP;
 }
 
 extern "C" int peagle_device_info(int32_t* compute_units, int32_t* clock_khz) {

@@ -88,8 +88,9 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
 // below acc_below are added to dk_acc/dv_acc, the others overwritten.
 hipError_t launch_bwd(const BwdParams& p, int D, int key_lo, int a_hi, int acc_below, hipStream_t stream,
                       KernelTimer* timer = nullptr);
-// Dense bf16 MFMA issue loop on every CU: the measured matrix-core ceiling of the device, in TFLOP/s.
-hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops);
+// Dense bf16 MFMA issue loop on every CU: the measured matrix-core ceiling of the device, in TFLOP/s, on
+// constant small-integer operands or on changing pseudo-random ones (the chip clocks lower under the latter).
+hipError_t measure_mfma_ceiling(hipStream_t stream, bool random_operands, float* tflops);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t stream);
 // Rotary embedding: table [n_pos][2][D/2] of cosines and sines; rotation of a bf16 [T, H, D] tensor
 // by each token's position (inverse: the transpose).

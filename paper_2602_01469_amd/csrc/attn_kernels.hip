@@ -639,6 +639,307 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
 }
 
 // =====================================================================================
+// Backward, part 1 with the leading full tiles of a row tile run as one software pipeline (D = 64; same
+// decomposition and results layout as dq_kernel).  The unit of work is a 32-key block, two per key tile.
+// A wave that issues a matrix instruction and then independent vector instructions runs the vector work
+// in the shadow of the matrix pipe, whereas matrix and vector phases that follow one another - in one wave
+// or in several waves of a SIMD - take the sum of their times (see dkdv_rowtile_pipelined).  So while the
+// vector unit turns the scores of unit u into dS, the matrix pipe runs dQ += K^T dS of unit u-1 and S, dP
+// of unit u+1, across key-tile boundaries: three K/V buffers rotate (tile e of the row tile's list lives in
+// buffer e % 3; the pipelined tiles are taken three at a time so that every LDS address is a per-lane
+// register plus an immediate), the copy of tile e+2 is issued when every wave has left tile e-1, and one
+// barrier per tile - between its two units - both frees that buffer and publishes tile e+1.
+//
+// Per-row terms cost no vector instruction here: -Delta is the accumulator input of the first dP
+// instruction (sixteen equal registers per lane, lane <-> row), and the probabilities are left
+// unnormalised, p' = 2^(c s), the factor 2^(-lse) being applied to the row's dQ once at the end.  That is
+// exact as long as 2^(c s) cannot leave the fp32 range, which |lse| <= 64 (log2 units) guarantees for
+// every key of the row; a workgroup with a row outside that range (or a non-finite lse) takes the plain
+// routine with the normalised probabilities for all its tiles.
+// Tiles that carry a bitmask (the diagonal and chain tiles that end a row tile's list) and the up to two
+// full tiles left over by the groups of three go through dq_tile, in the same buffers.
+// =====================================================================================
+constexpr int kDqAhead = 2;
+
+template <int D>
+struct DqPipe {
+  f32x16 sc[2], dpc[2];     // S and dP of the units in flight (index = 32-key block of the unit's tile)
+  u32x4 dsb[2][2];          // dS of a unit as bf16 B operands, per 16-key step
+  bf16x8 ring[kDqAhead];    // A operands on their way from LDS
+};
+
+// A operand of matrix instruction j of a unit's body: first the D/16 transposed K fragments of the unit whose
+// dQ is due (j = 16-key step * D/32 + feature block), then the D/8 natural fragments of the unit whose S / dP
+// start (even: K, odd: V).
+template <int D>
+__device__ __forceinline__ bf16x8 dq_pipe_frag(const char* k_dq, int kb_dq, const char* k_s, const char* v_s, int kb_s,
+                                               const NatOff<D>& no, const TrOff<D>& to, int j) {
+  constexpr int N2 = D / 16;
+  if (j < N2) return frag_tr<D>(k_dq, to, kb_dq * 32 + (j / (D / 32)) * 16, j % (D / 32));
+  const int i = j - N2;
+  return frag_nat<D>((i & 1) ? v_s : k_s, no, kb_s, i >> 1);
+}
+
+// Body of the unit (tile e, block KB): its vector work rides on the matrix instructions dQ of the unit before
+// it (block 1-KB of k_dq: tile e-1 for KB = 0, tile e for KB = 1) and, unless LAST, S / dP of the unit after it
+// (block 1-KB of k_s, v_s: tile e for KB = 0, tile e+1 for KB = 1).  k_self is K of tile e: the next body's
+// dQ fragments (this unit's) are prefetched from it.
+template <int D, int KB, bool LAST>
+__device__ __forceinline__ void dq_pipe_body(DqPipe<D>& P, const char* k_dq, const char* k_s, const char* v_s,
+                                             const char* k_self, const NatOff<D>& no, const TrOff<D>& to,
+                                             const bf16x8 (&qf)[1][D / 16], const bf16x8 (&dof)[1][D / 16],
+                                             f32x16 (&dq)[1][D / 32], const f32x16& ndelta16, float c) {
+  constexpr int N2 = D / 16, NM = LAST ? N2 : N2 + D / 8, O = 1 - KB;
+  static_assert(N2 % kDqAhead == 0 && (D / 8) % kDqAhead == 0, "fragment slots must repeat from body to body");
+#pragma unroll
+  for (int j = 0; j < NM; ++j) {
+    const int slot = j % kDqAhead;
+    const bf16x8 a = P.ring[slot];
+    if (j < N2) {
+      dq[0][j % (D / 32)] = mfma32(a, __builtin_bit_cast(bf16x8, P.dsb[O][j / (D / 32)]), dq[0][j % (D / 32)]);
+    } else {
+      const int i = j - N2, st = i >> 1;
+      if (i & 1) P.dpc[O] = mfma32(a, dof[0][st], st == 0 ? ndelta16 : P.dpc[O]);
+      else P.sc[O] = mfma32(a, qf[0][st], st == 0 ? zero16() : P.sc[O]);
+    }
+    if (j + kDqAhead < NM) {
+      P.ring[slot] = dq_pipe_frag<D>(k_dq, O, k_s, v_s, O, no, to, j + kDqAhead);
+    } else {
+      const int jn = j + kDqAhead - NM;
+      P.ring[slot] = frag_tr<D>(k_self, to, KB * 32 + (jn / (D / 32)) * 16, jn % (D / 32));
+    }
+    // Vector work of the unit, skewed by one matrix instruction: p' = 2^(c s) of a few scores here, their
+    // products with dP and the rounding to bf16 behind the next instruction, so that neighbouring vector
+    // instructions do not depend on one another (registers <-> keys 8*(i/4) + 4g + i%4 of the block).
+    // The empty assembly statements keep each value's computation where it is written: without them the
+    // compiler moves it to the first use, which for dS is the next body.
+    if (j > 0) {
+#pragma unroll
+      for (int i = 16 * (j - 1) / (NM - 1); i < 16 * j / (NM - 1); ++i) {
+        P.sc[KB][i] *= P.dpc[KB][i];
+        if (i & 1) {
+          uint32_t w = pack_bf16(P.sc[KB][i - 1], P.sc[KB][i]);
+          asm volatile("" : "+v"(w));
+          P.dsb[KB][i >> 3][(i & 7) >> 1] = w;
+        }
+      }
+    }
+    if (j + 1 < NM) {
+#pragma unroll
+      for (int i = 16 * j / (NM - 1); i < 16 * (j + 1) / (NM - 1); ++i) {
+        float e = exp2_fast(P.sc[KB][i] * c);
+        asm volatile("" : "+v"(e));
+        P.sc[KB][i] = e;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
+  constexpr int kTileBytes = kKeysPerTile * D * 2;
+  constexpr int N2 = D / 16;
+  constexpr float kLseRange = 64.f;  // log2 units
+  __shared__ __attribute__((aligned(16))) char lds[3][2][kTileBytes];  // [buffer][K|V]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const DeviceTileMap& tm = p.tm;
+  const int group = p.Hq / p.Hkv;
+  int b = blockIdx.x;
+  const int kvh = b % p.Hkv;
+  b /= p.Hkv;
+  const int hc = b % group;
+  const int rt = p.rt_hi - 1 - b / group;  // heaviest row tiles first
+  const int h = kvh * group + hc;
+
+  const int r = wave * 32 + ln;  // row of the tile owned by this lane (shared with lane ^ 32)
+  int tq;
+  const bool row_ok = row_token(tm, rt, r, p.L, tq);
+
+  // The K half of the buffer that the first pipelined body reads its (absent) predecessor from: that body
+  // multiplies it by dS = 0, so it only has to be finite.
+  {
+    uint4* z = reinterpret_cast<uint4*>(lds[2][0]);
+    for (int i = tid; i < kTileBytes / 16; i += 256) z[i] = make_uint4(0, 0, 0, 0);
+  }
+
+  bf16x8 qf[1][D / 16], dof[1][D / 16];
+  float lse2, delta;
+  {
+    const size_t off = ((size_t)(row_ok ? tq : 0) * p.Hq + h) * D + g * 8;
+    float dl = 0.f;
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      qf[0][st] = as_frag(row_ok ? ld16(p.q + off + st * 16) : z);
+      dof[0][st] = as_frag(row_ok ? ld16(p.d_o + off + st * 16) : z);
+      const bf16x8 of = as_frag(row_ok ? ld16(p.o + off + st * 16) : z);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dl = __builtin_fmaf((float)dof[0][st][j], (float)of[j], dl);
+    }
+    delta = sum_halves(dl);
+    lse2 = row_ok ? p.lse[(size_t)h * p.T + tq] * kLog2e : 0.f;
+    if (row_ok && g == 0) {  // per-row terms in the form the dK/dV kernel consumes
+      p.delta[(size_t)h * p.T + tq] = -delta;
+      p.nlse[(size_t)h * p.T + tq] = -lse2 / p.c_log2;
+    }
+  }
+
+  f32x16 dq[1][D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) dq[0][db] = zero16();
+
+  const NatOff<D> no = nat_offsets<D>(lane);
+  const TrOff<D> to = tr_offsets<D>(lane);
+  const int e0 = tm.row_ptr[rt], e1 = tm.row_ptr[rt + 1];
+  const int n_lead = tm.row_lead[rt];  // leading full tiles
+  auto entry_at = [&](int e) { return e < e1 ? e : e1 - 1; };
+  TileEntry t_cur = load_entry(tm.row_entries, e0);
+  TileEntry t_n1 = load_entry(tm.row_entries, entry_at(e0 + 1));
+  TileEntry t_n2 = load_entry(tm.row_entries, entry_at(e0 + 2));
+
+  // the first two tiles are on their way before anything else
+  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, t_cur.tile, p.L, wave, lane);
+  if (e0 + 1 < e1) dma_key_tile<D, 4>(lds[1][0], lds[1][1], p.k, p.v, p.Hkv, kvh, tm, t_n1.tile, p.L, wave, lane);
+
+  // unnormalised probabilities for the whole workgroup, or normalised ones for the whole workgroup
+  const bool in_range = __builtin_fabsf(lse2) <= kLseRange;  // (false for NaN)
+  const bool unnormalised = __syncthreads_or(row_ok && !in_range) == 0;
+  const float lse_used[1] = {unnormalised ? 0.f : lse2};
+  const float delta_used[1] = {delta};
+  const float row_factor = (unnormalised ? exp2_fast(-lse2) : 1.f) * p.scale;
+  const int n_groups = unnormalised ? n_lead / 3 : 0;  // groups of three pipelined tiles
+
+  dma_publish();  // tiles e0 and e0+1 have landed (and the zero fill above is visible)
+  int e = e0;
+
+  if (n_groups > 0) {
+    f32x16 ndelta16;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ndelta16[i] = -delta;
+    const float c = p.c_log2;
+    DqPipe<D> P;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) P.dsb[a][t] = u32x4{0, 0, 0, 0};
+    {  // S and dP of the first unit; nothing to overlap them with
+      P.sc[0] = zero16();
+      P.dpc[0] = ndelta16;
+#pragma unroll
+      for (int st = 0; st < D / 16; ++st) {
+        P.sc[0] = mfma32(frag_nat<D>(lds[0][0], no, 0, st), qf[0][st], P.sc[0]);
+        P.dpc[0] = mfma32(frag_nat<D>(lds[0][1], no, 0, st), dof[0][st], P.dpc[0]);
+      }
+#pragma unroll
+      for (int j = 0; j < kDqAhead; ++j) P.ring[j] = dq_pipe_frag<D>(lds[2][0], 1, lds[0][0], lds[0][1], 1, no, to, j);
+    }
+    // One key tile in buffer B (a compile-time constant).
+    auto tile = [&](auto buf_tag, auto last_tag) {
+      constexpr int B = decltype(buf_tag)::value, BP = (B + 2) % 3, BN = (B + 1) % 3;
+      constexpr bool LAST = decltype(last_tag)::value;
+      const u32x2 ahead = fetch_entry(tm.row_entries, entry_at(e + 3));
+      dq_pipe_body<D, 0, false>(P, lds[BP][0], lds[B][0], lds[B][1], lds[B][0], no, to, qf, dof, dq, ndelta16, c);
+      // Every wave has left tile e-1 (its last reader was the body above) and has waited for its own copies of
+      // tile e+1: after the barrier that buffer may be overwritten and tile e+1 may be read.
+      dma_publish();
+      if (e + 2 < e1) dma_key_tile<D, 4>(lds[BP][0], lds[BP][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane);
+      dq_pipe_body<D, 1, LAST>(P, lds[B][0], lds[BN][0], lds[BN][1], lds[B][0], no, to, qf, dof, dq, ndelta16, c);
+      t_cur = t_n1;
+      t_n1 = t_n2;
+      t_n2 = take_entry(ahead);
+      ++e;
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    using B2 = std::integral_constant<int, 2>;
+    for (int gi = 0; gi < n_groups - 1; ++gi) {
+      tile(B0{}, std::false_type{});
+      tile(B1{}, std::false_type{});
+      tile(B2{}, std::false_type{});
+    }
+    tile(B0{}, std::false_type{});
+    tile(B1{}, std::false_type{});
+    tile(B2{}, std::true_type{});  // starts no further unit
+    // dQ of the last unit (block 1 of the tile in buffer 2)
+#pragma unroll
+    for (int j = 0; j < N2; ++j) {
+      const bf16x8 a = j < kDqAhead ? P.ring[j] : frag_tr<D>(lds[2][0], to, 32 + (j / (D / 32)) * 16, j % (D / 32));
+      dq[0][j % (D / 32)] = mfma32(a, __builtin_bit_cast(bf16x8, P.dsb[1][j / (D / 32)]), dq[0][j % (D / 32)]);
+    }
+    // tiles e and e+1 have been copied (e+1 perhaps not yet published), and a wave may still be reading tile e-1
+    dma_publish();
+  }
+
+  // The remaining tiles, one barrier each: tile e sits in buffer (e - e0) % 3, tile e+1 is published, the
+  // copy of tile e+2 goes to the buffer tile e-1 has left.
+  int buf = 0;  // (e - e0) % 3: the pipelined part ends on a multiple of three
+  for (; e < e1; ++e) {
+    const u32x2 ahead = fetch_entry(tm.row_entries, entry_at(e + 3));
+    const int buf2 = buf == 0 ? 2 : buf - 1;
+    if (e + 2 < e1) dma_key_tile<D, 4>(lds[buf2][0], lds[buf2][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane);
+    const char* kt_lds = lds[0][0] + buf * (2 * kTileBytes);
+    const char* vt_lds = kt_lds + kTileBytes;
+    if (t_cur.mask_id < 0) {
+      const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
+      dq_tile<D, 1, false>(kt_lds, vt_lds, no, to, qf, dof, dq, lse_used, delta_used, mw, p.c_log2);
+    } else {
+      const u32x2 w = *reinterpret_cast<const u32x2*>(tm.masks + ((size_t)t_cur.mask_id * kRowsPerTile + r) * 2);
+      const uint32_t mw[2] = {w[0] >> (4 * g), w[1] >> (4 * g)};
+      // a 32-key block that none of the wave's 32 rows can see contributes exact zeros and is left out
+      const bool see0 = wave_sees_block(mw[0]), see1 = wave_sees_block(mw[1]);
+      if (see0 && see1) dq_tile<D, 1, true>(kt_lds, vt_lds, no, to, qf, dof, dq, lse_used, delta_used, mw, p.c_log2);
+      else if (see0) dq_tile<D, 1, true, 0, 1>(kt_lds, vt_lds, no, to, qf, dof, dq, lse_used, delta_used, mw, p.c_log2);
+      else if (see1) dq_tile<D, 1, true, 1, 2>(kt_lds, vt_lds, no, to, qf, dof, dq, lse_used, delta_used, mw, p.c_log2);
+    }
+    dma_publish();
+    t_cur = t_n1;
+    t_n1 = t_n2;
+    t_n2 = take_entry(ahead);
+    buf = buf == 2 ? 0 : buf + 1;
+  }
+
+  if (row_ok) {
+    if (p.rope_table) {
+      // q was the rotated copy: turn dQ back.  The lane holds features db*32 + 8*q4 + 4g + j of its
+      // row, so both members of every pair (feature, feature + D/2) are in its own registers.
+      const float* rope = p.rope_table + (size_t)token_position(tm, tq, p.L) * D;
+#pragma unroll
+      for (int db = 0; db < D / 64; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = db * 32 + 8 * q4 + 4 * g;
+          const f32x4 cs = *reinterpret_cast<const f32x4*>(rope + d0);
+          const f32x4 sn = *reinterpret_cast<const f32x4*>(rope + D / 2 + d0);
+          f32x4 lo, hi;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            lo[j] = dq[0][db][4 * q4 + j];
+            hi[j] = dq[0][db + D / 64][4 * q4 + j];
+          }
+          rope_turn4<true>(lo, hi, cs, sn);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            dq[0][db][4 * q4 + j] = lo[j];
+            dq[0][db + D / 64][4 * q4 + j] = hi[j];
+          }
+        }
+    }
+    __bf16* drow = p.dq + ((size_t)tq * p.Hq + h) * D;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        u32x2 w;
+        w[0] = pack_bf16(dq[0][db][4 * q4 + 0] * row_factor, dq[0][db][4 * q4 + 1] * row_factor);
+        w[1] = pack_bf16(dq[0][db][4 * q4 + 2] * row_factor, dq[0][db][4 * q4 + 3] * row_factor);
+        *reinterpret_cast<u32x2*>(drow + db * 32 + 8 * q4 + 4 * g) = w;
+      }
+  }
+}
+
+// =====================================================================================
 // Backward, part 2: dK, dV, key-tile owned.  A workgroup holds a PAIR of adjacent key tiles
 // (128 keys) of one KV head in registers and loops over the row tiles that see the first of
 // them (clipped to the segment) for the query heads [h_lo, h_hi) assigned to it; the second
@@ -1370,19 +1671,35 @@ __global__ __launch_bounds__(256) void draft_decode_combine_kernel(DecodeParams 
 
 // Pure MFMA issue loop (no memory traffic): four independent accumulator chains per wave,
 // 8 workgroups x 4 waves per CU.  Used only to report the measured matrix-core ceiling.
+// RANDOM = false: small integer operands that never change (little switching activity in the multipliers);
+// RANDOM = true: four sets of operands drawn from a hash, roughly uniform in (-2, 2) with every significand
+// bit in use, taken in turn - the activity the matrix cores see on real Q, K, V.  The chip lowers its clock
+// under the second kind of load, so the two rates differ.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters) {
-  bf16x8 a, b;
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    a[j] = (__bf16)(float)(threadIdx.x % 3);
-    b[j] = (__bf16)(float)(threadIdx.x % 5);
-  }
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (RANDOM) {
+        uint32_t x = (blockIdx.x * 256u + threadIdx.x) * 64u + s * 16u + j;
+        x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+        a[s][j] = (__bf16)(((float)(x & 0xffffu) - 32767.5f) * (2.0f / 32768.0f));
+        b[s][j] = (__bf16)(((float)(x >> 16) - 32767.5f) * (2.0f / 32768.0f));
+      } else {
+        a[s][j] = (__bf16)(float)(threadIdx.x % 3);
+        b[s][j] = (__bf16)(float)(threadIdx.x % 5);
+      }
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] = zero16();
-  for (int it = 0; it < iters; ++it) {
+  for (int it = 0; it < iters; it += 4) {  // (iters is a multiple of four)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] = mfma32(a, b, acc[i]);
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = mfma32(a[RANDOM ? i : 0], b[RANDOM ? (i + u) & 3 : 0], acc[i]);
   }
   float s = 0.f;
 #pragma unroll
@@ -1478,7 +1795,7 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
   {
     const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
     TimedSpan span(timer, kKindDq, stream);
-    if (D == 64) hipLaunchKernelGGL((dq_kernel<64, 1>), grid, block, 0, stream, p);
+    if (D == 64) hipLaunchKernelGGL((dq_pipe_kernel<64>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((dq_kernel<128, 1>), grid, block, 0, stream, p);
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
@@ -1575,7 +1892,7 @@ hipError_t launch_cast_bf16(const float* src, void* dst, size_t n, hipStream_t s
   return hipGetLastError();
 }
 
-hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops) {
+hipError_t measure_mfma_ceiling(hipStream_t stream, bool random_operands, float* tflops) {
   int dev = 0, cus = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -1588,14 +1905,19 @@ hipError_t measure_mfma_ceiling(hipStream_t stream, float* tflops) {
   e = hipEventCreate(&e0);
   if (e == hipSuccess) e = hipEventCreate(&e1);
   if (e == hipSuccess) {
-    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, stream, out, iters);  // warm-up
+    auto launch = [&] {
+      if (random_operands) hipLaunchKernelGGL(mfma_ceiling_kernel<true>, dim3(blocks), dim3(256), 0, stream, out, iters);
+      else hipLaunchKernelGGL(mfma_ceiling_kernel<false>, dim3(blocks), dim3(256), 0, stream, out, iters);
+    };
+    // warm-up: the clock settles over a few milliseconds of load
+    for (int w = 0; w < 3; ++w) launch();
     (void)hipEventRecord(e0, stream);
-    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, stream, out, iters);
+    for (int w = 0; w < 3; ++w) launch();
     (void)hipEventRecord(e1, stream);
     e = hipEventSynchronize(e1);
     float ms = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    if (e == hipSuccess) *tflops = (float)((double)blocks * 4 * iters * 4 * 32768.0 / ((double)ms * 1e9));
+    if (e == hipSuccess) *tflops = (float)(3.0 * (double)blocks * 4 * iters * 4 * 32768.0 / ((double)ms * 1e9));
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);

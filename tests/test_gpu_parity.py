@@ -165,11 +165,14 @@ def test_dense_segments_longer_than_one_dkdv_launch(bounds):
         assert rel_l2(got[n], whole[n]) <= PART_REL, n
 
 
-@pytest.mark.parametrize("qscale", [12.0, 40.0])
+@pytest.mark.parametrize("qscale", [10.0, 12.0, 40.0])
 def test_large_logits_take_the_running_max_path(qscale):
     """Scores far outside the exponent range that the forward's first pass (reference max fixed at
-    0) can hold: the kernel must detect it and redo the row tile with the running-max form."""
-    L, K, Hq, Hkv, D = 200, 4, 4, 2, 64
+    0) can hold: the kernel must detect it and redo the row tile with the running-max form.  The dQ
+    kernel leaves its probabilities unnormalised only while |lse| <= 64 in log2 units: at the smaller
+    scales some workgroups are inside that range and some outside, at the largest none is inside, and
+    the sequence is long enough for the pipelined groups of three full tiles to occur."""
+    L, K, Hq, Hkv, D = 600, 4, 4, 2, 64
     print(f"case large_logits qscale={qscale}", flush=True)
     T = L * K
     qb, kb, vb, dob = (rand_bits((T, Hq, D), 300, qscale), rand_bits((T, Hkv, D), 301), rand_bits((T, Hkv, D), 302),
