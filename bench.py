@@ -590,7 +590,26 @@ def main() -> int:
     kernels = {name: {"ms_per_step": a[0] / prof_reps, "launches_per_step": a[1] // prof_reps,
                       "avg_launch_ms": a[0] / max(a[1], 1)} for name, a in acc.items() if a[1] > 0}
     mfma_ceiling = pe.peagle_measure_mfma_ceiling(stream)
+    # the same issue loop on changing pseudo-random operands: the chip holds a lower clock under that load
+    mfma_ceiling_random = pe.peagle_measure_mfma_ceiling(stream, random_operands=True)
     torch.cuda.synchronize()
+    # The same step on all-zero operands: identical instruction stream and launches, almost no switching
+    # activity in the matrix cores, so the chip keeps its full clock - the difference to ms_per_step is what the
+    # power limit costs on real data (context only: zeros are not a workload).
+    ms_zero = None
+    if not args.partitioned_only:
+        qz, kz, vz, doz = (torch.zeros_like(x) for x in (q, k, v, do))
+        zstep = lambda: pe.peagle_attn_step_partitioned(tm, shape, 0, S, qz, kz, vz, doz, o, lse, dq, dk, dv, None,
+                                                        None, ws, stream)
+        for _ in range(3):
+            zstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(args.steps // 2, 1)):
+            zstep()
+        torch.cuda.synchronize()
+        ms_zero = (time.perf_counter() - t0) * 1e3 / max(args.steps // 2, 1)
+        del qz, kz, vz, doz
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written
         dst = torch.empty_like(src)
@@ -632,6 +651,9 @@ def main() -> int:
         "pct_of_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "pct_of_measured_mfma_ceiling": 100.0 * value / mfma_ceiling if mfma_ceiling > 0 else None,
         "measured_mfma_ceiling_tflops": mfma_ceiling,
+        "measured_mfma_ceiling_random_operands_tflops": mfma_ceiling_random,
+        "pct_of_measured_mfma_ceiling_random_operands": 100.0 * value / mfma_ceiling_random if mfma_ceiling_random > 0 else None,
+        "ms_per_step_on_zero_operands": ms_zero,
         "useful_flops_per_step": flops,
         "useful_over_computed_pairs": pairs / computed_pairs,
         "tilemap_build_ms": tilemap_ms,

@@ -107,31 +107,62 @@ __global__ __launch_bounds__(256) void expand_shared_kernel(const __bf16* x0, co
 
 // Gradients of the shared vectors: column sums of the chain tokens' rows [L0, T) of acc [T, cols] (fp32),
 // in two deterministic stages.  Stage 1: block b sums the tokens L0 + b, L0 + b + nblk, ... into
-// partial[b][cols]; stage 2 (one block) sums the partials.  The same two launches also copy the depth-0
-// rows [0, L0) to their own output (stage 1, by all blocks).  gridDim.y selects dK or dV.
+// partial[b][cols]; stage 2 sums the partials, a thread per 16-byte column piece.  Stage 1 also copies the
+// depth-0 rows [0, L0) to their own output (all blocks).  gridDim.y selects dK or dV.
 __global__ __launch_bounds__(256) void shared_grad_stage1(const float* acc_k, const float* acc_v, float* partial,
                                                           float* out0_k, float* out0_v, int T, int L0, int cols) {
+  __shared__ f32x4 red[256];
   const float* acc = blockIdx.y ? acc_v : acc_k;
   float* out0 = blockIdx.y ? out0_v : out0_k;
-  const int nblk = gridDim.x, b = blockIdx.x;
-  for (int c4 = threadIdx.x; c4 < cols / 4; c4 += blockDim.x) {
+  const int nblk = gridDim.x, b = blockIdx.x, n4 = cols / 4;
+  // Threads are laid out as (token lane, 16-byte column piece): consecutive threads read consecutive pieces of
+  // one row, `lanes` rows at a time, four rows in flight per thread; the token lanes of a piece are then summed
+  // through LDS in a fixed order.
+  const int lanes = n4 <= 256 ? 256 / n4 : 1;
+  const int tl = n4 <= 256 ? threadIdx.x / n4 : 0;
+  for (int c0 = 0; c0 < n4; c0 += 256) {
+    const int c4 = c0 + (n4 <= 256 ? threadIdx.x % n4 : threadIdx.x);
+    const bool on = c4 < n4 && tl < lanes;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (int t = L0 + b; t < T; t += nblk) sum += *reinterpret_cast<const f32x4*>(acc + (size_t)t * cols + c4 * 4);
-    *reinterpret_cast<f32x4*>(partial + ((size_t)blockIdx.y * nblk + b) * cols + c4 * 4) = sum;
-    for (int t = b; t < L0; t += nblk)
-      *reinterpret_cast<f32x4*>(out0 + (size_t)t * cols + c4 * 4) =
-          *reinterpret_cast<const f32x4*>(acc + (size_t)t * cols + c4 * 4);
+    if (on) {
+      const size_t stride = (size_t)nblk * lanes;
+      size_t t = (size_t)L0 + b + (size_t)tl * nblk;
+      for (; t + 3 * stride < (size_t)T; t += 4 * stride) {
+        const f32x4 x0 = *reinterpret_cast<const f32x4*>(acc + t * cols + c4 * 4);
+        const f32x4 x1 = *reinterpret_cast<const f32x4*>(acc + (t + stride) * cols + c4 * 4);
+        const f32x4 x2 = *reinterpret_cast<const f32x4*>(acc + (t + 2 * stride) * cols + c4 * 4);
+        const f32x4 x3 = *reinterpret_cast<const f32x4*>(acc + (t + 3 * stride) * cols + c4 * 4);
+        sum += (x0 + x1) + (x2 + x3);
+      }
+      for (; t < (size_t)T; t += stride) sum += *reinterpret_cast<const f32x4*>(acc + t * cols + c4 * 4);
+      for (size_t t0 = (size_t)b + (size_t)tl * nblk; t0 < (size_t)L0; t0 += stride)
+        *reinterpret_cast<f32x4*>(out0 + t0 * cols + c4 * 4) = *reinterpret_cast<const f32x4*>(acc + t0 * cols + c4 * 4);
+    }
+    red[threadIdx.x] = sum;
+    __syncthreads();
+    if (on && tl == 0) {
+      for (int l = 1; l < lanes; ++l) sum += red[threadIdx.x + l * n4];
+      *reinterpret_cast<f32x4*>(partial + ((size_t)blockIdx.y * nblk + b) * cols + c4 * 4) = sum;
+    }
+    __syncthreads();
   }
 }
 __global__ __launch_bounds__(256) void shared_grad_stage2(const float* partial, float* out_k, float* out_v, int nblk,
                                                           int cols) {
   float* out = blockIdx.y ? out_v : out_k;
-  for (int c4 = threadIdx.x; c4 < cols / 4; c4 += blockDim.x) {
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (int b = 0; b < nblk; ++b)
-      sum += *reinterpret_cast<const f32x4*>(partial + ((size_t)blockIdx.y * nblk + b) * cols + c4 * 4);
-    *reinterpret_cast<f32x4*>(out + c4 * 4) = sum;
+  const int c4 = blockIdx.x * blockDim.x + threadIdx.x;  // one thread per 16-byte column piece
+  if (c4 >= cols / 4) return;
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+  const float* src = partial + (size_t)blockIdx.y * nblk * cols + c4 * 4;
+  int b = 0;
+  for (; b + 3 < nblk; b += 4) {
+    s0 += *reinterpret_cast<const f32x4*>(src + (size_t)b * cols);
+    s1 += *reinterpret_cast<const f32x4*>(src + (size_t)(b + 1) * cols);
+    s2 += *reinterpret_cast<const f32x4*>(src + (size_t)(b + 2) * cols);
+    s3 += *reinterpret_cast<const f32x4*>(src + (size_t)(b + 3) * cols);
   }
+  for (; b < nblk; ++b) s0 += *reinterpret_cast<const f32x4*>(src + (size_t)b * cols);
+  *reinterpret_cast<f32x4*>(out + c4 * 4) = (s0 + s1) + (s2 + s3);
 }
 
 inline unsigned grid_for(size_t n) {
@@ -192,8 +223,8 @@ hipError_t launch_shared_grads(const float* acc_k, const float* acc_v, float* pa
                      dk0, dv0, T, L0, cols);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(shared_grad_stage2, dim3(1, 2), dim3(256), 0, stream, partial, dk_shared, dv_shared,
-                     n_partial_blocks, cols);
+  hipLaunchKernelGGL(shared_grad_stage2, dim3((unsigned)((cols / 4 + 63) / 64), 2), dim3(64), 0, stream, partial,
+                     dk_shared, dv_shared, n_partial_blocks, cols);
   return hipGetLastError();
 }
 
