@@ -313,9 +313,14 @@ int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_s
  *   dk_shared, dv_shared   device, fp32 [Hkv, D] (out): sums over all positions of depth >= 1 (for the
  *                   keys, of the gradients turned back to the unrotated frame); deterministic
  *   workspace       device, >= peagle_rope_shared_workspace_bytes(): besides the rotary workspace it holds
- *                   the expanded V and fp32 dK / dV over all T tokens
+ *                   one row of Hkv x D partial sums of dK and of dV per wave of the workgroups that own the
+ *                   chain keys (a few MB)
  * The keys are expanded and rotated in one pass (each chain row reads the shared vector, not HBM rows
- * of its own), the values expanded by a copy; the attention kernels are those of the rotary step.
+ * of its own).  The values are not expanded: the kernels read every chain key's value row from
+ * v_shared.  No [T, Hkv, D] gradient tensor exists either: the depth-0 keys' dK / dV are written to
+ * dk0 / dv0 directly, and the chain keys' dK (turned back to the unrotated frame key by key) and dV are
+ * summed over each wave's 32 keys inside the dK/dV kernel, then over the waves by a two-stage
+ * reduction in a fixed order.
  */
 size_t peagle_rope_shared_workspace_bytes(const peagle_tilemap_t* tm, const peagle_shape_t* shape);
 int peagle_attn_step_rope_shared(const peagle_tilemap_t* tm, const peagle_shape_t* shape, const void* q,

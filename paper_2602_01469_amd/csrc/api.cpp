@@ -54,9 +54,17 @@ int check_shape(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
   return PEAGLE_OK;
 }
 
+// First-layer form of the step (null members: the ordinary step)
+struct SharedForm {
+  const void* v_shared = nullptr;  // [Hkv, D]: the value row of every chain key
+  float* dk_part = nullptr;        // per-wave sums of the chain keys' dK / dV, see BwdParams
+  float* dv_part = nullptr;
+};
+
 FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
-                   const void* k, const void* v, void* o, float* lse) {
+                   const void* k, const void* v, void* o, float* lse, const SharedForm& sf = SharedForm()) {
   FwdParams p{};
+  p.v_shared = (const __bf16*)sf.v_shared;
   p.q = (const __bf16*)q;
   p.k = (const __bf16*)k;
   p.v = (const __bf16*)v;
@@ -76,9 +84,12 @@ FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const Se
 BwdParams make_bwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
                    const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
                    float* dk_acc, float* dv_acc, void* workspace, int chain_accumulate,
-                   const float* rope_table = nullptr) {
+                   const float* rope_table = nullptr, const SharedForm& sf = SharedForm()) {
   const WsLayout w = ws_layout(tm, s);
   BwdParams p{};
+  p.v_shared = (const __bf16*)sf.v_shared;
+  p.shared_dk_part = sf.dk_part;
+  p.shared_dv_part = sf.dv_part;
   p.q = (const __bf16*)q;
   p.k = (const __bf16*)k;
   p.v = (const __bf16*)v;
@@ -171,7 +182,7 @@ static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, in
                      const void* q, const void* k, const void* v, const void* d_o, void* o, float* lse, void* dq,
                      float* dk_acc, float* dv_acc, void* dk_bf16, void* dv_bf16, void* workspace, size_t ws_bytes,
                      void* stream, peagle::KernelTimer* timer, const float* rope_table = nullptr,
-                     int32_t rope_n_pos = 0, bool inputs_rotated = false) {
+                     int32_t rope_n_pos = 0, bool inputs_rotated = false, const SharedForm& sf = SharedForm()) {
   int rc = check_shape(tm, shape);
   if (rc != PEAGLE_OK) return rc;
   if (!q || !k || !v || !d_o || !o || !lse || !dq || !dk_acc || !dv_acc) return PEAGLE_ENULL;
@@ -201,11 +212,11 @@ static int step_impl(const peagle_tilemap_t* tm, const peagle_shape_t* shape, in
     rc = peagle::resolve_segment(tm, shape->L, s, &sr);
     if (rc != PEAGLE_OK) return rc;
     if (sr.a_lo >= sr.a_hi) continue;  // segment lies beyond the cropped length
-    const FwdParams fp = make_fwd(tm, shape, sr, q, k, v, o, lse);
+    const FwdParams fp = make_fwd(tm, shape, sr, q, k, v, o, lse, sf);
     if (peagle::launch_fwd(fp, shape->D, st, timer) != hipSuccess) return PEAGLE_EHIP;
     // Depth-0 keys below the segment start already hold earlier segments' sums: add to them.
     // Keys first seen by this segment (its own depth-0 range and its chains) are overwritten.
-    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0, rope_table);
+    const BwdParams bp = make_bwd(tm, shape, sr, q, k, v, o, d_o, lse, dq, dk_acc, dv_acc, workspace, 0, rope_table, sf);
     if (peagle::launch_bwd(bp, shape->D, sr.key_lo, sr.a_hi, sr.a_lo, st, timer) != hipSuccess) return PEAGLE_EHIP;
   }
   if (seg_end == tm->S || tm->seg_bounds[seg_end] >= shape->L) {
@@ -299,19 +310,19 @@ extern "C" int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, con
 
 namespace {
 
-// Workspace of the first-layer form: the rotary workspace, the expanded V, fp32 dK / dV over all tokens,
-// and the partial sums of the shared-vector gradients.
+// Workspace of the first-layer form: the rotary workspace (rotated Q, expanded and rotated K) and the per-wave
+// sums of the chain keys' dK / dV (one row of Hkv x D per wave of every chain-tile workgroup).
 struct SharedWs {
-  size_t v_off, dk_off, dv_off, part_off, total;
+  size_t pk_off, pv_off, total;
+  int32_t part_rows;
 };
 SharedWs shared_ws(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
   SharedWs w;
-  const size_t T = tokens_of(tm, s), cols = (size_t)s->Hkv * s->D;
-  w.v_off = rope_ws(tm, s).total;
-  w.dk_off = w.v_off + align256(T * cols * 2);
-  w.dv_off = w.dk_off + align256(T * cols * sizeof(float));
-  w.part_off = w.dv_off + align256(T * cols * sizeof(float));
-  w.total = w.part_off + align256((size_t)2 * peagle::kSharedGradBlocks * cols * sizeof(float));
+  const size_t cols = (size_t)s->Hkv * s->D;
+  w.part_rows = tm->n_row_tiles * ((tm->n_csub + 1) / 2) * 4;
+  w.pk_off = rope_ws(tm, s).total;
+  w.pv_off = w.pk_off + align256((size_t)w.part_rows * cols * sizeof(float));
+  w.total = w.pv_off + align256((size_t)w.part_rows * cols * sizeof(float));
   return w;
 }
 
@@ -343,23 +354,30 @@ extern "C" int peagle_attn_step_rope_shared(const peagle_tilemap_t* tm, const pe
   char* ws = (char*)workspace;
   void* q_rot = ws + rw.q_off;
   void* k_rot = ws + rw.k_off;
-  void* v_full = ws + sw.v_off;
-  float* dk_acc = (float*)(ws + sw.dk_off);
-  float* dv_acc = (float*)(ws + sw.dv_off);
   if (peagle::launch_rope_rotate(q, q_rot, shape->Hq, T, shape->D, tm->dview, shape->L, rope_table, false, st) !=
       hipSuccess)
     return PEAGLE_EHIP;
+  // K: the depth-0 rows and, for every chain token, the shared vector turned to that token's position
   if (peagle::launch_expand_shared(k0, k_shared, k_rot, shape->Hkv, T, L0, shape->D, tm->dview, shape->L, rope_table,
                                    st) != hipSuccess)
     return PEAGLE_EHIP;
-  if (peagle::launch_expand_shared(v0, v_shared, v_full, shape->Hkv, T, L0, shape->D, tm->dview, shape->L, nullptr,
-                                   st) != hipSuccess)
-    return PEAGLE_EHIP;
-  rc = step_impl(tm, shape, 0, tm->S, q_rot, k_rot, v_full, d_o, o, lse, dq, dk_acc, dv_acc, nullptr, nullptr, workspace,
-                 ws_bytes, stream, nullptr, rope_table, n_pos, /*inputs_rotated=*/true);
+  // V is not expanded: the kernels take every chain key's value row from v_shared, and v0 holds exactly the rows
+  // of the depth-0 tokens (the first L0 of the stored order).  Likewise dK / dV: the depth-0 keys' gradients go
+  // straight to the caller's dk0 / dv0 (the first L0 rows are all the kernels write there in this form), the
+  // chain keys' come out as per-wave sums.
+  SharedForm sf;
+  sf.v_shared = v_shared;
+  sf.dk_part = (float*)(ws + sw.pk_off);
+  sf.dv_part = (float*)(ws + sw.pv_off);
+  rc = step_impl(tm, shape, 0, tm->S, q_rot, k_rot, v0, d_o, o, lse, dq, dk0, dv0, nullptr, nullptr, workspace,
+                 ws_bytes, stream, nullptr, rope_table, n_pos, /*inputs_rotated=*/true, sf);
   if (rc != PEAGLE_OK) return rc;
-  return peagle::launch_shared_grads(dk_acc, dv_acc, (float*)(ws + sw.part_off), peagle::kSharedGradBlocks, dk0, dv0,
-                                     dk_shared, dv_shared, T, L0, shape->Hkv * shape->D, st) == hipSuccess
+  SegRange whole;
+  rc = peagle::resolve_segment(tm, shape->L, -1, &whole);
+  if (rc != PEAGLE_OK) return rc;
+  const int rows = whole.rt_hi * ((tm->n_csub + 1) / 2) * 4;  // rows written by a length-L step
+  return peagle::launch_shared_grads(sf.dk_part, sf.dv_part, rows, dk_shared, dv_shared, shape->Hkv * shape->D,
+                                     st) == hipSuccess
              ? PEAGLE_OK
              : PEAGLE_EHIP;
 }

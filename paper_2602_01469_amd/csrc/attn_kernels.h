@@ -19,6 +19,8 @@ struct FwdParams {
   int L, T, Hq, Hkv;
   int rt_lo, rt_hi;    // row tiles of the segment
   float c_log2;        // softmax scale * log2(e)
+  const __bf16* v_shared;  // null, or [Hkv, D]: the value row of every chain key (first-layer form; v then holds
+                           // the depth-0 rows only)
 };
 
 struct BwdParams {
@@ -49,6 +51,13 @@ struct BwdParams {
   float c_log2, scale;
   const float* rope_table;  // null, or [positions][2][D/2] cosines and sines: q and k are rotated copies, and dQ / dK
                             // are turned back to the unrotated inputs' frame before they are stored
+  // First-layer form (every chain key carries the same K and V vector, rotated by its position): v_shared [Hkv, D]
+  // is the value row of every chain key (v then holds the depth-0 rows only), and the chain keys' dK / dV are not
+  // stored per key but summed over the 32 keys of a wave into shared_dk_part / shared_dv_part
+  // [(row tile * chain-tile pairs + pair) * 4 + wave][Hkv][D], which a reduction then adds up.  All null otherwise.
+  const __bf16* v_shared;
+  float* shared_dk_part;
+  float* shared_dv_part;
 };
 
 // Inference-side drafting step (Sec. 2 of the paper: all K draft positions in one forward pass): the K
@@ -96,13 +105,13 @@ hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStrea
 // by each token's position (inverse: the transpose).
 hipError_t launch_rope_table(double base, int D, int n_pos, float* table, hipStream_t stream);
 // First-layer form: expansion of (own depth-0 rows, one shared vector for every later token) into a full
-// [T, H, D] tensor, rotated when a table is given; and the reduction of the chain rows' gradients.
+// [T, H, D] tensor, rotated when a table is given.
 hipError_t launch_expand_shared(const void* x0, const void* x_shared, void* out, int H, int T, int L0, int D,
                                 const DeviceTileMap& tm, int L, const float* table_or_null, hipStream_t stream);
-constexpr int kSharedGradBlocks = 256;
-hipError_t launch_shared_grads(const float* acc_k, const float* acc_v, float* partial, int n_partial_blocks, float* dk0,
-                               float* dv0, float* dk_shared, float* dv_shared, int T, int L0, int cols,
-                               hipStream_t stream);
+// Column sums of part_k / part_v [rows][cols] (the per-wave sums of the chain keys' gradients) into
+// dk_shared / dv_shared [cols], in a fixed order.
+hipError_t launch_shared_grads(const float* part_k, const float* part_v, int rows, float* dk_shared, float* dv_shared,
+                               int cols, hipStream_t stream);
 hipError_t launch_rope_rotate(const void* x, void* out, int H, int T, int D, const DeviceTileMap& tm, int L,
                               const float* table, bool inverse, hipStream_t stream, KernelTimer* timer = nullptr);
 

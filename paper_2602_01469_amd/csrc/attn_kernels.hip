@@ -83,10 +83,10 @@ __device__ __forceinline__ TileEntry load_entry(const TileEntry* list, int e) { 
 // Key tile straight into its swizzled LDS image (K and V): wave w of NW fills the 1 KiB blocks
 // w, w + NW, ...; lane l of block b owns LDS bytes [1024 b + 16 l, +16), i.e. tile row
 // b*(512/D) + l/(D/8) and physical chunk l%(D/8), and fetches the logical chunk that lives there.
-template <int D, int NW>
+template <int D, int NW, bool SV = false>
 __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __bf16* kbase, const __bf16* vbase,
                                              int Hkv, int kvh, const DeviceTileMap& tm, int kt, int L, int wave,
-                                             int lane) {
+                                             int lane, const __bf16* v_shared = nullptr) {
   constexpr int kBlocks = kKeysPerTile * D * 2 / 1024;
   static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
   const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
@@ -102,6 +102,20 @@ __device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __b
       const size_t first = ((size_t)(kt * kKeysPerTile + i * NW * (512 / D)) * Hkv + kvh) * D;
       dma16_untracked(uniform_ptr(kbase + first), voff, kd + i * NW * 1024);
       dma16_untracked(uniform_ptr(vbase + first), voff, vd + i * NW * 1024);
+    }
+  } else if (SV && kt >= tm.n_d0) {
+    // First-layer form, chain tile: every key's value row is the one shared vector of its KV head.  (SV is a
+    // template flag: kernels of the ordinary step carry none of this.)
+#pragma unroll
+    for (int i = 0; i < kBlocks / NW; ++i) {
+      const int blk = i * NW + wave;
+      const int row = blk * (512 / D) + row_in_blk;
+      int tok;
+      const bool ok = key_token(tm, kt, row, L, tok);
+      const int chunk = (phys ^ swz<D>(row)) << 3;
+      const size_t off = ((size_t)(ok ? tok : 0) * Hkv + kvh) * D + chunk;
+      dma16_untracked(ok ? (const void*)(kbase + off) : tm.zeros, kd + i * NW * 1024);
+      dma16_untracked(ok ? (const void*)(v_shared + (size_t)kvh * D + chunk) : tm.zeros, vd + i * NW * 1024);
     }
   } else {
 #pragma unroll
@@ -329,7 +343,7 @@ __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds,
   }
 }
 
-template <int D, int NH>
+template <int D, int NH, bool SV>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
@@ -379,7 +393,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
     }
     TileEntry cur = load_entry(tm.row_entries, e0);
     TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
-    dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
+    dma_key_tile<D, 4, SV>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
     dma_publish();
     // The leading full tiles run in a counted loop of their own (no mask branch, accumulators
     // stay in place); the partial tiles that end a row tile's list take the general loop.
@@ -388,7 +402,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
       const int buf = (e - e0) & 1;
       const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
-        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
+        dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
       dma_publish();
@@ -399,7 +413,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
       const int buf = (e - e0) & 1;
       const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
-        dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
+        dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
       if (cur.mask_id < 0) {
         const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
         fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
@@ -496,7 +510,7 @@ __device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, 
   }
 }
 
-template <int D, int NH>
+template <int D, int NH, bool SV>
 __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
@@ -552,7 +566,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   const int e_lead = e0 + tm.row_lead[rt];  // end of the leading run of full tiles
   TileEntry cur = load_entry(tm.row_entries, e0);
   TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
-  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
+  dma_key_tile<D, 4, SV>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
   dma_publish();
 
   int e = e0;
@@ -560,7 +574,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     const int buf = (e - e0) & 1;
     const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
+      dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
     const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
     dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     dma_publish();
@@ -571,7 +585,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     const int buf = (e - e0) & 1;
     const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
+      dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
     if (cur.mask_id < 0) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
@@ -736,7 +750,7 @@ __device__ __forceinline__ void dq_pipe_body(DqPipe<D>& P, const char* k_dq, con
   }
 }
 
-template <int D>
+template <int D, bool SV>
 __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   constexpr int N2 = D / 16;
@@ -800,8 +814,8 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
   TileEntry t_n2 = load_entry(tm.row_entries, entry_at(e0 + 2));
 
   // the first two tiles are on their way before anything else
-  dma_key_tile<D, 4>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, t_cur.tile, p.L, wave, lane);
-  if (e0 + 1 < e1) dma_key_tile<D, 4>(lds[1][0], lds[1][1], p.k, p.v, p.Hkv, kvh, tm, t_n1.tile, p.L, wave, lane);
+  dma_key_tile<D, 4, SV>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, t_cur.tile, p.L, wave, lane, p.v_shared);
+  if (e0 + 1 < e1) dma_key_tile<D, 4, SV>(lds[1][0], lds[1][1], p.k, p.v, p.Hkv, kvh, tm, t_n1.tile, p.L, wave, lane, p.v_shared);
 
   // unnormalised probabilities for the whole workgroup, or normalised ones for the whole workgroup
   const bool in_range = __builtin_fabsf(lse2) <= kLseRange;  // (false for NaN)
@@ -844,7 +858,7 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
       // Every wave has left tile e-1 (its last reader was the body above) and has waited for its own copies of
       // tile e+1: after the barrier that buffer may be overwritten and tile e+1 may be read.
       dma_publish();
-      if (e + 2 < e1) dma_key_tile<D, 4>(lds[BP][0], lds[BP][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane);
+      if (e + 2 < e1) dma_key_tile<D, 4, SV>(lds[BP][0], lds[BP][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane, p.v_shared);
       dq_pipe_body<D, 1, LAST>(P, lds[B][0], lds[BN][0], lds[BN][1], lds[B][0], no, to, qf, dof, dq, ndelta16, c);
       t_cur = t_n1;
       t_n1 = t_n2;
@@ -878,7 +892,7 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
   for (; e < e1; ++e) {
     const u32x2 ahead = fetch_entry(tm.row_entries, entry_at(e + 3));
     const int buf2 = buf == 0 ? 2 : buf - 1;
-    if (e + 2 < e1) dma_key_tile<D, 4>(lds[buf2][0], lds[buf2][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane);
+    if (e + 2 < e1) dma_key_tile<D, 4, SV>(lds[buf2][0], lds[buf2][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane, p.v_shared);
     const char* kt_lds = lds[0][0] + buf * (2 * kTileBytes);
     const char* vt_lds = kt_lds + kTileBytes;
     if (t_cur.mask_id < 0) {
@@ -1080,7 +1094,7 @@ __device__ __forceinline__ void dkdv_rowtile_pipelined(const char* q_lds, const 
 // LISTED: the map names rows by explicit token lists (sampled / packed maps); their tokens are then
 // fetched an iteration before the copy that uses them.  A dense map computes them when it issues
 // the copy and carries no token registers.
-template <int D, bool LISTED>
+template <int D, bool LISTED, bool SV>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p) {
   constexpr int kTileBytes = kRowsPerTile * D * 2;
   constexpr int kBufBytes = 2 * kTileBytes + 2 * kRowsPerTile * 4;  // Q | dO | lse2 | delta
@@ -1169,7 +1183,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
 #pragma unroll
     for (int st = 0; st < D / 16; ++st) {
       const uint4 z = make_uint4(0, 0, 0, 0);
-      const uint4 a = ld16(p.k + off + st * 16), c = ld16(p.v + off + st * 16);
+      const __bf16* vrow = SV && chain ? p.v_shared + (size_t)kvh * D + g * 8 : p.v + off;
+      const uint4 a = ld16(p.k + off + st * 16), c = ld16(vrow + st * 16);
       kf[st] = as_frag(key_ok ? a : z);
       vf[st] = as_frag(key_ok ? c : z);
     }
@@ -1309,6 +1324,65 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
     step(ei_n, hh_n);
     step(ei_a, hh_a);
     step(ei_b, hh_b);
+  }
+
+  if (SV && chain) {
+    // First-layer form: the chain keys' gradients are only ever needed summed over the keys (they all come from
+    // one shared vector), so each wave adds up its 32 keys here - dK after it has been turned back to the
+    // unrotated frame, key by key - and stores one row of D sums per tensor.  The sum over keys runs across
+    // lanes: the wave lays its values out in LDS as [d][key] (33 floats per d: conflict-free both ways) and lane
+    // l adds up row d = l (and l + 64).  The row tiles' buffers are free: every wave is past the loop's last
+    // barrier.  Keys that do not exist contribute zero.
+    float* red = reinterpret_cast<float*>(lds) + (size_t)wave * (D * 33);
+    static_assert(4 * D * 33 * 4 <= kLdsBytes, "the four waves' transposition buffers must fit");
+    const bool have = tile_present && key_ok;
+    const float* rope = p.rope_table && have ? p.rope_table + (size_t)token_position(tm, key_tok, p.L) * D : nullptr;
+    const int b_chain = (int)blockIdx.x - p.n_d0_items;
+    const int n_cpair = (tm.n_csub + 1) / 2;
+    const size_t prow = ((size_t)(p.rt_lo + b_chain / p.Hkv / n_cpair) * n_cpair + (b_chain / p.Hkv) % n_cpair) * 4 + wave;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {  // 0: dK, 1: dV
+      if (which == 0 && rope) {
+#pragma unroll
+        for (int db = 0; db < D / 64; ++db)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int d0 = db * 32 + 8 * q4 + 4 * g;
+            f32x4 lo, hi;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              lo[j] = dk[db][4 * q4 + j];
+              hi[j] = dk[db + D / 64][4 * q4 + j];
+            }
+            rope_turn4<true>(lo, hi, *reinterpret_cast<const f32x4*>(rope + d0),
+                             *reinterpret_cast<const f32x4*>(rope + D / 2 + d0));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              dk[db][4 * q4 + j] = lo[j];
+              dk[db + D / 64][4 * q4 + j] = hi[j];
+            }
+          }
+      }
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int d = db * 32 + 8 * (i / 4) + 4 * g + (i % 4);
+          const float x = which ? dv[db][i] : dk[db][i] * p.scale;
+          red[d * 33 + ln] = have ? x : 0.f;
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the wave's own LDS writes have landed
+      float* out = (which ? p.shared_dv_part : p.shared_dk_part) + (prow * p.Hkv + kvh) * D;
+#pragma unroll
+      for (int d = lane; d < D; d += 64) {
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) sum += red[d * 33 + j];
+        out[d] = sum;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // ... and its reads, before the buffer is written again
+    }
+    return;
   }
 
   // store from registers: lane <-> key, registers <-> d = db*32 + 8*q4 + 4g + j
@@ -1776,11 +1850,18 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
   const int nh = pick_nh(group, D, true);
   const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
   TimedSpan span(timer, kKindFwd, stream);
+  const bool sv = p.v_shared != nullptr;  // first-layer form: kernels that read chain V rows from the shared vector
   if (D == 64) {
-    if (nh == 2) hipLaunchKernelGGL((fwd_kernel<64, 2>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((fwd_kernel<64, 1>), grid, block, 0, stream, p);
+    if (nh == 2) {
+      if (sv) hipLaunchKernelGGL((fwd_kernel<64, 2, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((fwd_kernel<64, 2, false>), grid, block, 0, stream, p);
+    } else {
+      if (sv) hipLaunchKernelGGL((fwd_kernel<64, 1, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((fwd_kernel<64, 1, false>), grid, block, 0, stream, p);
+    }
   } else {
-    hipLaunchKernelGGL((fwd_kernel<128, 1>), grid, block, 0, stream, p);
+    if (sv) hipLaunchKernelGGL((fwd_kernel<128, 1, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((fwd_kernel<128, 1, false>), grid, block, 0, stream, p);
   }
   return span.finish();
 }
@@ -1792,11 +1873,17 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
   const int nh = pick_nh(group, D, false);
+  const bool sv = p.v_shared != nullptr;  // first-layer form (both or neither of v_shared / shared_dk_part are set)
   {
     const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
     TimedSpan span(timer, kKindDq, stream);
-    if (D == 64) hipLaunchKernelGGL((dq_pipe_kernel<64>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((dq_kernel<128, 1>), grid, block, 0, stream, p);
+    if (D == 64) {
+      if (sv) hipLaunchKernelGGL((dq_pipe_kernel<64, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((dq_pipe_kernel<64, false>), grid, block, 0, stream, p);
+    } else {
+      if (sv) hipLaunchKernelGGL((dq_kernel<128, 1, true>), grid, block, 0, stream, p);
+      else hipLaunchKernelGGL((dq_kernel<128, 1, false>), grid, block, 0, stream, p);
+    }
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
   }
@@ -1834,12 +1921,13 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
       const dim3 grid((unsigned)(p.n_d0_items + n_chain_items));
       TimedSpan span(timer, kKindDkDv, stream);
       const bool listed = p.tm.row_tok != nullptr;
+      auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, p); };
       if (D == 64) {
-        if (listed) hipLaunchKernelGGL((dkdv_kernel<64, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((dkdv_kernel<64, false>), grid, dim3(256), 0, stream, p);
+        if (listed) sv ? go(dkdv_kernel<64, true, true>) : go(dkdv_kernel<64, true, false>);
+        else sv ? go(dkdv_kernel<64, false, true>) : go(dkdv_kernel<64, false, false>);
       } else {
-        if (listed) hipLaunchKernelGGL((dkdv_kernel<128, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((dkdv_kernel<128, false>), grid, dim3(256), 0, stream, p);
+        if (listed) sv ? go(dkdv_kernel<128, true, true>) : go(dkdv_kernel<128, true, false>);
+        else sv ? go(dkdv_kernel<128, false, true>) : go(dkdv_kernel<128, false, false>);
       }
       hipError_t e = span.finish();
       if (e != hipSuccess) return e;

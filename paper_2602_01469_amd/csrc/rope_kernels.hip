@@ -105,64 +105,34 @@ __global__ __launch_bounds__(256) void expand_shared_kernel(const __bf16* x0, co
   }
 }
 
-// Gradients of the shared vectors: column sums of the chain tokens' rows [L0, T) of acc [T, cols] (fp32),
-// in two deterministic stages.  Stage 1: block b sums the tokens L0 + b, L0 + b + nblk, ... into
-// partial[b][cols]; stage 2 sums the partials, a thread per 16-byte column piece.  Stage 1 also copies the
-// depth-0 rows [0, L0) to their own output (all blocks).  gridDim.y selects dK or dV.
-__global__ __launch_bounds__(256) void shared_grad_stage1(const float* acc_k, const float* acc_v, float* partial,
-                                                          float* out0_k, float* out0_v, int T, int L0, int cols) {
+// Gradients of the shared vectors: column sums of acc [T][cols] (fp32; the per-wave sums of the chain keys' dK or
+// dV that the dK/dV kernel leaves - a few thousand rows).  A block of 256 threads is 16 row lanes x 16 column
+// pieces of 16 bytes: row lane r adds up rows r, r + 16, ... of its piece, eight loads in flight, and the 16 lanes
+// are then summed through LDS in a fixed order (deterministic).  gridDim.y selects dK or dV.
+__global__ __launch_bounds__(256) void shared_grad_reduce(const float* acc_k, const float* acc_v, float* out_k,
+                                                          float* out_v, int T, int cols) {
   __shared__ f32x4 red[256];
   const float* acc = blockIdx.y ? acc_v : acc_k;
-  float* out0 = blockIdx.y ? out0_v : out0_k;
-  const int nblk = gridDim.x, b = blockIdx.x, n4 = cols / 4;
-  // Threads are laid out as (token lane, 16-byte column piece): consecutive threads read consecutive pieces of
-  // one row, `lanes` rows at a time, four rows in flight per thread; the token lanes of a piece are then summed
-  // through LDS in a fixed order.
-  const int lanes = n4 <= 256 ? 256 / n4 : 1;
-  const int tl = n4 <= 256 ? threadIdx.x / n4 : 0;
-  for (int c0 = 0; c0 < n4; c0 += 256) {
-    const int c4 = c0 + (n4 <= 256 ? threadIdx.x % n4 : threadIdx.x);
-    const bool on = c4 < n4 && tl < lanes;
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    if (on) {
-      const size_t stride = (size_t)nblk * lanes;
-      size_t t = (size_t)L0 + b + (size_t)tl * nblk;
-      for (; t + 3 * stride < (size_t)T; t += 4 * stride) {
-        const f32x4 x0 = *reinterpret_cast<const f32x4*>(acc + t * cols + c4 * 4);
-        const f32x4 x1 = *reinterpret_cast<const f32x4*>(acc + (t + stride) * cols + c4 * 4);
-        const f32x4 x2 = *reinterpret_cast<const f32x4*>(acc + (t + 2 * stride) * cols + c4 * 4);
-        const f32x4 x3 = *reinterpret_cast<const f32x4*>(acc + (t + 3 * stride) * cols + c4 * 4);
-        sum += (x0 + x1) + (x2 + x3);
-      }
-      for (; t < (size_t)T; t += stride) sum += *reinterpret_cast<const f32x4*>(acc + t * cols + c4 * 4);
-      for (size_t t0 = (size_t)b + (size_t)tl * nblk; t0 < (size_t)L0; t0 += stride)
-        *reinterpret_cast<f32x4*>(out0 + t0 * cols + c4 * 4) = *reinterpret_cast<const f32x4*>(acc + t0 * cols + c4 * 4);
-    }
-    red[threadIdx.x] = sum;
-    __syncthreads();
-    if (on && tl == 0) {
-      for (int l = 1; l < lanes; ++l) sum += red[threadIdx.x + l * n4];
-      *reinterpret_cast<f32x4*>(partial + ((size_t)blockIdx.y * nblk + b) * cols + c4 * 4) = sum;
-    }
-    __syncthreads();
-  }
-}
-__global__ __launch_bounds__(256) void shared_grad_stage2(const float* partial, float* out_k, float* out_v, int nblk,
-                                                          int cols) {
   float* out = blockIdx.y ? out_v : out_k;
-  const int c4 = blockIdx.x * blockDim.x + threadIdx.x;  // one thread per 16-byte column piece
-  if (c4 >= cols / 4) return;
-  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
-  const float* src = partial + (size_t)blockIdx.y * nblk * cols + c4 * 4;
-  int b = 0;
-  for (; b + 3 < nblk; b += 4) {
-    s0 += *reinterpret_cast<const f32x4*>(src + (size_t)b * cols);
-    s1 += *reinterpret_cast<const f32x4*>(src + (size_t)(b + 1) * cols);
-    s2 += *reinterpret_cast<const f32x4*>(src + (size_t)(b + 2) * cols);
-    s3 += *reinterpret_cast<const f32x4*>(src + (size_t)(b + 3) * cols);
+  const int c4 = blockIdx.x * 16 + (threadIdx.x & 15), rl = threadIdx.x >> 4, n4 = cols / 4;
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  if (c4 < n4) {
+    const float* col = acc + c4 * 4;
+    int t = rl;
+    for (; t + 7 * 16 < T; t += 8 * 16) {
+      f32x4 x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const f32x4*>(col + (size_t)(t + 16 * u) * cols);
+      sum += ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+    }
+    for (; t < T; t += 16) sum += *reinterpret_cast<const f32x4*>(col + (size_t)t * cols);
   }
-  for (; b < nblk; ++b) s0 += *reinterpret_cast<const f32x4*>(src + (size_t)b * cols);
-  *reinterpret_cast<f32x4*>(out + c4 * 4) = (s0 + s1) + (s2 + s3);
+  red[threadIdx.x] = sum;
+  __syncthreads();
+  if (rl == 0 && c4 < n4) {
+    for (int l = 1; l < 16; ++l) sum += red[threadIdx.x + 16 * l];
+    *reinterpret_cast<f32x4*>(out + c4 * 4) = sum;
+  }
 }
 
 inline unsigned grid_for(size_t n) {
@@ -216,15 +186,10 @@ hipError_t launch_expand_shared(const void* x0, const void* x_shared, void* out,
   return hipGetLastError();
 }
 
-hipError_t launch_shared_grads(const float* acc_k, const float* acc_v, float* partial, int n_partial_blocks, float* dk0,
-                               float* dv0, float* dk_shared, float* dv_shared, int T, int L0, int cols,
-                               hipStream_t stream) {
-  hipLaunchKernelGGL(shared_grad_stage1, dim3((unsigned)n_partial_blocks, 2), dim3(256), 0, stream, acc_k, acc_v, partial,
-                     dk0, dv0, T, L0, cols);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(shared_grad_stage2, dim3((unsigned)((cols / 4 + 63) / 64), 2), dim3(64), 0, stream, partial,
-                     dk_shared, dv_shared, n_partial_blocks, cols);
+hipError_t launch_shared_grads(const float* part_k, const float* part_v, int rows, float* dk_shared, float* dv_shared,
+                               int cols, hipStream_t stream) {
+  hipLaunchKernelGGL(shared_grad_reduce, dim3((unsigned)((cols / 4 + 15) / 16), 2), dim3(256), 0, stream, part_k, part_v,
+                     dk_shared, dv_shared, rows, cols);
   return hipGetLastError();
 }
 
