@@ -111,6 +111,8 @@ def sweep(args) -> int:
     torch.cuda.set_device(0)
     K, Hq, Hkv, D, L_max = 8, 64, 8, 64, 20480
     bounds = list(range(0, L_max, 2048)) + [L_max]
+    torch.zeros(1, device="cuda")  # (the first HIP call of a process takes tens of milliseconds of its own)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     tm = pe.peagle_build_tilemap(L_max, K, bounds, device=0)
     build_ms = (time.perf_counter() - t0) * 1e3

@@ -316,8 +316,9 @@ int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, const peagle_s
  *                   one row of Hkv x D partial sums of dK and of dV per wave of the workgroups that own the
  *                   chain keys (a few MB)
  * The keys are expanded and rotated in one pass (each chain row reads the shared vector, not HBM rows
- * of its own).  The values are not expanded: the kernels read every chain key's value row from
- * v_shared.  No [T, Hkv, D] gradient tensor exists either: the depth-0 keys' dK / dV are written to
+ * of its own).  The values are not expanded at D = 64: the kernels read every chain key's value row
+ * from v_shared (at D = 128 the forward and dQ kernels have no registers for that and get an expanded V
+ * in the workspace).  No [T, Hkv, D] gradient tensor exists either: the depth-0 keys' dK / dV are written to
  * dk0 / dv0 directly, and the chain keys' dK (turned back to the unrotated frame key by key) and dV are
  * summed over each wave's 32 keys inside the dK/dV kernel, then over the waves by a two-stage
  * reduction in a fixed order.

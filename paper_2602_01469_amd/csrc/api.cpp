@@ -59,12 +59,13 @@ struct SharedForm {
   const void* v_shared = nullptr;  // [Hkv, D]: the value row of every chain key
   float* dk_part = nullptr;        // per-wave sums of the chain keys' dK / dV, see BwdParams
   float* dv_part = nullptr;
+  bool fwd_reads_v_tensor = false;  // `v` is a full [T, Hkv, D] tensor: the forward does not need v_shared
 };
 
 FwdParams make_fwd(const peagle_tilemap_t* tm, const peagle_shape_t* s, const SegRange& sr, const void* q,
                    const void* k, const void* v, void* o, float* lse, const SharedForm& sf = SharedForm()) {
   FwdParams p{};
-  p.v_shared = (const __bf16*)sf.v_shared;
+  p.v_shared = sf.fwd_reads_v_tensor ? nullptr : (const __bf16*)sf.v_shared;
   p.q = (const __bf16*)q;
   p.k = (const __bf16*)k;
   p.v = (const __bf16*)v;
@@ -310,10 +311,11 @@ extern "C" int peagle_attn_step_partitioned_rope(const peagle_tilemap_t* tm, con
 
 namespace {
 
-// Workspace of the first-layer form: the rotary workspace (rotated Q, expanded and rotated K) and the per-wave
-// sums of the chain keys' dK / dV (one row of Hkv x D per wave of every chain-tile workgroup).
+// Workspace of the first-layer form: the rotary workspace (rotated Q, expanded and rotated K), the per-wave sums
+// of the chain keys' dK / dV (one row of Hkv x D per wave of every chain-tile workgroup) and, at D = 128 only, an
+// expanded V (the forward and dQ kernels of that size do not read chain V rows from the shared vector).
 struct SharedWs {
-  size_t pk_off, pv_off, total;
+  size_t pk_off, pv_off, v_off, total;
   int32_t part_rows;
 };
 SharedWs shared_ws(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
@@ -322,7 +324,8 @@ SharedWs shared_ws(const peagle_tilemap_t* tm, const peagle_shape_t* s) {
   w.part_rows = tm->n_row_tiles * ((tm->n_csub + 1) / 2) * 4;
   w.pk_off = rope_ws(tm, s).total;
   w.pv_off = w.pk_off + align256((size_t)w.part_rows * cols * sizeof(float));
-  w.total = w.pv_off + align256((size_t)w.part_rows * cols * sizeof(float));
+  w.v_off = w.pv_off + align256((size_t)w.part_rows * cols * sizeof(float));
+  w.total = w.v_off + (s->D == 64 ? 0 : align256(tokens_of(tm, s) * cols * 2));
   return w;
 }
 
@@ -369,7 +372,17 @@ extern "C" int peagle_attn_step_rope_shared(const peagle_tilemap_t* tm, const pe
   sf.v_shared = v_shared;
   sf.dk_part = (float*)(ws + sw.pk_off);
   sf.dv_part = (float*)(ws + sw.pv_off);
-  rc = step_impl(tm, shape, 0, tm->S, q_rot, k_rot, v0, d_o, o, lse, dq, dk0, dv0, nullptr, nullptr, workspace,
+  const void* v_arg = v0;
+  if (shape->D != 64) {
+    // (this size's forward and dQ kernels read every V row from a tensor: expand V for them)
+    void* v_full = ws + sw.v_off;
+    if (peagle::launch_expand_shared(v0, v_shared, v_full, shape->Hkv, T, L0, shape->D, tm->dview, shape->L, nullptr,
+                                     st) != hipSuccess)
+      return PEAGLE_EHIP;
+    v_arg = v_full;
+    sf.fwd_reads_v_tensor = true;
+  }
+  rc = step_impl(tm, shape, 0, tm->S, q_rot, k_rot, v_arg, d_o, o, lse, dq, dk0, dv0, nullptr, nullptr, workspace,
                  ws_bytes, stream, nullptr, rope_table, n_pos, /*inputs_rotated=*/true, sf);
   if (rc != PEAGLE_OK) return rc;
   SegRange whole;

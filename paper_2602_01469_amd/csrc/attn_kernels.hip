@@ -1860,8 +1860,8 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
       else hipLaunchKernelGGL((fwd_kernel<64, 1, false>), grid, block, 0, stream, p);
     }
   } else {
-    if (sv) hipLaunchKernelGGL((fwd_kernel<128, 1, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((fwd_kernel<128, 1, false>), grid, block, 0, stream, p);
+    if (sv) return hipErrorInvalidValue;  // (D = 128 has no such instantiation: its callers expand V instead)
+    hipLaunchKernelGGL((fwd_kernel<128, 1, false>), grid, block, 0, stream, p);
   }
   return span.finish();
 }
@@ -1873,7 +1873,10 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
   const int nh = pick_nh(group, D, false);
-  const bool sv = p.v_shared != nullptr;  // first-layer form (both or neither of v_shared / shared_dk_part are set)
+  // First-layer form.  The dQ kernel reads chain V rows from the shared vector at D = 64 only: at D = 128 it has
+  // no registers to spare (that instantiation spilled three times as much and ran 25 % slower), so there the
+  // caller passes an expanded V in `v` for it; the dK/dV kernel takes the shared vector at either size.
+  const bool sv = p.v_shared != nullptr && D == 64, sv_dkdv = p.shared_dk_part != nullptr;
   {
     const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
     TimedSpan span(timer, kKindDq, stream);
@@ -1881,8 +1884,7 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
       if (sv) hipLaunchKernelGGL((dq_pipe_kernel<64, true>), grid, block, 0, stream, p);
       else hipLaunchKernelGGL((dq_pipe_kernel<64, false>), grid, block, 0, stream, p);
     } else {
-      if (sv) hipLaunchKernelGGL((dq_kernel<128, 1, true>), grid, block, 0, stream, p);
-      else hipLaunchKernelGGL((dq_kernel<128, 1, false>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((dq_kernel<128, 1, false>), grid, block, 0, stream, p);
     }
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
@@ -1923,11 +1925,11 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
       const bool listed = p.tm.row_tok != nullptr;
       auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, p); };
       if (D == 64) {
-        if (listed) sv ? go(dkdv_kernel<64, true, true>) : go(dkdv_kernel<64, true, false>);
-        else sv ? go(dkdv_kernel<64, false, true>) : go(dkdv_kernel<64, false, false>);
+        if (listed) sv_dkdv ? go(dkdv_kernel<64, true, true>) : go(dkdv_kernel<64, true, false>);
+        else sv_dkdv ? go(dkdv_kernel<64, false, true>) : go(dkdv_kernel<64, false, false>);
       } else {
-        if (listed) sv ? go(dkdv_kernel<128, true, true>) : go(dkdv_kernel<128, true, false>);
-        else sv ? go(dkdv_kernel<128, false, true>) : go(dkdv_kernel<128, false, false>);
+        if (listed) sv_dkdv ? go(dkdv_kernel<128, true, true>) : go(dkdv_kernel<128, true, false>);
+        else sv_dkdv ? go(dkdv_kernel<128, false, true>) : go(dkdv_kernel<128, false, false>);
       }
       hipError_t e = span.finish();
       if (e != hipSuccess) return e;

@@ -625,5 +625,5 @@ def test_rope_shared_entry_point_validates_before_launch():
     assert call() == -8
     need = pe.peagle_rope_shared_workspace_bytes(tm, ok)
     # beside the rotary workspace: one fp32 row of Hkv x D per wave (4) of each of the 16 row tiles' chain-tile
-    # workgroups, for dK and for dV - and no [T, Hkv, D] tensor of any kind
+    # workgroups, for dK and for dV - and no [T, Hkv, D] tensor of any kind (D = 64)
     assert need == pe.peagle_rope_workspace_bytes(tm, ok) + 2 * (16 * 4) * (2 * 64) * 4
