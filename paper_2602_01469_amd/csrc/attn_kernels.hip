@@ -1209,15 +1209,34 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
   const bool fast_rows = !LISTED && tm.A * tm.K == kRowsPerTile && p.fast_rows;
   constexpr int kRowsApart = 4 * (512 / D);  // between the rows a lane copies
   const size_t fast_step = kRowsApart % tm.A == 0 ? (size_t)(kRowsApart / tm.A) * p.L * p.Hq * D : 0;
+  // Everything but the one per-lane offset is computed on the scalar unit from values forced wave-uniform (the
+  // compiler otherwise carries the row tile and head in vector registers and builds each copy's 64-bit
+  // address there): LDS addresses are plain integers from the buffer's base, the source pointers scalar
+  // multiplies and adds, and the choice between the two forms is made once, not per copy.
+  const uint32_t lds_addr0 = lds_scalar_addr(lds);
+  const uint32_t wave_s = (uint32_t)__builtin_amdgcn_readfirstlane(wave);
+  constexpr int kPer = RowDmaLane<D, 4>::kPer;
   auto issue_fast = [&](int hh, int rt, int buf) {
-    char* base = lds + buf * kBufBytes;
-    const size_t row0 = ((size_t)rt * tm.A * p.Hq + hh) * D;
-    dma_row_tile_fast<D, 4>(base, p.q + row0, rl, wave, fast_step);
-    dma_row_tile_fast<D, 4>(base + kTileBytes, p.d_o + row0, rl, wave, fast_step);
-    float* stat = reinterpret_cast<float*>(base + 2 * kTileBytes);
-    const size_t s0 = (size_t)hh * p.T + (size_t)rt * tm.A;
-    if (wave < 2) dma_row_stat_fast<D, 4>(stat, p.nlse + s0, rl, wave & 1);
-    else if (wave < 4) dma_row_stat_fast<D, 4>(stat + kRowsPerTile, p.delta + s0, rl, wave & 1);
+    const int hh_s = __builtin_amdgcn_readfirstlane(hh), rt_s = __builtin_amdgcn_readfirstlane(rt);
+    const uint32_t dst = lds_addr0 + (uint32_t)buf * kBufBytes + wave_s * 1024;
+    const size_t row0 = ((size_t)rt_s * tm.A * p.Hq + hh_s) * D;
+    const __bf16* qs = p.q + row0;
+    const __bf16* ds = p.d_o + row0;
+    if (fast_step) {
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) dma16_untracked(qs + i * fast_step, rl.fast_off[0], dst + i * 4 * 1024);
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) dma16_untracked(ds + i * fast_step, rl.fast_off[0], dst + kTileBytes + i * 4 * 1024);
+    } else {
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) dma16_untracked(qs, rl.fast_off[i], dst + i * 4 * 1024);
+#pragma unroll
+      for (int i = 0; i < kPer; ++i) dma16_untracked(ds, rl.fast_off[i], dst + kTileBytes + i * 4 * 1024);
+    }
+    const float* stat0 = (wave_s < 2 ? p.nlse : p.delta) + (size_t)hh_s * p.T + (size_t)rt_s * tm.A;
+    dma4_untracked(stat0, rl.fast_stat_off,
+                   lds_addr0 + (uint32_t)buf * kBufBytes + 2 * kTileBytes + (wave_s < 2 ? 0 : kRowsPerTile * 4) +
+                       (wave_s & 1) * 64 * 4);
   };
   auto issue = [&](int hh, const Toks& t, int buf) {
     char* base = lds + buf * kBufBytes;
