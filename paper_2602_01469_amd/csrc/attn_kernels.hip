@@ -80,17 +80,30 @@ __device__ __forceinline__ TileEntry take_entry(u32x2 w) {
 }
 __device__ __forceinline__ TileEntry load_entry(const TileEntry* list, int e) { return take_entry(fetch_entry(list, e)); }
 
+// LDS addresses of the K/V tile buffers of the row-stationary kernels, [slot][K|V][tile bytes], as plain scalar
+// integers: the address of slot 0 is taken once per kernel and everything else is integer arithmetic (taken
+// per copy from a pointer, each address costs a null check and two moves to the scalar unit).
+template <int D>
+struct KeyTileLds {
+  uint32_t base;  // address of slot 0's K image + 1024 * wave
+  __device__ __forceinline__ KeyTileLds(const char* slot0, int wave)
+      : base(lds_scalar_addr(slot0 + wave * 1024)) {}
+  __device__ __forceinline__ uint32_t k(int slot) const { return base + (uint32_t)slot * (2u * kKeysPerTile * D * 2); }
+  __device__ __forceinline__ uint32_t v(int slot) const { return k(slot) + kKeysPerTile * D * 2; }
+};
+
 // Key tile straight into its swizzled LDS image (K and V): wave w of NW fills the 1 KiB blocks
 // w, w + NW, ...; lane l of block b owns LDS bytes [1024 b + 16 l, +16), i.e. tile row
 // b*(512/D) + l/(D/8) and physical chunk l%(D/8), and fetches the logical chunk that lives there.
 template <int D, int NW, bool SV = false>
-__device__ __forceinline__ void dma_key_tile(char* k_lds, char* v_lds, const __bf16* kbase, const __bf16* vbase,
+__device__ __forceinline__ void dma_key_tile(uint32_t kd, uint32_t vd, const __bf16* kbase, const __bf16* vbase,
                                              int Hkv, int kvh, const DeviceTileMap& tm, int kt, int L, int wave,
                                              int lane, const __bf16* v_shared = nullptr) {
+  // kd, vd: LDS byte addresses of this wave's first block of the K and of the V image (tile address + 1024 *
+  // wave), as wave-uniform integers - see KeyTileLds
   constexpr int kBlocks = kKeysPerTile * D * 2 / 1024;
   static_assert(kBlocks % NW == 0, "tile must split evenly over the waves");
   const int row_in_blk = lane / (D / 8), phys = lane % (D / 8);
-  const uint32_t kd = lds_scalar_addr(k_lds + wave * 1024), vd = lds_scalar_addr(v_lds + wave * 1024);
   if (kt < tm.n_d0 && (kt + 1) * kKeysPerTile <= L) {
     // A whole tile of depth-0 keys: the rows a lane copies are NW * 512/D apart (a multiple of the swizzle
     // period), so its byte offset from each copy's first row is one value, the same for every tile, and the
@@ -349,6 +362,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];  // [buffer][K|V]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const KeyTileLds<D> kl(&lds[0][0][0], wave);
   const DeviceTileMap& tm = p.tm;
   const int group = p.Hq / p.Hkv;
   const int hpg = group / NH;
@@ -393,7 +407,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
     }
     TileEntry cur = load_entry(tm.row_entries, e0);
     TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
-    dma_key_tile<D, 4, SV>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
+    dma_key_tile<D, 4, SV>(kl.k(0), kl.v(0), p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
     dma_publish();
     // The leading full tiles run in a counted loop of their own (no mask branch, accumulators
     // stay in place); the partial tiles that end a row tile's list take the general loop.
@@ -402,7 +416,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
       const int buf = (e - e0) & 1;
       const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
-        dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
+        dma_key_tile<D, 4, SV>(kl.k(buf ^ 1), kl.v(buf ^ 1), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
       dma_publish();
@@ -413,7 +427,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
       const int buf = (e - e0) & 1;
       const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
-        dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
+        dma_key_tile<D, 4, SV>(kl.k(buf ^ 1), kl.v(buf ^ 1), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
       if (cur.mask_id < 0) {
         const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
         fwd_tile<D, NH, false, SAFE>(lds[buf][0], lds[buf][1], no, to, qf, o, m, lsum, mw, p.c_log2);
@@ -566,7 +580,10 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   const int e_lead = e0 + tm.row_lead[rt];  // end of the leading run of full tiles
   TileEntry cur = load_entry(tm.row_entries, e0);
   TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
-  dma_key_tile<D, 4, SV>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
+  // (LDS addresses taken per copy from the buffers' pointers here, not through KeyTileLds: this kernel runs at
+  // D = 128 only, at the register limit, and with the integer form the allocator spilled 96 registers instead
+  // of 37 and the kernel ran 7 % slower)
+  dma_key_tile<D, 4, SV>(lds_scalar_addr(lds[0][0] + wave * 1024), lds_scalar_addr(lds[0][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
   dma_publish();
 
   int e = e0;
@@ -574,7 +591,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     const int buf = (e - e0) & 1;
     const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
+      dma_key_tile<D, 4, SV>(lds_scalar_addr(lds[buf ^ 1][0] + wave * 1024), lds_scalar_addr(lds[buf ^ 1][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
     const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
     dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     dma_publish();
@@ -585,7 +602,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     const int buf = (e - e0) & 1;
     const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4, SV>(lds[buf ^ 1][0], lds[buf ^ 1][1], p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
+      dma_key_tile<D, 4, SV>(lds_scalar_addr(lds[buf ^ 1][0] + wave * 1024), lds_scalar_addr(lds[buf ^ 1][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
     if (cur.mask_id < 0) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
@@ -758,6 +775,7 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(16))) char lds[3][2][kTileBytes];  // [buffer][K|V]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, ln = lane & 31;
+  const KeyTileLds<D> kl(&lds[0][0][0], wave);
   const DeviceTileMap& tm = p.tm;
   const int group = p.Hq / p.Hkv;
   int b = blockIdx.x;
@@ -814,8 +832,8 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
   TileEntry t_n2 = load_entry(tm.row_entries, entry_at(e0 + 2));
 
   // the first two tiles are on their way before anything else
-  dma_key_tile<D, 4, SV>(lds[0][0], lds[0][1], p.k, p.v, p.Hkv, kvh, tm, t_cur.tile, p.L, wave, lane, p.v_shared);
-  if (e0 + 1 < e1) dma_key_tile<D, 4, SV>(lds[1][0], lds[1][1], p.k, p.v, p.Hkv, kvh, tm, t_n1.tile, p.L, wave, lane, p.v_shared);
+  dma_key_tile<D, 4, SV>(kl.k(0), kl.v(0), p.k, p.v, p.Hkv, kvh, tm, t_cur.tile, p.L, wave, lane, p.v_shared);
+  if (e0 + 1 < e1) dma_key_tile<D, 4, SV>(kl.k(1), kl.v(1), p.k, p.v, p.Hkv, kvh, tm, t_n1.tile, p.L, wave, lane, p.v_shared);
 
   // unnormalised probabilities for the whole workgroup, or normalised ones for the whole workgroup
   const bool in_range = __builtin_fabsf(lse2) <= kLseRange;  // (false for NaN)
@@ -858,7 +876,7 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
       // Every wave has left tile e-1 (its last reader was the body above) and has waited for its own copies of
       // tile e+1: after the barrier that buffer may be overwritten and tile e+1 may be read.
       dma_publish();
-      if (e + 2 < e1) dma_key_tile<D, 4, SV>(lds[BP][0], lds[BP][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane, p.v_shared);
+      if (e + 2 < e1) dma_key_tile<D, 4, SV>(kl.k(BP), kl.v(BP), p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane, p.v_shared);
       dq_pipe_body<D, 1, LAST>(P, lds[B][0], lds[BN][0], lds[BN][1], lds[B][0], no, to, qf, dof, dq, ndelta16, c);
       t_cur = t_n1;
       t_n1 = t_n2;
@@ -892,7 +910,7 @@ __global__ __launch_bounds__(256, 2) void dq_pipe_kernel(BwdParams p) {
   for (; e < e1; ++e) {
     const u32x2 ahead = fetch_entry(tm.row_entries, entry_at(e + 3));
     const int buf2 = buf == 0 ? 2 : buf - 1;
-    if (e + 2 < e1) dma_key_tile<D, 4, SV>(lds[buf2][0], lds[buf2][1], p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane, p.v_shared);
+    if (e + 2 < e1) dma_key_tile<D, 4, SV>(kl.k(buf2), kl.v(buf2), p.k, p.v, p.Hkv, kvh, tm, t_n2.tile, p.L, wave, lane, p.v_shared);
     const char* kt_lds = lds[0][0] + buf * (2 * kTileBytes);
     const char* vt_lds = kt_lds + kTileBytes;
     if (t_cur.mask_id < 0) {
