@@ -412,8 +412,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
     // The leading full tiles run in a counted loop of their own (no mask branch, accumulators
     // stay in place); the partial tiles that end a row tile's list take the general loop.
     int e = e0;
-    for (; e < e_lead; ++e) {
-      const int buf = (e - e0) & 1;
+    auto full_tile = [&](int buf) {
       const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
       if (e + 1 < e1)
         dma_key_tile<D, 4, SV>(kl.k(buf ^ 1), kl.v(buf ^ 1), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
@@ -422,7 +421,15 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdParams p) {
       dma_publish();
       cur = nxt;
       nxt = take_entry(ahead);
+      ++e;
+    };
+    // (two at a time with the buffer index a constant: every LDS address is then a per-lane register plus an
+    // immediate, which saves the eight vector additions per tile that a buffer index in a register costs)
+    while (e + 1 < e_lead) {
+      full_tile(0);
+      full_tile(1);
     }
+    if (e < e_lead) full_tile(0);
     for (; e < e1; ++e) {
       const int buf = (e - e0) & 1;
       const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
