@@ -24,6 +24,10 @@ def build(verbose: bool = False, sanitize_host_to: str = "") -> str:
     cmd = [
         HIPCC, "-x", "hip", "--offload-arch=gfx950", *opt, "-std=c++17", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        # Matrix instructions write ordinary vector registers in every kernel.  Kernels with one wave per SIMD (the
+        # D=128 dK/dV kernel) would otherwise get all their accumulators in the accumulation registers and copy
+        # every score out before the vector unit can touch it (that kernel: -7 %); the others are unaffected.
+        "-mllvm", "-amdgpu-mfma-vgpr-form",
         "-fgpu-flush-denormals-to-zero", "-Wno-unused-command-line-argument",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
         "-o", out_path,
