@@ -91,6 +91,14 @@ SMALL = [
     ("group_of_12", 150, 8, 12, 1, 64, 240, [0, 64, 150], None),
     ("seven_mha_heads", 90, 4, 7, 7, 64, 250, None, None),
     ("odd_group_d128", 70, 8, 9, 3, 128, 260, None, None),
+    # deep chains up to the largest supported K (one anchor per row tile), and depths that do not divide 128
+    ("k32", 20, 32, 2, 1, 64, 270, None, None),
+    ("k64_segments", 9, 64, 2, 2, 64, 280, [0, 4, 9], None),
+    ("k128_largest_depth", 5, 128, 2, 1, 64, 290, [0, 2, 5], None),
+    ("k128_d128", 3, 128, 1, 1, 128, 293, None, None),
+    ("k5_segments", 60, 5, 4, 2, 64, 291, [0, 25, 60], None),
+    ("k7_d128", 40, 7, 2, 1, 128, 292, None, None),
+    ("k2", 200, 2, 2, 1, 64, 294, [0, 64, 200], None),
 ]
 
 

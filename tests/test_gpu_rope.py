@@ -92,6 +92,8 @@ ROPE_CASES = [
     ("several_tiles_group_of_6", 700, 4, 6, 1, 64, 840, [0, 256, 512, 700], None),
     ("k1", 300, 1, 2, 2, 64, 850, None, None),
     ("odd_group_d128", 70, 8, 9, 3, 128, 860, None, None),
+    ("k32_positions_far_past_the_anchors", 20, 32, 2, 1, 64, 870, None, None),
+    ("k5_segments", 60, 5, 4, 2, 64, 880, [0, 25, 60], None),
 ]
 
 
@@ -301,6 +303,9 @@ SHARED_CASES = [
     ("dense_k1_no_chain", (300,), 1, 2, 2, 64, None, 3020, None, True),
     ("sampled", (300,), 8, 4, 2, 64, 0.7, 3030, [0, 100, 300], False),
     ("packed", (100, 37, 64, 1, 90), 8, 4, 1, 64, 0.8, 3040, None, False),
+    ("dense_k2_one_chain_tile", (200,), 2, 4, 2, 64, None, 3050, [0, 64, 200], True),
+    ("dense_k5", (120,), 5, 2, 1, 64, None, 3060, [0, 50, 120], True),
+    ("dense_k32", (20,), 32, 2, 1, 64, None, 3070, None, True),
 ]
 
 
