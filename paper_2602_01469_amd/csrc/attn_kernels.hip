@@ -234,26 +234,6 @@ __device__ __forceinline__ void dma_row_stat(float* lds_stat, const float* base,
                  lds_scalar_addr(reinterpret_cast<const char*>(lds_stat + half * 64)));
 }
 
-// The same two copies for a row tile of a dense map whose 128 rows all exist (see RowDmaLane::fast_off):
-// `row0` = the head's row of the tile's first anchor at depth 0 (wave-uniform).
-// `step` != 0: the rows a lane copies are NW * 512/D apart, a whole number of depths (A divides that), so copy i
-// reads `step` elements behind copy i-1 for every lane: the step goes into the scalar base and one per-lane
-// offset serves all copies.
-template <int D, int NW>
-__device__ __forceinline__ void dma_row_tile_fast(char* lds_tile, const __bf16* row0, const RowDmaLane<D, NW>& rl, int wave,
-                                                  size_t step) {
-  const uint32_t dst = lds_scalar_addr(lds_tile + wave * 1024);
-#pragma unroll
-  for (int i = 0; i < RowDmaLane<D, NW>::kPer; ++i) {
-    if (step) dma16_untracked(uniform_ptr(row0 + i * step), rl.fast_off[0], dst + i * NW * 1024);
-    else dma16_untracked(uniform_ptr(row0), rl.fast_off[i], dst + i * NW * 1024);
-  }
-}
-template <int D, int NW>
-__device__ __forceinline__ void dma_row_stat_fast(float* lds_stat, const float* stat0, const RowDmaLane<D, NW>& rl, int half) {
-  dma4_untracked(uniform_ptr(stat0), rl.fast_stat_off, lds_scalar_addr(reinterpret_cast<const char*>(lds_stat + half * 64)));
-}
-
 // Does any row of the wave see a key of the 32-key block whose (shifted) mask word each lane holds?
 __device__ __forceinline__ bool wave_sees_block(uint32_t mw) {
   return __builtin_amdgcn_ballot_w64((mw & kLaneKeyBits) != 0) != 0;
@@ -312,12 +292,12 @@ __device__ __forceinline__ void softmax_block(f32x16& s, uint32_t mw, float c, f
 // (row tile, NH query heads of one KV group); wave w owns rows [32w, 32w+32) of the tile.
 // K/V tiles are staged once in LDS per workgroup and serve all NH heads.
 // =====================================================================================
-template <int D, int NH, bool MASKED, bool SAFE, int KB0 = 0, int KB1 = 2>
+template <int D, int NH, bool MASKED, bool SAFE>
 __device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds, const NatOff<D>& no, const TrOff<D>& to,
                                          const bf16x8 (&qf)[NH][D / 16], f32x16 (&o)[NH][D / 32], float (&m)[NH],
                                          float (&lsum)[NH], const uint32_t (&mw)[2], float c) {
 #pragma unroll
-  for (int kb = KB0; kb < KB1; ++kb) {  // the tile's 32-key blocks [KB0, KB1)
+  for (int kb = 0; kb < 2; ++kb) {  // the tile's two 32-key blocks
     // S^T block: 32 keys x 32 rows, lane <-> row, registers <-> keys 8*(i/4) + 4g + i%4
     f32x16 s[NH];
 #pragma unroll
@@ -531,8 +511,11 @@ __device__ __forceinline__ void dq_tile(const char* kt_lds, const char* vt_lds, 
   }
 }
 
-template <int D, int NH, bool SV>
-__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
+// (This plain form serves D = 128, one query head per workgroup; D = 64 runs dq_pipe_kernel below.  NH stays a
+// named constant because dq_tile is written for NH heads sharing the K / V fragments.)
+template <int D>
+__global__ __launch_bounds__(256, 2) void dq_kernel(BwdParams p) {
+  constexpr int NH = 1;
   constexpr int kTileBytes = kKeysPerTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
 
@@ -587,10 +570,10 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
   const int e_lead = e0 + tm.row_lead[rt];  // end of the leading run of full tiles
   TileEntry cur = load_entry(tm.row_entries, e0);
   TileEntry nxt = load_entry(tm.row_entries, e0 + 1 < e1 ? e0 + 1 : e0);
-  // (LDS addresses taken per copy from the buffers' pointers here, not through KeyTileLds: this kernel runs at
-  // D = 128 only, at the register limit, and with the integer form the allocator spilled 96 registers instead
+  // (LDS addresses taken per copy from the buffers' pointers here, not through KeyTileLds: this kernel is at
+  // the register limit, and with the integer form the allocator spilled 96 registers instead
   // of 37 and the kernel ran 7 % slower)
-  dma_key_tile<D, 4, SV>(lds_scalar_addr(lds[0][0] + wave * 1024), lds_scalar_addr(lds[0][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane, p.v_shared);
+  dma_key_tile<D, 4>(lds_scalar_addr(lds[0][0] + wave * 1024), lds_scalar_addr(lds[0][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, cur.tile, p.L, wave, lane);
   dma_publish();
 
   int e = e0;
@@ -598,7 +581,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     const int buf = (e - e0) & 1;
     const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4, SV>(lds_scalar_addr(lds[buf ^ 1][0] + wave * 1024), lds_scalar_addr(lds[buf ^ 1][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
+      dma_key_tile<D, 4>(lds_scalar_addr(lds[buf ^ 1][0] + wave * 1024), lds_scalar_addr(lds[buf ^ 1][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
     const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
     dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
     dma_publish();
@@ -609,7 +592,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void dq_kernel(BwdParams p) {
     const int buf = (e - e0) & 1;
     const u32x2 ahead = fetch_entry(tm.row_entries, e + 2 < e1 ? e + 2 : e);
     if (e + 1 < e1)
-      dma_key_tile<D, 4, SV>(lds_scalar_addr(lds[buf ^ 1][0] + wave * 1024), lds_scalar_addr(lds[buf ^ 1][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane, p.v_shared);
+      dma_key_tile<D, 4>(lds_scalar_addr(lds[buf ^ 1][0] + wave * 1024), lds_scalar_addr(lds[buf ^ 1][1] + wave * 1024), p.k, p.v, p.Hkv, kvh, tm, nxt.tile, p.L, wave, lane);
     if (cur.mask_id < 0) {
       const uint32_t mw[2] = {0xffffffffu, 0xffffffffu};
       dq_tile<D, NH, false>(lds[buf][0], lds[buf][1], no, to, qf, dof, dq, lse2, delta, mw, p.c_log2);
@@ -1232,7 +1215,10 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void dkdv_kernel(BwdParams p)
   // dense map whose row tiles hold 128 real rows, tensors within reach of a 32-bit offset: copies of whole row
   // tiles take the short form
   const bool fast_rows = !LISTED && tm.A * tm.K == kRowsPerTile && p.fast_rows;
-  constexpr int kRowsApart = 4 * (512 / D);  // between the rows a lane copies
+  // The rows a lane copies are kRowsApart apart; when that is a whole number of depths (A divides it), copy i
+  // reads fast_step elements behind copy i-1 for every lane: the step goes into the scalar base and one per-lane
+  // offset serves all copies.  Otherwise (fast_step = 0) each copy has its own per-lane offset.
+  constexpr int kRowsApart = 4 * (512 / D);
   const size_t fast_step = kRowsApart % tm.A == 0 ? (size_t)(kRowsApart / tm.A) * p.L * p.Hq * D : 0;
   // Everything but the one per-lane offset is computed on the scalar unit from values forced wave-uniform (the
   // compiler otherwise carries the row tile and head in vector registers and builds each copy's 64-bit
@@ -1829,9 +1815,9 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* out, int iters
 
 namespace {
 
-// Query heads of one KV group that share a workgroup's K/V tiles: two in the D = 64 forward
-// (the register budget of two waves per SIMD allows it), one everywhere else.
-inline int pick_nh(int group, int D, bool forward) { return (forward && D == 64 && group % 2 == 0) ? 2 : 1; }
+// Query heads of one KV group that share a workgroup's K/V tiles in the forward: two at D = 64 (the register
+// budget of two waves per SIMD allows it), one at D = 128.  The backward kernels take one head per workgroup.
+inline int pick_nh(int group, int D) { return (D == 64 && group % 2 == 0) ? 2 : 1; }
 
 struct TimedSpan {
   KernelTimer* t;
@@ -1891,7 +1877,7 @@ hipError_t launch_fwd(const FwdParams& p, int D, hipStream_t stream, KernelTimer
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
   const int group = p.Hq / p.Hkv;
-  const int nh = pick_nh(group, D, true);
+  const int nh = pick_nh(group, D);
   const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
   TimedSpan span(timer, kKindFwd, stream);
   const bool sv = p.v_shared != nullptr;  // first-layer form: kernels that read chain V rows from the shared vector
@@ -1915,20 +1901,18 @@ hipError_t launch_bwd(const BwdParams& pin, int D, int key_lo, int a_hi, int acc
   BwdParams p = pin;
   const int n_rt = p.rt_hi - p.rt_lo;
   if (n_rt <= 0) return hipSuccess;
-  const int group = p.Hq / p.Hkv;
-  const int nh = pick_nh(group, D, false);
   // First-layer form.  The dQ kernel reads chain V rows from the shared vector at D = 64 only: at D = 128 it has
   // no registers to spare (that instantiation spilled three times as much and ran 25 % slower), so there the
   // caller passes an expanded V in `v` for it; the dK/dV kernel takes the shared vector at either size.
   const bool sv = p.v_shared != nullptr && D == 64, sv_dkdv = p.shared_dk_part != nullptr;
   {
-    const dim3 grid((unsigned)(n_rt * (p.Hq / nh))), block(256);
+    const dim3 grid((unsigned)(n_rt * p.Hq)), block(256);  // one query head per workgroup
     TimedSpan span(timer, kKindDq, stream);
     if (D == 64) {
       if (sv) hipLaunchKernelGGL((dq_pipe_kernel<64, true>), grid, block, 0, stream, p);
       else hipLaunchKernelGGL((dq_pipe_kernel<64, false>), grid, block, 0, stream, p);
     } else {
-      hipLaunchKernelGGL((dq_kernel<128, 1, false>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((dq_kernel<128>), grid, block, 0, stream, p);
     }
     hipError_t e = span.finish();
     if (e != hipSuccess) return e;
