@@ -64,7 +64,14 @@ def _check_against_oracle(got, ref, what="", lse_abs=LSE_ABS, o_abs_extra=0.0):
     _check_o_abs(got["O"], ref["O"], what, o_abs_extra)
     assert max_abs(got["LSE"], ref["LSE"]) <= lse_abs, what
     for n in ("dQ", "dK", "dV"):
-        assert rel_l2(got[n], ref[n]) <= GRAD_REL, (what, n)
+        assert _grad_rel(got[n], ref[n]) <= GRAD_REL, (what, n)
+
+
+def _grad_rel(got, ref):
+    """rel-L2 of a gradient, the reference norm floored at an rms of 1e-3 (unit-variance inputs give gradients
+    with an rms of 0.1 to 1): a problem whose rows all see a single key (one anchor, K = 1) has dQ = 0 exactly,
+    where the kernel's dP - Delta leaves rounding noise of 1e-7 and a plain ratio is meaningless."""
+    return float(np.linalg.norm((got - ref).ravel()) / max(np.linalg.norm(ref.ravel()), 1e-3 * np.sqrt(ref.size)))
 
 
 def _oracle(qb, kb, vb, dob, L, K, scale):
@@ -655,11 +662,13 @@ def test_rebuilding_a_sampled_map_in_place_between_steps():
 
 def test_random_small_problems_match_oracle():
     """Seeded sweep over batches, depths, head shapes, retention rates, segmentations and assignments:
-    the partitioned step on the general tile map against the oracle, every output."""
+    the partitioned step on the general tile map against the oracle, every output.  PEAGLE_SWEEP_CASES widens
+    the sweep for a one-off run."""
     from gpu_harness import SampledRun
     from peagle_inputs import cod_depth_counts
+    import os
     rng = np.random.default_rng(77)
-    for case in range(10):
+    for case in range(int(os.environ.get("PEAGLE_SWEEP_CASES", "10"))):
         K = int(rng.choice([1, 2, 4, 5, 8, 16]))
         n_seq = int(rng.integers(1, 4))
         seq_lens = tuple(int(x) for x in rng.integers(1, 120, size=n_seq))
@@ -690,6 +699,46 @@ def test_random_small_problems_match_oracle():
         got = run.results()
         q, k, v, do = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
         _check_against_oracle(got, orc.attn_backward(q, k, v, do, L, K, run.shape.scale, tokens=tok), what)
+
+
+def test_random_dense_problems_match_oracle():
+    """Seeded sweep over dense maps: depths from 1 to the largest supported (128, one anchor per row tile) and depths
+    that do not divide 128, lengths cropped below the map's, random segment cuts (multiples of the anchors per row
+    tile), head shapes and both head sizes; the separate forward / backward calls or the partitioned step, every
+    output against the oracle.  PEAGLE_SWEEP_CASES widens the sweep for a one-off run (about once per 1e8 output
+    elements such a run meets a row of one or two keys whose O error reaches 1.02e-2: the bf16 rounding of P
+    against values of opposite sign, not a defect)."""
+    import os
+    rng = np.random.default_rng(4242)
+    n_cases = int(os.environ.get("PEAGLE_SWEEP_CASES", "14"))
+    for case in range(n_cases):
+        K = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 8, 8, 12, 16, 20, 32, 64, 128]))
+        A = 128 // K
+        L_max = int(rng.integers(1, max(2, min(420, 2400 // K))))
+        S = int(rng.integers(1, 5))
+        inner = sorted({int(c) * A for c in rng.integers(1, max(2, -(-L_max // A)), size=S - 1)} - {0})
+        inner = [c for c in inner if c < L_max]
+        bounds = [0] + inner + [L_max] if inner else None
+        L = L_max if rng.random() < 0.5 else int(rng.integers(1, L_max + 1))
+        D = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        Hq = Hkv * int(rng.choice([1, 2, 3, 4]))
+        whole_step = bool(rng.random() < 0.6)
+        what = (f"dense case {case}: L={L} of L_max={L_max} K={K} Hq={Hq} Hkv={Hkv} D={D} bounds={bounds} "
+                f"{'step' if whole_step else 'fwd+bwd'}")
+        print(what, flush=True)
+        T = L * K
+        seed = 5000 + 10 * case
+        qb, kb, vb, dob = (rand_bits((T, Hq, D), seed), rand_bits((T, Hkv, D), seed + 1),
+                           rand_bits((T, Hkv, D), seed + 2), rand_bits((T, Hq, D), seed + 3))
+        tm = pe.peagle_build_tilemap(L_max, K, bounds, device=0)
+        r = Run(tm, L, K, Hq, Hkv, D, qb, kb, vb, dob)
+        if whole_step:
+            r.step(0, 1 if bounds is None else len(bounds) - 1)
+        else:
+            r.fwd()
+            r.bwd()
+        _check_against_oracle(r.results(), _oracle(qb, kb, vb, dob, L, K, r.shape.scale), what)
 
 
 def test_partitioned_step_replays_from_a_hip_graph():
